@@ -1,0 +1,159 @@
+/*
+ * dpclip.h - C ABI of the MI355X (gfx950) DP-SGD hot path: per-example squared gradient norms,
+ * clip-weighted gradient sums accumulated over micro-batches, and the Gaussian-noise + Adam update
+ * with decoupled weight decay ("Large-Scale Differentially Private BERT", Algorithm 1).
+ *
+ * One training step, in the notation of Algorithm 1 (g_t line through theta_t line):
+ *
+ *     g_t     = ( N(0, sigma^2 C^2 I) + sum_{x_j in B_t} clip(grad L(theta; x_j), C) ) / |B_t|
+ *     m_t     = beta1 m_{t-1} + (1 - beta1) g_t          v_t = beta2 v_{t-1} + (1 - beta2) g_t^2
+ *     mhat_t  = m_t / (1 - beta1^t)                      vhat_t = v_t / (1 - beta2^t)
+ *     theta_t = theta_{t-1} - eta_t ( mhat_t / (sqrt(vhat_t) + xi) + lambda theta_{t-1} )
+ *
+ * with clip(g, C) = g * min(1, C / ||g||_2), the norm taken over ALL parameters of one example's
+ * gradient.  The mega-batch B_t is processed as micro-batches (Section 5.3, gradient accumulation):
+ * for each micro-batch the caller runs pass 1 (dp_sqnorms_* over every layer, "+=" into sqnorms[B]),
+ * then pass 2 (dp_clip_accumulate_* over every layer, "+=" into the fp32 sum buffers), and after the
+ * last micro-batch one dp_noise_adamw over the flat parameter space.
+ *
+ * Per-example gradients are never materialised.  For a dense layer y = xW + b with inputs A_i [T, d_in]
+ * and output gradients G_i [T, d_out] of example i (the outer-product form of the fully connected
+ * layer's gradient, Section 4.3) the example's weight gradient is A_i^T G_i and its bias gradient is
+ * sum_t G_i[t, :].
+ *
+ * Conventions
+ *   - Every pointer except dp_ctx* and the out-parameters of dp_create / dp_choose_path is a DEVICE
+ *     pointer owned by the caller.  The library neither frees nor keeps it beyond the completion of the
+ *     call's work on the context's stream.
+ *   - All tensors are dense row-major.  A, Xhat: [B, T, d_in|d];  G: [B, T, d_out|d];  ids: int32 [B, T];
+ *     weight-shaped sums: [d_in, d_out];  embedding sums: [V, d].  sqnorms, sums, params, m, v: fp32.
+ *   - dtype selects the element type of A / Xhat / G: DP_F32 (4-byte aligned) or DP_BF16 (16-byte aligned
+ *     pointers and d_in, d_out, d multiples of 8).  Accumulation is always fp32.
+ *   - Calls are asynchronous on the context's stream and return argument and launch errors at once.
+ *     Errors found on the device (a token id outside [0, V)) are returned by the next dp_sync.
+ *   - Results are deterministic: the same call sequence on the same inputs gives the same bits.
+ *   - No entry point prints, throws or exits.  A context must be used by one host thread at a time.
+ */
+#ifndef DPCLIP_H
+#define DPCLIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dp_ctx dp_ctx; /* opaque: stream, workspace, device error word */
+
+typedef enum { DP_F32 = 0, DP_BF16 = 1 } dp_dtype;
+
+/* How the dense weight-gradient norm is evaluated (see dp_sqnorms_dense). */
+typedef enum { DP_PATH_AUTO = 0, DP_PATH_GRAM = 1, DP_PATH_MATERIALISE = 2 } dp_path;
+
+typedef enum {
+    DP_OK = 0,
+    DP_ERR_NULL = -1,      /* a required pointer is NULL */
+    DP_ERR_SHAPE = -2,     /* a size is negative, or not a multiple the dtype requires */
+    DP_ERR_DTYPE = -3,     /* unknown dp_dtype / dp_path value */
+    DP_ERR_ALIGN = -4,     /* pointer alignment */
+    DP_ERR_VALUE = -5,     /* C <= 0, sigma < 0, batch_size == 0, step == 0, beta outside [0,1), eps < 0 ... */
+    DP_ERR_INDEX = -6,     /* a token id outside [0, V) was met on the device (reported by dp_sync) */
+    DP_ERR_WORKSPACE = -7, /* the context's workspace is too small for this call */
+    DP_ERR_HIP = -8        /* a HIP runtime call failed; dp_last_error has the text */
+} dp_status;
+
+/* Create a context bound to `hip_stream` (a hipStream_t, borrowed; NULL = the null stream) on the current
+ * device, with a device workspace of `workspace_bytes` (0 = 512 MiB) for clip factors, split-reduction
+ * partials and sort buffers.  *out is set only on DP_OK. */
+dp_status dp_create(dp_ctx** out, void* hip_stream, size_t workspace_bytes);
+/* Synchronise the stream, then free the workspace and the context. */
+dp_status dp_destroy(dp_ctx* ctx);
+/* hipStreamSynchronize, then fetch-and-clear the device error word: DP_OK or DP_ERR_INDEX / DP_ERR_HIP. */
+dp_status dp_sync(dp_ctx* ctx);
+const char* dp_status_str(dp_status s);
+/* Text of the last error of this context; static storage inside the context. */
+const char* dp_last_error(const dp_ctx* ctx);
+
+/* ---------------------------------------------------------------------------------------------------
+ * Pass 1: per-example squared norms.  Each call ADDS one layer's contribution to sqnorms[i], i < B.
+ * The caller zeroes sqnorms once per micro-batch (dp_zero_f32) and calls every layer on one stream;
+ * the sum over layers is the squared global norm that clip() of Algorithm 1 needs.
+ * B == 0 or T == 0 is a no-op.
+ * ------------------------------------------------------------------------------------------------- */
+
+/* Dense layer: sqnorms[i] += ||A_i^T G_i||_F^2  (+ ||sum_t G_i[t,:]||^2 if has_bias).
+ * DP_PATH_GRAM evaluates sum_{t,s} (a_t.a_s)(g_t.g_s) from the two T x T Gram matrices;
+ * DP_PATH_MATERIALISE forms A_i^T G_i tile by tile and sums the squares; DP_PATH_AUTO picks by
+ * dp_choose_path.  Both give the same value up to fp32 rounding order. */
+dp_status dp_sqnorms_dense(dp_ctx* ctx, const void* A, const void* G, dp_dtype dtype, int B, int T, int d_in,
+                           int d_out, int has_bias, dp_path path, float* sqnorms);
+
+/* LayerNorm y = gamma * xhat + beta, Xhat = the NORMALISED activations:
+ * sqnorms[i] += sum_j (sum_t G[i,t,j] Xhat[i,t,j])^2 + sum_j (sum_t G[i,t,j])^2. */
+dp_status dp_sqnorms_layernorm(dp_ctx* ctx, const void* Xhat, const void* G, dp_dtype dtype, int B, int T, int d,
+                               float* sqnorms);
+
+/* Embedding lookup y_t = E[ids_t] (Section 4.3 names the word-piece, positional and token-type tables):
+ * sqnorms[i] += sum_v || sum_{t: ids[i,t] = v} G[i,t,:] ||^2.
+ * distinct_per_example != 0 promises that no id repeats inside an example (position ids), which
+ * reduces the value to ||G_i||_F^2; ids are then only range-checked. */
+dp_status dp_sqnorms_embedding(dp_ctx* ctx, const int32_t* ids, const void* G, dp_dtype dtype, int B, int T, int d,
+                               int V, int distinct_per_example, float* sqnorms);
+
+/* ---------------------------------------------------------------------------------------------------
+ * Pass 2: clip-weighted sums.  With c_i = min(1, C / sqrt(sqnorms[i])) (c_i = 1 where sqnorms[i] == 0),
+ * each call ADDS sum_i c_i * (example i's gradient of this layer) to the caller's fp32 sum buffers.
+ * The caller zeroes the sum buffers once per mega-batch; repeated calls over micro-batches accumulate.
+ * sqnorms must hold the finished pass-1 result of the SAME micro-batch.
+ * ------------------------------------------------------------------------------------------------- */
+
+/* sum_W[p,q] += sum_i c_i sum_t A[i,t,p] G[i,t,q];  sum_b[q] += sum_i c_i sum_t G[i,t,q] (sum_b may be NULL).
+ * For DP_BF16 the clip factor is applied to G in fp32 and the product is rounded back to bf16
+ * (round-to-nearest-even) before the matrix-core contraction; accumulation is fp32. */
+dp_status dp_clip_accumulate_dense(dp_ctx* ctx, const void* A, const void* G, dp_dtype dtype, int B, int T, int d_in,
+                                   int d_out, float C, const float* sqnorms, float* sum_W, float* sum_b);
+
+/* sum_gamma[j] += sum_i c_i sum_t G[i,t,j] Xhat[i,t,j];  sum_beta[j] += sum_i c_i sum_t G[i,t,j]. */
+dp_status dp_clip_accumulate_layernorm(dp_ctx* ctx, const void* Xhat, const void* G, dp_dtype dtype, int B, int T,
+                                       int d, float C, const float* sqnorms, float* sum_gamma, float* sum_beta);
+
+/* sum_E[ids[i,t], :] += c_i G[i,t,:] for every token.  Rows are added in ascending (i, t) order per id. */
+dp_status dp_clip_accumulate_embedding(dp_ctx* ctx, const int32_t* ids, const void* G, dp_dtype dtype, int B, int T,
+                                       int d, int V, float C, const float* sqnorms, float* sum_E);
+
+/* The clip factors themselves (pass 2 computes them internally; exposed for checks): c[i], i < B. */
+dp_status dp_clip_factors(dp_ctx* ctx, const float* sqnorms, int B, float C, float* c);
+
+/* ---------------------------------------------------------------------------------------------------
+ * Update (Algorithm 1, g_t line to theta_t line) over the slice [elem_offset, elem_offset + n) of the
+ * flat parameter space; params, m, v, sum point at the slice's first element.
+ *   g = (sum + sigma*C*z) / batch_size,  z ~ N(0,1) drawn per GLOBAL element index from Philox4x32-10:
+ *   element e uses word e%4 of the block with counter (lo32(e/4), hi32(e/4), lo32(step), hi32(step)) and
+ *   key (lo32(seed), hi32(seed)); u = ((word >> 9) + 0.5) * 2^-23; Box-Muller on the word pairs (0,1)
+ *   and (2,3): even element rho*cos(2 pi u_odd), odd element rho*sin(2 pi u_odd), rho = sqrt(-2 ln u_even).
+ *   The noise therefore does not depend on how the caller slices the update.  sigma == 0 draws nothing.
+ * batch_size is the mega-batch example count |B_t|; step is t >= 1 (bias correction and RNG counter);
+ * eps is xi (the paper sets 1e-11), added outside the square root; weight decay multiplies theta_{t-1}.
+ * zero_sum != 0 also clears `sum` for the next mega-batch.
+ * ------------------------------------------------------------------------------------------------- */
+dp_status dp_noise_adamw(dp_ctx* ctx, float* params, float* m, float* v, float* sum, uint64_t n,
+                         uint64_t elem_offset, float sigma, float C, uint64_t seed, uint64_t step,
+                         uint64_t batch_size, float lr, float beta1, float beta2, float eps, float weight_decay,
+                         int zero_sum);
+
+/* ---------------------------------------------------------------------------------------------------
+ * Aids
+ * ------------------------------------------------------------------------------------------------- */
+dp_status dp_zero_f32(dp_ctx* ctx, float* p, uint64_t n);
+/* The raw Philox words that serve elements [elem_offset, elem_offset + n) (same mapping as above). */
+dp_status dp_philox_u32(dp_ctx* ctx, uint32_t* out, uint64_t n, uint64_t elem_offset, uint64_t seed, uint64_t step);
+/* The standard normals z that dp_noise_adamw draws for elements [elem_offset, elem_offset + n). */
+dp_status dp_normal_f32(dp_ctx* ctx, float* out, uint64_t n, uint64_t elem_offset, uint64_t seed, uint64_t step);
+/* Host-only, pure: the path DP_PATH_AUTO takes for this shape (HOST pointer out). */
+dp_status dp_choose_path(int T, int d_in, int d_out, dp_dtype dtype, dp_path* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DPCLIP_H */

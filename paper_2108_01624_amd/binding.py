@@ -1,0 +1,222 @@
+"""ctypes binding of libdpclip.so: one Python function per C entry point, same names, argument
+marshalling only (tensor -> device pointer, dtype -> enum).  Every step of the path runs in the
+library's HIP kernels; there is no fallback: if the library is missing, loading raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import c_char_p, c_float, c_int, c_size_t, c_uint64, c_void_p
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libdpclip.so")
+_lib = None
+
+DP_F32, DP_BF16 = 0, 1
+DP_PATH_AUTO, DP_PATH_GRAM, DP_PATH_MATERIALISE = 0, 1, 2
+DP_OK = 0
+STATUS_NAMES = {0: "DP_OK", -1: "DP_ERR_NULL", -2: "DP_ERR_SHAPE", -3: "DP_ERR_DTYPE", -4: "DP_ERR_ALIGN",
+                -5: "DP_ERR_VALUE", -6: "DP_ERR_INDEX", -7: "DP_ERR_WORKSPACE", -8: "DP_ERR_HIP"}
+
+# name -> argument types (all return dp_status unless listed in _RESTYPES)
+SIGNATURES = {
+    "dp_create": [ctypes.POINTER(c_void_p), c_void_p, c_size_t],
+    "dp_destroy": [c_void_p],
+    "dp_sync": [c_void_p],
+    "dp_status_str": [c_int],
+    "dp_last_error": [c_void_p],
+    "dp_sqnorms_dense": [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p],
+    "dp_sqnorms_layernorm": [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_void_p],
+    "dp_sqnorms_embedding": [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p],
+    "dp_clip_factors": [c_void_p, c_void_p, c_int, c_float, c_void_p],
+    "dp_clip_accumulate_dense": [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_float, c_void_p,
+                                 c_void_p, c_void_p],
+    "dp_clip_accumulate_layernorm": [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_float, c_void_p,
+                                     c_void_p, c_void_p],
+    "dp_clip_accumulate_embedding": [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_float, c_void_p,
+                                     c_void_p],
+    "dp_noise_adamw": [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_uint64, c_uint64, c_float, c_float, c_uint64,
+                       c_uint64, c_uint64, c_float, c_float, c_float, c_float, c_float, c_int],
+    "dp_zero_f32": [c_void_p, c_void_p, c_uint64],
+    "dp_philox_u32": [c_void_p, c_void_p, c_uint64, c_uint64, c_uint64, c_uint64],
+    "dp_normal_f32": [c_void_p, c_void_p, c_uint64, c_uint64, c_uint64, c_uint64],
+    "dp_choose_path": [c_int, c_int, c_int, c_int, ctypes.POINTER(c_int)],
+}
+_RESTYPES = {"dp_status_str": c_char_p, "dp_last_error": c_char_p}
+
+
+class DpError(RuntimeError):
+    def __init__(self, status: int, where: str, detail: str = ""):
+        self.status = status
+        super().__init__(f"{where}: {STATUS_NAMES.get(status, status)}" + (f" ({detail})" if detail else ""))
+
+
+def load_library():
+    """dlopen libdpclip.so and declare the prototypes.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2108_01624_amd.build` "
+                           "(there is no fallback path)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    for name, argtypes in SIGNATURES.items():
+        fn = getattr(lib, name)
+        fn.argtypes = argtypes
+        fn.restype = _RESTYPES.get(name, c_int)
+    _lib = lib
+    return lib
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _dtype_of(t) -> int:
+    import torch
+
+    if t.dtype == torch.float32:
+        return DP_F32
+    if t.dtype == torch.bfloat16:
+        return DP_BF16
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def _check(ctx, st: int, where: str):
+    if st != DP_OK:
+        detail = load_library().dp_last_error(ctx).decode() if ctx else ""
+        raise DpError(st, where, detail)
+
+
+# ---- one function per entry point (same names as the C ABI) ---------------------------------------
+def dp_create(stream_handle: int = 0, workspace_bytes: int = 0) -> int:
+    h = c_void_p()
+    st = load_library().dp_create(ctypes.byref(h), c_void_p(stream_handle), workspace_bytes)
+    if st != DP_OK:
+        raise DpError(st, "dp_create")
+    return h.value
+
+
+def dp_destroy(ctx):
+    _check(None, load_library().dp_destroy(ctx), "dp_destroy")
+
+
+def dp_sync(ctx):
+    _check(ctx, load_library().dp_sync(ctx), "dp_sync")
+
+
+def dp_status_str(s: int) -> str:
+    return load_library().dp_status_str(s).decode()
+
+
+def dp_last_error(ctx) -> str:
+    return load_library().dp_last_error(ctx).decode()
+
+
+def dp_sqnorms_dense(ctx, A, G, has_bias, path, sqnorms, *, B=None, T=None):
+    B = A.shape[0] if B is None else B
+    T = A.shape[1] if T is None else T
+    st = load_library().dp_sqnorms_dense(ctx, _ptr(A), _ptr(G), _dtype_of(A), B, T, A.shape[-1], G.shape[-1],
+                                         int(has_bias), int(path), _ptr(sqnorms))
+    _check(ctx, st, "dp_sqnorms_dense")
+
+
+def dp_sqnorms_layernorm(ctx, Xhat, G, sqnorms):
+    B, T, d = Xhat.shape
+    _check(ctx, load_library().dp_sqnorms_layernorm(ctx, _ptr(Xhat), _ptr(G), _dtype_of(G), B, T, d, _ptr(sqnorms)),
+           "dp_sqnorms_layernorm")
+
+
+def dp_sqnorms_embedding(ctx, ids, G, V, distinct_per_example, sqnorms):
+    B, T, d = G.shape
+    st = load_library().dp_sqnorms_embedding(ctx, _ptr(ids), _ptr(G), _dtype_of(G), B, T, d, int(V),
+                                             int(distinct_per_example), _ptr(sqnorms))
+    _check(ctx, st, "dp_sqnorms_embedding")
+
+
+def dp_clip_factors(ctx, sqnorms, C, c):
+    _check(ctx, load_library().dp_clip_factors(ctx, _ptr(sqnorms), sqnorms.shape[0], float(C), _ptr(c)), "dp_clip_factors")
+
+
+def dp_clip_accumulate_dense(ctx, A, G, C, sqnorms, sum_W, sum_b=None):
+    B, T, d_in = A.shape
+    st = load_library().dp_clip_accumulate_dense(ctx, _ptr(A), _ptr(G), _dtype_of(A), B, T, d_in, G.shape[-1], float(C),
+                                                 _ptr(sqnorms), _ptr(sum_W), _ptr(sum_b))
+    _check(ctx, st, "dp_clip_accumulate_dense")
+
+
+def dp_clip_accumulate_layernorm(ctx, Xhat, G, C, sqnorms, sum_gamma, sum_beta):
+    B, T, d = Xhat.shape
+    st = load_library().dp_clip_accumulate_layernorm(ctx, _ptr(Xhat), _ptr(G), _dtype_of(G), B, T, d, float(C),
+                                                     _ptr(sqnorms), _ptr(sum_gamma), _ptr(sum_beta))
+    _check(ctx, st, "dp_clip_accumulate_layernorm")
+
+
+def dp_clip_accumulate_embedding(ctx, ids, G, V, C, sqnorms, sum_E):
+    B, T, d = G.shape
+    st = load_library().dp_clip_accumulate_embedding(ctx, _ptr(ids), _ptr(G), _dtype_of(G), B, T, d, int(V), float(C),
+                                                     _ptr(sqnorms), _ptr(sum_E))
+    _check(ctx, st, "dp_clip_accumulate_embedding")
+
+
+def dp_noise_adamw(ctx, params, m, v, sum_, *, n=None, elem_offset=0, sigma, C, seed, step, batch_size, lr, beta1, beta2,
+                   eps=1e-11, weight_decay, zero_sum=False):
+    n = params.numel() if n is None else n
+    st = load_library().dp_noise_adamw(ctx, _ptr(params), _ptr(m), _ptr(v), _ptr(sum_), n, elem_offset, sigma, C, seed,
+                                       step, batch_size, lr, beta1, beta2, eps, weight_decay, int(zero_sum))
+    _check(ctx, st, "dp_noise_adamw")
+
+
+def dp_zero_f32(ctx, p, n=None):
+    _check(ctx, load_library().dp_zero_f32(ctx, _ptr(p), p.numel() if n is None else n), "dp_zero_f32")
+
+
+def dp_philox_u32(ctx, out, elem_offset, seed, step, n=None):
+    _check(ctx, load_library().dp_philox_u32(ctx, _ptr(out), out.numel() if n is None else n, elem_offset, seed, step),
+           "dp_philox_u32")
+
+
+def dp_normal_f32(ctx, out, elem_offset, seed, step, n=None):
+    _check(ctx, load_library().dp_normal_f32(ctx, _ptr(out), out.numel() if n is None else n, elem_offset, seed, step),
+           "dp_normal_f32")
+
+
+def dp_choose_path(T, d_in, d_out, dtype=DP_BF16) -> int:
+    out = c_int()
+    st = load_library().dp_choose_path(T, d_in, d_out, dtype, ctypes.byref(out))
+    if st != DP_OK:
+        raise DpError(st, "dp_choose_path")
+    return out.value
+
+
+class Context:
+    """A dp_ctx bound to torch's current HIP stream on the current device."""
+
+    def __init__(self, workspace_bytes: int = 0, stream=None):
+        import torch
+
+        if not torch.cuda.is_available():
+            raise RuntimeError("paper_2108_01624_amd needs a GPU: there is no CPU path")
+        s = torch.cuda.current_stream() if stream is None else stream
+        self.stream = s
+        self.handle = dp_create(s.cuda_stream, workspace_bytes)
+
+    def close(self):
+        if self.handle:
+            dp_destroy(self.handle)
+            self.handle = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        self.close()
+
+    def __getattr__(self, name):
+        # ctx.sqnorms_dense(...) == dp_sqnorms_dense(ctx.handle, ...)
+        fn = globals().get("dp_" + name)
+        if fn is None:
+            raise AttributeError(name)
+        return lambda *a, **k: fn(self.handle, *a, **k)

@@ -1,0 +1,290 @@
+// C ABI entry points: argument checks, context management and dispatch to the kernel launchers.
+#include <limits.h>
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "dp_common.h"
+
+namespace {
+
+constexpr size_t DEFAULT_WORKSPACE = (size_t)512 << 20;
+constexpr int CBUF_CAP = 1 << 20;
+
+#define REQUIRE_CTX(ctx) \
+    if (!(ctx)) return DP_ERR_NULL
+
+#define FAIL(ctx, code, ...)          \
+    do {                              \
+        DP_SET_ERR(ctx, __VA_ARGS__); \
+        return code;                  \
+    } while (0)
+
+dp_status check_dtype(dp_ctx* ctx, dp_dtype dt) {
+    if (dt != DP_F32 && dt != DP_BF16) FAIL(ctx, DP_ERR_DTYPE, "unknown dtype %d", (int)dt);
+    return DP_OK;
+}
+
+dp_status check_tensor(dp_ctx* ctx, const char* name, const void* p, dp_dtype dt, int width) {
+    if (!p) FAIL(ctx, DP_ERR_NULL, "%s is NULL", name);
+    if (dt == DP_BF16) {
+        if (width % 8) FAIL(ctx, DP_ERR_SHAPE, "%s: width %d is not a multiple of 8 (bf16)", name, width);
+        if ((uintptr_t)p & 15) FAIL(ctx, DP_ERR_ALIGN, "%s is not 16-byte aligned (bf16)", name);
+    } else if ((uintptr_t)p & 3) {
+        FAIL(ctx, DP_ERR_ALIGN, "%s is not 4-byte aligned", name);
+    }
+    return DP_OK;
+}
+
+dp_status check_f32(dp_ctx* ctx, const char* name, const void* p) {
+    if (!p) FAIL(ctx, DP_ERR_NULL, "%s is NULL", name);
+    if ((uintptr_t)p & 3) FAIL(ctx, DP_ERR_ALIGN, "%s is not 4-byte aligned", name);
+    return DP_OK;
+}
+
+dp_status check_bt(dp_ctx* ctx, int B, int T) {
+    if (B < 0 || T < 0) FAIL(ctx, DP_ERR_SHAPE, "negative B or T");
+    if ((long)B * T > (long)INT_MAX - 4096) FAIL(ctx, DP_ERR_SHAPE, "B*T = %ld exceeds 2^31", (long)B * T);
+    return DP_OK;
+}
+
+dp_status check_clip(dp_ctx* ctx, float C, int B) {
+    if (!(C > 0.f) || !isfinite(C)) FAIL(ctx, DP_ERR_VALUE, "clip norm C must be positive and finite");
+    if (B > ctx->cbuf_cap) FAIL(ctx, DP_ERR_WORKSPACE, "B = %d exceeds the clip-factor buffer (%d)", B, ctx->cbuf_cap);
+    return DP_OK;
+}
+
+#define TRY(expr)                    \
+    do {                             \
+        dp_status s__ = (expr);      \
+        if (s__ != DP_OK) return s__; \
+    } while (0)
+
+}  // namespace
+
+extern "C" {
+
+dp_status dp_create(dp_ctx** out, void* hip_stream, size_t workspace_bytes) {
+    if (!out) return DP_ERR_NULL;
+    dp_ctx* ctx = (dp_ctx*)calloc(1, sizeof(dp_ctx));
+    if (!ctx) return DP_ERR_HIP;
+    ctx->stream = (hipStream_t)hip_stream;
+    ctx->ws_bytes = workspace_bytes ? workspace_bytes : DEFAULT_WORKSPACE;
+    ctx->cbuf_cap = CBUF_CAP;
+    hipError_t e = hipGetDevice(&ctx->device);
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->ws, ctx->ws_bytes);
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->err_word, sizeof(int));
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->cbuf, (size_t)ctx->cbuf_cap * sizeof(float));
+    if (e == hipSuccess) e = hipMemset(ctx->err_word, 0, sizeof(int));
+    if (e != hipSuccess) {
+        if (ctx->ws) (void)hipFree(ctx->ws);
+        if (ctx->err_word) (void)hipFree(ctx->err_word);
+        if (ctx->cbuf) (void)hipFree(ctx->cbuf);
+        free(ctx);
+        return DP_ERR_HIP;
+    }
+    *out = ctx;
+    return DP_OK;
+}
+
+dp_status dp_destroy(dp_ctx* ctx) {
+    REQUIRE_CTX(ctx);
+    (void)hipStreamSynchronize(ctx->stream);
+    (void)hipFree(ctx->ws);
+    (void)hipFree(ctx->err_word);
+    (void)hipFree(ctx->cbuf);
+    free(ctx);
+    return DP_OK;
+}
+
+dp_status dp_sync(dp_ctx* ctx) {
+    REQUIRE_CTX(ctx);
+    DP_HIP_CHECK(ctx, hipStreamSynchronize(ctx->stream));
+    int w = 0;
+    DP_HIP_CHECK(ctx, hipMemcpy(&w, ctx->err_word, sizeof(int), hipMemcpyDeviceToHost));
+    if (w) {
+        DP_HIP_CHECK(ctx, hipMemset(ctx->err_word, 0, sizeof(int)));
+        FAIL(ctx, DP_ERR_INDEX, "a token id outside [0, V) was met on the device");
+    }
+    return DP_OK;
+}
+
+const char* dp_status_str(dp_status s) {
+    switch (s) {
+        case DP_OK: return "DP_OK";
+        case DP_ERR_NULL: return "DP_ERR_NULL";
+        case DP_ERR_SHAPE: return "DP_ERR_SHAPE";
+        case DP_ERR_DTYPE: return "DP_ERR_DTYPE";
+        case DP_ERR_ALIGN: return "DP_ERR_ALIGN";
+        case DP_ERR_VALUE: return "DP_ERR_VALUE";
+        case DP_ERR_INDEX: return "DP_ERR_INDEX";
+        case DP_ERR_WORKSPACE: return "DP_ERR_WORKSPACE";
+        case DP_ERR_HIP: return "DP_ERR_HIP";
+    }
+    return "DP_ERR_UNKNOWN";
+}
+
+const char* dp_last_error(const dp_ctx* ctx) { return ctx ? ctx->msg : "no context"; }
+
+dp_status dp_choose_path(int T, int d_in, int d_out, dp_dtype dtype, dp_path* out) {
+    if (!out) return DP_ERR_NULL;
+    if (dtype != DP_F32 && dtype != DP_BF16) return DP_ERR_DTYPE;
+    if (T < 0 || d_in < 0 || d_out < 0) return DP_ERR_SHAPE;
+    // flops of the symmetric Gram form, T(T+1)/2 * (d_in + d_out) multiply-adds per example, against those
+    // of materialising the d_in x d_out gradient, T * d_in * d_out.
+    const double gram = 0.5 * ((double)T + 1.0) * ((double)d_in + (double)d_out);
+    const double mat = (double)d_in * (double)d_out;
+    *out = gram <= mat ? DP_PATH_GRAM : DP_PATH_MATERIALISE;
+    return DP_OK;
+}
+
+dp_status dp_sqnorms_dense(dp_ctx* ctx, const void* A, const void* G, dp_dtype dtype, int B, int T, int d_in,
+                           int d_out, int has_bias, dp_path path, float* sqnorms) {
+    REQUIRE_CTX(ctx);
+    TRY(check_dtype(ctx, dtype));
+    if (path != DP_PATH_AUTO && path != DP_PATH_GRAM && path != DP_PATH_MATERIALISE)
+        FAIL(ctx, DP_ERR_DTYPE, "unknown path %d", (int)path);
+    TRY(check_bt(ctx, B, T));
+    if (d_in < 0 || d_out < 0) FAIL(ctx, DP_ERR_SHAPE, "negative layer width");
+    TRY(check_tensor(ctx, "A", A, dtype, d_in));
+    TRY(check_tensor(ctx, "G", G, dtype, d_out));
+    TRY(check_f32(ctx, "sqnorms", sqnorms));
+    if (B == 0 || T == 0 || d_out == 0) return DP_OK;
+    if (d_in == 0) {  // no weights; only the bias term is left
+        if (has_bias) return dpk_colstat_sqnorms(ctx, nullptr, G, dtype, B, T, d_out, 0, 1, sqnorms);
+        return DP_OK;
+    }
+    if (path == DP_PATH_AUTO) dp_choose_path(T, d_in, d_out, dtype, &path);
+    if (path == DP_PATH_GRAM) return dpk_gram_sqnorms(ctx, A, G, dtype, B, T, d_in, d_out, has_bias, sqnorms);
+    return dpk_materialise_sqnorms(ctx, A, G, dtype, B, T, d_in, d_out, has_bias, sqnorms);
+}
+
+dp_status dp_sqnorms_layernorm(dp_ctx* ctx, const void* Xhat, const void* G, dp_dtype dtype, int B, int T, int d,
+                               float* sqnorms) {
+    REQUIRE_CTX(ctx);
+    TRY(check_dtype(ctx, dtype));
+    TRY(check_bt(ctx, B, T));
+    if (d < 0) FAIL(ctx, DP_ERR_SHAPE, "negative width");
+    TRY(check_tensor(ctx, "Xhat", Xhat, dtype, d));
+    TRY(check_tensor(ctx, "G", G, dtype, d));
+    TRY(check_f32(ctx, "sqnorms", sqnorms));
+    return dpk_colstat_sqnorms(ctx, Xhat, G, dtype, B, T, d, 1, 1, sqnorms);
+}
+
+dp_status dp_sqnorms_embedding(dp_ctx* ctx, const int32_t* ids, const void* G, dp_dtype dtype, int B, int T, int d,
+                               int V, int distinct_per_example, float* sqnorms) {
+    REQUIRE_CTX(ctx);
+    TRY(check_dtype(ctx, dtype));
+    TRY(check_bt(ctx, B, T));
+    if (d < 0 || V <= 0) FAIL(ctx, DP_ERR_SHAPE, "width must be >= 0 and V > 0");
+    TRY(check_f32(ctx, "ids", ids));
+    TRY(check_tensor(ctx, "G", G, dtype, d));
+    TRY(check_f32(ctx, "sqnorms", sqnorms));
+    return dpk_embedding_sqnorms(ctx, ids, G, dtype, B, T, d, V, distinct_per_example, sqnorms);
+}
+
+dp_status dp_clip_factors(dp_ctx* ctx, const float* sqnorms, int B, float C, float* c) {
+    REQUIRE_CTX(ctx);
+    if (B < 0) FAIL(ctx, DP_ERR_SHAPE, "negative B");
+    TRY(check_f32(ctx, "sqnorms", sqnorms));
+    TRY(check_f32(ctx, "c", c));
+    if (!(C > 0.f) || !isfinite(C)) FAIL(ctx, DP_ERR_VALUE, "clip norm C must be positive and finite");
+    if (B == 0) return DP_OK;
+    return dpk_clip_factors(ctx, sqnorms, B, C, c);
+}
+
+dp_status dp_clip_accumulate_dense(dp_ctx* ctx, const void* A, const void* G, dp_dtype dtype, int B, int T, int d_in,
+                                   int d_out, float C, const float* sqnorms, float* sum_W, float* sum_b) {
+    REQUIRE_CTX(ctx);
+    TRY(check_dtype(ctx, dtype));
+    TRY(check_bt(ctx, B, T));
+    if (d_in < 0 || d_out < 0) FAIL(ctx, DP_ERR_SHAPE, "negative layer width");
+    TRY(check_tensor(ctx, "A", A, dtype, d_in));
+    TRY(check_tensor(ctx, "G", G, dtype, d_out));
+    TRY(check_f32(ctx, "sqnorms", sqnorms));
+    TRY(check_f32(ctx, "sum_W", sum_W));
+    if (sum_b) TRY(check_f32(ctx, "sum_b", sum_b));
+    if (dtype == DP_BF16 && ((uintptr_t)sum_W & 15)) FAIL(ctx, DP_ERR_ALIGN, "sum_W is not 16-byte aligned");
+    TRY(check_clip(ctx, C, B));
+    if (B == 0 || T == 0 || d_out == 0) return DP_OK;
+    TRY(dpk_clip_factors(ctx, sqnorms, B, C, ctx->cbuf));
+    if (d_in > 0) TRY(dpk_weighted_gemm(ctx, A, G, dtype, B, T, d_in, d_out, ctx->cbuf, sum_W));
+    if (sum_b) TRY(dpk_colstat_sums(ctx, nullptr, G, dtype, B, T, d_out, ctx->cbuf, nullptr, sum_b));
+    return DP_OK;
+}
+
+dp_status dp_clip_accumulate_layernorm(dp_ctx* ctx, const void* Xhat, const void* G, dp_dtype dtype, int B, int T,
+                                       int d, float C, const float* sqnorms, float* sum_gamma, float* sum_beta) {
+    REQUIRE_CTX(ctx);
+    TRY(check_dtype(ctx, dtype));
+    TRY(check_bt(ctx, B, T));
+    if (d < 0) FAIL(ctx, DP_ERR_SHAPE, "negative width");
+    TRY(check_tensor(ctx, "Xhat", Xhat, dtype, d));
+    TRY(check_tensor(ctx, "G", G, dtype, d));
+    TRY(check_f32(ctx, "sqnorms", sqnorms));
+    TRY(check_f32(ctx, "sum_gamma", sum_gamma));
+    TRY(check_f32(ctx, "sum_beta", sum_beta));
+    TRY(check_clip(ctx, C, B));
+    if (B == 0 || T == 0 || d == 0) return DP_OK;
+    TRY(dpk_clip_factors(ctx, sqnorms, B, C, ctx->cbuf));
+    return dpk_colstat_sums(ctx, Xhat, G, dtype, B, T, d, ctx->cbuf, sum_gamma, sum_beta);
+}
+
+dp_status dp_clip_accumulate_embedding(dp_ctx* ctx, const int32_t* ids, const void* G, dp_dtype dtype, int B, int T,
+                                       int d, int V, float C, const float* sqnorms, float* sum_E) {
+    REQUIRE_CTX(ctx);
+    TRY(check_dtype(ctx, dtype));
+    TRY(check_bt(ctx, B, T));
+    if (d < 0 || V <= 0) FAIL(ctx, DP_ERR_SHAPE, "width must be >= 0 and V > 0");
+    TRY(check_f32(ctx, "ids", ids));
+    TRY(check_tensor(ctx, "G", G, dtype, d));
+    TRY(check_f32(ctx, "sqnorms", sqnorms));
+    TRY(check_f32(ctx, "sum_E", sum_E));
+    TRY(check_clip(ctx, C, B));
+    if (B == 0 || T == 0 || d == 0) return DP_OK;
+    TRY(dpk_clip_factors(ctx, sqnorms, B, C, ctx->cbuf));
+    return dpk_embedding_sums(ctx, ids, G, dtype, B, T, d, V, ctx->cbuf, sum_E);
+}
+
+dp_status dp_noise_adamw(dp_ctx* ctx, float* params, float* m, float* v, float* sum, uint64_t n,
+                         uint64_t elem_offset, float sigma, float C, uint64_t seed, uint64_t step,
+                         uint64_t batch_size, float lr, float beta1, float beta2, float eps, float weight_decay,
+                         int zero_sum) {
+    REQUIRE_CTX(ctx);
+    TRY(check_f32(ctx, "params", params));
+    TRY(check_f32(ctx, "m", m));
+    TRY(check_f32(ctx, "v", v));
+    TRY(check_f32(ctx, "sum", sum));
+    if (!(sigma >= 0.f) || !isfinite(sigma)) FAIL(ctx, DP_ERR_VALUE, "sigma must be >= 0 and finite");
+    if (!(C > 0.f) || !isfinite(C)) FAIL(ctx, DP_ERR_VALUE, "clip norm C must be positive and finite");
+    if (batch_size == 0) FAIL(ctx, DP_ERR_VALUE, "batch_size must be positive");
+    if (step == 0) FAIL(ctx, DP_ERR_VALUE, "step counts from 1");
+    if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f)) FAIL(ctx, DP_ERR_VALUE, "beta outside [0, 1)");
+    if (!(eps >= 0.f) || !isfinite(eps)) FAIL(ctx, DP_ERR_VALUE, "eps must be >= 0 and finite");
+    if (!isfinite(lr) || !isfinite(weight_decay)) FAIL(ctx, DP_ERR_VALUE, "lr and weight_decay must be finite");
+    if (elem_offset + n < elem_offset) FAIL(ctx, DP_ERR_SHAPE, "elem_offset + n overflows");
+    return dpk_noise_adamw(ctx, params, m, v, sum, n, elem_offset, sigma, C, seed, step, batch_size, lr, beta1, beta2,
+                           eps, weight_decay, zero_sum);
+}
+
+dp_status dp_zero_f32(dp_ctx* ctx, float* p, uint64_t n) {
+    REQUIRE_CTX(ctx);
+    TRY(check_f32(ctx, "p", p));
+    return dpk_zero_f32(ctx, p, n);
+}
+
+dp_status dp_philox_u32(dp_ctx* ctx, uint32_t* out, uint64_t n, uint64_t elem_offset, uint64_t seed, uint64_t step) {
+    REQUIRE_CTX(ctx);
+    TRY(check_f32(ctx, "out", out));
+    if (elem_offset + n < elem_offset) FAIL(ctx, DP_ERR_SHAPE, "elem_offset + n overflows");
+    return dpk_philox_u32(ctx, out, n, elem_offset, seed, step);
+}
+
+dp_status dp_normal_f32(dp_ctx* ctx, float* out, uint64_t n, uint64_t elem_offset, uint64_t seed, uint64_t step) {
+    REQUIRE_CTX(ctx);
+    TRY(check_f32(ctx, "out", out));
+    if (elem_offset + n < elem_offset) FAIL(ctx, DP_ERR_SHAPE, "elem_offset + n overflows");
+    return dpk_normal_f32(ctx, out, n, elem_offset, seed, step);
+}
+
+}  // extern "C"

@@ -1,0 +1,145 @@
+// Internal declarations shared by the HIP sources of libdpclip (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "dpclip.h"
+
+struct dp_ctx {
+    hipStream_t stream;
+    int device;
+    char* ws;         // device workspace
+    size_t ws_bytes;
+    int* err_word;    // device: bit 0 = token id out of range
+    float* cbuf;      // device: clip factors of the current micro-batch
+    int cbuf_cap;     // capacity of cbuf in floats
+    char msg[256];
+};
+
+#define DP_SET_ERR(ctx, ...) snprintf((ctx)->msg, sizeof((ctx)->msg), __VA_ARGS__)
+
+#define DP_HIP_CHECK(ctx, expr)                                                      \
+    do {                                                                             \
+        hipError_t e__ = (expr);                                                     \
+        if (e__ != hipSuccess) {                                                     \
+            DP_SET_ERR(ctx, "%s failed: %s", #expr, hipGetErrorString(e__));         \
+            return DP_ERR_HIP;                                                       \
+        }                                                                            \
+    } while (0)
+
+#define DP_LAUNCH_CHECK(ctx, what)                                                   \
+    do {                                                                             \
+        hipError_t e__ = hipGetLastError();                                          \
+        if (e__ != hipSuccess) {                                                     \
+            DP_SET_ERR(ctx, "launch of %s failed: %s", what, hipGetErrorString(e__)); \
+            return DP_ERR_HIP;                                                       \
+        }                                                                            \
+    } while (0)
+
+static inline size_t dp_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Simple bump allocator over the context workspace (valid for the duration of one API call:
+// all kernels of a call run on one stream before those of the next call).
+struct dp_ws_alloc {
+    dp_ctx* ctx;
+    size_t off;
+    explicit dp_ws_alloc(dp_ctx* c) : ctx(c), off(0) {}
+    template <typename T>
+    T* get(size_t count) {
+        size_t o = dp_align_up(off, 256);
+        size_t end = o + count * sizeof(T);
+        if (end > ctx->ws_bytes) return nullptr;
+        off = end;
+        return reinterpret_cast<T*>(ctx->ws + o);
+    }
+    size_t remaining() const {
+        size_t o = dp_align_up(off, 256);
+        return o >= ctx->ws_bytes ? 0 : ctx->ws_bytes - o;
+    }
+};
+
+// ------------------------------------------------------------------------------------------------
+// device helpers
+// ------------------------------------------------------------------------------------------------
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float dp_bf16_bits_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+__device__ __forceinline__ float dp_bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float dp_bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// fp32 -> bf16 bits, round to nearest even (inputs here are finite products c*g).
+__device__ __forceinline__ uint32_t dp_f32_to_bf16_bits(float x) {
+    uint32_t u = __float_as_uint(x);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ uint32_t dp_pack_bf16x2(float lo, float hi) {
+    return dp_f32_to_bf16_bits(lo) | (dp_f32_to_bf16_bits(hi) << 16);
+}
+
+__device__ __forceinline__ float dp_wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// Sum over a workgroup of NT threads (NT multiple of 64, <= 1024); result valid in thread 0.
+// `red` is LDS scratch of at least NT/64 floats.  Fixed order => deterministic.
+template <int NT>
+__device__ __forceinline__ float dp_block_sum(float v, float* red) {
+    v = dp_wave_sum(v);
+    const int w = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[w] = v;
+    __syncthreads();
+    float t = 0.f;
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int i = 0; i < NT / 64; ++i) t += red[i];
+    }
+    return t;
+}
+
+__device__ __forceinline__ float dp_clip_factor(float sqnorm, float C) {
+    // c = min(1, C / ||g||); a zero gradient keeps factor 1
+    return sqnorm > 0.f ? fminf(1.f, C / sqrtf(sqnorm)) : 1.f;
+}
+
+// ------------------------------------------------------------------------------------------------
+// launchers implemented in the .hip files (host side; all enqueue on ctx->stream)
+// ------------------------------------------------------------------------------------------------
+dp_status dpk_zero_f32(dp_ctx*, float* p, uint64_t n);
+dp_status dpk_finish_partials(dp_ctx*, const float* partial, int B, int J, float* sqnorms);
+dp_status dpk_clip_factors(dp_ctx*, const float* sqnorms, int B, float C, float* c);
+dp_status dpk_reduce_partials(dp_ctx*, const float* part, int R, size_t stride, size_t n, float* out);
+dp_status dpk_materialise_f32(dp_ctx*, const float* A, const float* G, int B, int T, int d_in, int d_out,
+                              float* sqnorms);
+
+dp_status dpk_philox_u32(dp_ctx*, uint32_t* out, uint64_t n, uint64_t off, uint64_t seed, uint64_t step);
+dp_status dpk_normal_f32(dp_ctx*, float* out, uint64_t n, uint64_t off, uint64_t seed, uint64_t step);
+dp_status dpk_noise_adamw(dp_ctx*, float* params, float* m, float* v, float* sum, uint64_t n, uint64_t off,
+                          float sigma, float C, uint64_t seed, uint64_t step, uint64_t batch, float lr, float b1,
+                          float b2, float eps, float wd, int zero_sum);
+
+dp_status dpk_gram_sqnorms(dp_ctx*, const void* A, const void* G, dp_dtype, int B, int T, int d_in, int d_out,
+                           int has_bias, float* sqnorms);
+dp_status dpk_materialise_sqnorms(dp_ctx*, const void* A, const void* G, dp_dtype, int B, int T, int d_in, int d_out,
+                                  int has_bias, float* sqnorms);
+dp_status dpk_weighted_gemm(dp_ctx*, const void* A, const void* G, dp_dtype, int B, int T, int d_in, int d_out,
+                            const float* c, float* sum_W);
+
+// column statistics shared by LayerNorm and dense-bias terms:
+//   sqnorms:  n[i] += [use_x] sum_j (sum_t g x)^2 + [use_1] sum_j (sum_t g)^2
+//   sums:     out_x[j] += sum_i c_i sum_t g x ; out_1[j] += sum_i c_i sum_t g   (either may be NULL)
+dp_status dpk_colstat_sqnorms(dp_ctx*, const void* X, const void* G, dp_dtype, int B, int T, int d, int use_x,
+                              int use_1, float* sqnorms);
+dp_status dpk_colstat_sums(dp_ctx*, const void* X, const void* G, dp_dtype, int B, int T, int d, const float* c,
+                           float* out_x, float* out_1);
+
+dp_status dpk_embedding_sqnorms(dp_ctx*, const int32_t* ids, const void* G, dp_dtype, int B, int T, int d, int V,
+                                int distinct, float* sqnorms);
+dp_status dpk_embedding_sums(dp_ctx*, const int32_t* ids, const void* G, dp_dtype, int B, int T, int d, int V,
+                             const float* c, float* sum_E);

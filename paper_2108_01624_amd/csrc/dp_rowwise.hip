@@ -1,0 +1,620 @@
+// HBM-bound streaming kernels of the hot path: column statistics (LayerNorm gain/offset and dense-bias
+// gradients), embedding-table gradients (per-example segment reduction for the norms, stable radix sort
+// plus ordered segment sums for the clip-weighted scatter), and the ordered reduction of partial buffers.
+//
+// Roofline: HBM.  Each kernel reads its bf16 (or fp32) inputs exactly once; algorithmic bytes per
+// example are T*d*elem for every tensor read.  Threads own 4 consecutive columns (8-byte bf16 / 16-byte
+// fp32 loads), a wave covers 256 consecutive columns of one row, so every row read is fully coalesced.
+#include "dp_common.h"
+
+namespace {
+
+// ------------------------------------------------------------------------------------------------
+// element access: VW consecutive elements starting at element index `idx`
+// ------------------------------------------------------------------------------------------------
+template <bool BF16, int VW>
+__device__ __forceinline__ void load_vec(const void* __restrict__ base, size_t idx, float out[VW]) {
+    if constexpr (BF16) {
+        static_assert(VW == 4, "bf16 rows are read four elements at a time");
+        const uint2 w = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(base) + idx);
+        out[0] = dp_bf16_lo(w.x);
+        out[1] = dp_bf16_hi(w.x);
+        out[2] = dp_bf16_lo(w.y);
+        out[3] = dp_bf16_hi(w.y);
+    } else if constexpr (VW == 4) {
+        const float4 w = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(base) + idx);
+        out[0] = w.x; out[1] = w.y; out[2] = w.z; out[3] = w.w;
+    } else {
+        out[0] = reinterpret_cast<const float*>(base)[idx];
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// column statistics, per example (pass 1)
+//   grid (B, ceil(d / (64*VW))), 256 threads = 4 row groups x 64 column lanes
+// ------------------------------------------------------------------------------------------------
+template <bool BF16, int VW, bool USE_X, bool USE_1>
+__global__ __launch_bounds__(256) void colstat_sqnorms_kernel(const void* __restrict__ X, const void* __restrict__ G,
+                                                              int T, int d, float* __restrict__ out, int J,
+                                                              int direct) {
+    __shared__ float red[4][64][2 * VW];
+    __shared__ float wred[4];
+    const int i = blockIdx.x;
+    const int lane = threadIdx.x & 63, tg = threadIdx.x >> 6;
+    const int col = (blockIdx.y * 64 + lane) * VW;
+    float sx[VW], s1[VW];
+#pragma unroll
+    for (int k = 0; k < VW; ++k) sx[k] = s1[k] = 0.f;
+    if (col < d) {
+        const size_t base = (size_t)i * T * d + col;
+#pragma unroll 4
+        for (int t = tg; t < T; t += 4) {
+            float g[VW];
+            load_vec<BF16, VW>(G, base + (size_t)t * d, g);
+            if constexpr (USE_X) {
+                float x[VW];
+                load_vec<BF16, VW>(X, base + (size_t)t * d, x);
+#pragma unroll
+                for (int k = 0; k < VW; ++k) sx[k] += g[k] * x[k];
+            }
+#pragma unroll
+            for (int k = 0; k < VW; ++k) s1[k] += g[k];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < VW; ++k) {
+        red[tg][lane][k] = sx[k];
+        red[tg][lane][VW + k] = s1[k];
+    }
+    __syncthreads();
+    float val = 0.f;
+    if (tg == 0) {
+#pragma unroll
+        for (int k = 0; k < 2 * VW; ++k) {
+            const float s = (red[0][lane][k] + red[1][lane][k]) + (red[2][lane][k] + red[3][lane][k]);
+            const bool on = k < VW ? USE_X : USE_1;
+            if (on) val += s * s;
+        }
+    }
+    const float tot = dp_block_sum<256>(val, wred);
+    if (threadIdx.x == 0) {
+        if (direct) out[i] += tot;
+        else out[(size_t)i * J + blockIdx.y] = tot;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// clip-weighted column sums (pass 2)
+//   grid (R, ceil(d / (64*VW))): WG r reduces rows [r*rows_per, (r+1)*rows_per) of the B*T rows
+//   partial layout: part[r][0][d] = sum c g x,  part[r][1][d] = sum c g
+// ------------------------------------------------------------------------------------------------
+template <bool BF16, int VW, bool USE_X>
+__global__ __launch_bounds__(256) void colstat_sums_kernel(const void* __restrict__ X, const void* __restrict__ G,
+                                                           const float* __restrict__ c, int T, int d, long nrows,
+                                                           int rows_per, float* __restrict__ part) {
+    __shared__ float red[4][64][2 * VW];
+    const int lane = threadIdx.x & 63, tg = threadIdx.x >> 6;
+    const int col = (blockIdx.y * 64 + lane) * VW;
+    const long r0 = (long)blockIdx.x * rows_per;
+    const long r1 = r0 + rows_per < nrows ? r0 + rows_per : nrows;
+    float sx[VW], s1[VW];
+#pragma unroll
+    for (int k = 0; k < VW; ++k) sx[k] = s1[k] = 0.f;
+    if (col < d) {
+#pragma unroll 4
+        for (long r = r0 + tg; r < r1; r += 4) {
+            const float w = c[r / T];
+            float g[VW];
+            load_vec<BF16, VW>(G, (size_t)r * d + col, g);
+            if constexpr (USE_X) {
+                float x[VW];
+                load_vec<BF16, VW>(X, (size_t)r * d + col, x);
+#pragma unroll
+                for (int k = 0; k < VW; ++k) sx[k] += w * (g[k] * x[k]);
+            }
+#pragma unroll
+            for (int k = 0; k < VW; ++k) s1[k] += w * g[k];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < VW; ++k) {
+        red[tg][lane][k] = sx[k];
+        red[tg][lane][VW + k] = s1[k];
+    }
+    __syncthreads();
+    if (tg == 0 && col < d) {
+        float* p = part + (size_t)blockIdx.x * 2 * d;
+#pragma unroll
+        for (int k = 0; k < VW; ++k) {
+            p[col + k] = (red[0][lane][k] + red[1][lane][k]) + (red[2][lane][k] + red[3][lane][k]);
+            p[d + col + k] = (red[0][lane][VW + k] + red[1][lane][VW + k]) + (red[2][lane][VW + k] + red[3][lane][VW + k]);
+        }
+    }
+}
+
+// out[j] += sum_{r<R} part[r*stride + j], r ascending (fixed order)
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* __restrict__ part, int R, size_t stride,
+                                                              size_t n, float* __restrict__ out) {
+    const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= n) return;
+    float t = 0.f;
+    for (int r = 0; r < R; ++r) t += part[(size_t)r * stride + j];
+    out[j] += t;
+}
+
+__global__ __launch_bounds__(256) void reduce_partials_vec4_kernel(const float4* __restrict__ part, int R,
+                                                                   size_t stride4, size_t n4,
+                                                                   float4* __restrict__ out) {
+    const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= n4) return;
+    float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int r = 0; r < R; ++r) {
+        const float4 p = part[(size_t)r * stride4 + j];
+        t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
+    }
+    float4 o = out[j];
+    o.x += t.x; o.y += t.y; o.z += t.z; o.w += t.w;
+    out[j] = o;
+}
+
+// ------------------------------------------------------------------------------------------------
+// embedding, per-example norms (pass 1): grid (B, ceil(d/(64*VW))), one wave per workgroup.
+// The wave ranks the example's T ids (stable counting rank in LDS), walks the rows in id order and adds
+// the square of every run of equal ids, column by column.
+// ------------------------------------------------------------------------------------------------
+template <bool BF16, int VW, bool DISTINCT>
+__global__ __launch_bounds__(64) void embedding_sqnorms_kernel(const int32_t* __restrict__ ids,
+                                                               const void* __restrict__ G, int T, int d, int V,
+                                                               float* __restrict__ out, int J, int direct,
+                                                               int* __restrict__ err) {
+    extern __shared__ int32_t lds[];
+    int32_t* sid = lds;         // [T] ids of this example
+    int32_t* order = lds + T;   // [T] row index at each sorted position
+    const int i = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int col = (blockIdx.y * 64 + lane) * VW;
+    bool bad = false;
+    for (int t = lane; t < T; t += 64) {
+        const int32_t v = ids[(size_t)i * T + t];
+        if (v < 0 || v >= V) bad = true;
+        sid[t] = v;
+    }
+    if (bad) atomicOr(err, 1);
+    __syncthreads();
+    if constexpr (!DISTINCT) {
+        for (int t = lane; t < T; t += 64) {
+            const int32_t v = sid[t];
+            int rank = 0;
+            for (int s = 0; s < T; ++s) {
+                const int32_t u = sid[s];
+                rank += (u < v) || (u == v && s < t);
+            }
+            order[rank] = t;
+        }
+        __syncthreads();
+    }
+    float tot = 0.f;
+    if (col < d) {
+        const size_t base = (size_t)i * T * d + col;
+        if constexpr (DISTINCT) {
+#pragma unroll 8
+            for (int t = 0; t < T; ++t) {
+                float g[VW];
+                load_vec<BF16, VW>(G, base + (size_t)t * d, g);
+#pragma unroll
+                for (int k = 0; k < VW; ++k) tot += g[k] * g[k];
+            }
+        } else {
+            float run[VW];
+#pragma unroll
+            for (int k = 0; k < VW; ++k) run[k] = 0.f;
+            int32_t prev = sid[order[0]];
+#pragma unroll 8
+            for (int p = 0; p < T; ++p) {
+                const int t = order[p];
+                const int32_t v = sid[t];
+                float g[VW];
+                load_vec<BF16, VW>(G, base + (size_t)t * d, g);
+                if (v != prev) {
+#pragma unroll
+                    for (int k = 0; k < VW; ++k) {
+                        tot += run[k] * run[k];
+                        run[k] = 0.f;
+                    }
+                    prev = v;
+                }
+#pragma unroll
+                for (int k = 0; k < VW; ++k) run[k] += g[k];
+            }
+#pragma unroll
+            for (int k = 0; k < VW; ++k) tot += run[k] * run[k];
+        }
+    }
+    tot = dp_wave_sum(tot);
+    if (lane == 0) {
+        // (an out-of-range id only changes the grouping; the error itself is reported by dp_sync)
+        if (direct) out[i] += tot;
+        else out[(size_t)i * J + blockIdx.y] = tot;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// embedding, clip-weighted scatter (pass 2): stable LSD radix sort of (id, row) + ordered segment sums
+// ------------------------------------------------------------------------------------------------
+constexpr int SORT_CHUNK = 1024;
+
+__global__ __launch_bounds__(256) void sort_keys_init(const int32_t* __restrict__ ids, int N, int V,
+                                                      uint32_t* __restrict__ keys, uint32_t* __restrict__ vals,
+                                                      int* __restrict__ err) {
+    const int r = blockIdx.x * 256 + threadIdx.x;
+    if (r >= N) return;
+    const int32_t v = ids[r];
+    const bool bad = v < 0 || v >= V;
+    if (bad) atomicOr(err, 1);
+    keys[r] = bad ? (uint32_t)V : (uint32_t)v;  // sentinel V sorts last and is skipped
+    vals[r] = (uint32_t)r;
+}
+
+// hist[b * nchunks + c] = number of keys of chunk c whose digit is b
+__global__ __launch_bounds__(256) void sort_hist(const uint32_t* __restrict__ keys, int N, int shift,
+                                                 uint32_t* __restrict__ hist, int nchunks) {
+    __shared__ uint32_t dig[SORT_CHUNK];
+    const int c = blockIdx.x;
+    const int n0 = c * SORT_CHUNK;
+    const int valid = N - n0 < SORT_CHUNK ? N - n0 : SORT_CHUNK;
+    for (int k = threadIdx.x; k < valid; k += 256) dig[k] = (keys[n0 + k] >> shift) & 255u;
+    __syncthreads();
+    const uint32_t b = threadIdx.x;
+    uint32_t cnt = 0;
+    for (int k = 0; k < valid; ++k) cnt += dig[k] == b;
+    hist[(size_t)b * nchunks + c] = cnt;
+}
+
+// in-place exclusive scan of `n` counters by one workgroup
+__global__ __launch_bounds__(256) void sort_scan(uint32_t* __restrict__ hist, int n) {
+    __shared__ uint32_t tsum[256];
+    const int per = (n + 255) / 256;
+    const int lo = threadIdx.x * per;
+    const int hi = lo + per < n ? lo + per : n;
+    uint32_t s = 0;
+    for (int k = lo; k < hi; ++k) s += hist[k];
+    tsum[threadIdx.x] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t run = 0;
+        for (int k = 0; k < 256; ++k) {
+            const uint32_t t = tsum[k];
+            tsum[k] = run;
+            run += t;
+        }
+    }
+    __syncthreads();
+    uint32_t run = tsum[threadIdx.x];
+    for (int k = lo; k < hi; ++k) {
+        const uint32_t t = hist[k];
+        hist[k] = run;
+        run += t;
+    }
+}
+
+__global__ __launch_bounds__(256) void sort_scatter(const uint32_t* __restrict__ keys,
+                                                    const uint32_t* __restrict__ vals, int N, int shift,
+                                                    const uint32_t* __restrict__ base, int nchunks,
+                                                    uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out) {
+    __shared__ uint32_t dig[SORT_CHUNK];
+    __shared__ uint32_t dst[SORT_CHUNK];
+    const int c = blockIdx.x;
+    const int n0 = c * SORT_CHUNK;
+    const int valid = N - n0 < SORT_CHUNK ? N - n0 : SORT_CHUNK;
+    for (int k = threadIdx.x; k < valid; k += 256) dig[k] = (keys[n0 + k] >> shift) & 255u;
+    __syncthreads();
+    const uint32_t b = threadIdx.x;
+    uint32_t pos = base[(size_t)b * nchunks + c];
+    for (int k = 0; k < valid; ++k)
+        if (dig[k] == b) dst[k] = pos++;  // stable: ascending position inside the chunk
+    __syncthreads();
+    for (int k = threadIdx.x; k < valid; k += 256) {
+        const uint32_t o = dst[k];
+        keys_out[o] = keys[n0 + k];
+        vals_out[o] = vals[n0 + k];
+    }
+}
+
+// Ordered segment sums over the sorted (id, row) list.  Workgroup (pc, cc) = one wave; it owns the
+// SEG_CHUNK sorted positions [pc*SEG_CHUNK, ...) and 64*VW columns.  A run of equal ids that lies wholly
+// inside the chunk is added to sum_E directly (this workgroup is its only writer).  A run that continues
+// from the previous chunk goes to first[pc], a run that starts here and continues into the next chunk goes
+// to last[pc]; segment_fixup_kernel adds those pieces in chunk order.
+constexpr int SEG_CHUNK = 256;
+
+template <bool BF16, int VW>
+__global__ __launch_bounds__(64) void segment_sums_kernel(const uint32_t* __restrict__ keys,
+                                                          const uint32_t* __restrict__ vals,
+                                                          const void* __restrict__ G, const float* __restrict__ c,
+                                                          int N, int T, int d, int V, float* __restrict__ sum_E,
+                                                          float* __restrict__ first, float* __restrict__ last) {
+    __shared__ uint32_t skey[SEG_CHUNK + 2];  // [0] = key before the chunk, [1..n] = chunk, [n+1] = key after
+    __shared__ uint32_t srow[SEG_CHUNK];
+    __shared__ float sc[SEG_CHUNK];
+    const int pc = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int p0 = pc * SEG_CHUNK;
+    const int n = N - p0 < SEG_CHUNK ? N - p0 : SEG_CHUNK;
+    const uint32_t NONE = 0xFFFFFFFFu;
+    for (int k = lane; k < n; k += 64) {
+        skey[1 + k] = keys[p0 + k];
+        const uint32_t row = vals[p0 + k];
+        srow[k] = row;
+        sc[k] = c[row / (uint32_t)T];
+    }
+    if (lane == 0) {
+        skey[0] = p0 > 0 ? keys[p0 - 1] : NONE;
+        skey[n + 1] = p0 + n < N ? keys[p0 + n] : NONE;
+    }
+    __syncthreads();
+    const int col = (blockIdx.y * 64 + lane) * VW;
+    if (col >= d) return;
+    float acc[VW];
+#pragma unroll
+    for (int k = 0; k < VW; ++k) acc[k] = 0.f;
+    int seg_start = 0;
+    for (int k0 = 0; k0 < n; k0 += 8) {
+        float g[8][VW];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int k = k0 + u < n ? k0 + u : n - 1;
+            load_vec<BF16, VW>(G, (size_t)srow[k] * d + col, g[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int k = k0 + u;
+            if (k < n) {
+                const uint32_t key = skey[1 + k];
+                const float w = sc[k];
+#pragma unroll
+                for (int e = 0; e < VW; ++e) acc[e] += w * g[u][e];
+                if (skey[2 + k] != key) {  // the run ends at position k
+                    if (key < (uint32_t)V) {
+                        const bool from_prev = seg_start == 0 && skey[0] == key;
+                        float* dst = from_prev ? first + (size_t)pc * d + col : sum_E + (size_t)key * d + col;
+#pragma unroll
+                        for (int e = 0; e < VW; ++e) dst[e] = from_prev ? acc[e] : dst[e] + acc[e];
+                    }
+#pragma unroll
+                    for (int e = 0; e < VW; ++e) acc[e] = 0.f;
+                    seg_start = k + 1;
+                }
+            }
+        }
+    }
+    if (seg_start < n) {
+        // the last run continues into the next chunk (skey[n+1] equals its key)
+        const uint32_t key = skey[n];
+        if (key < (uint32_t)V) {
+            const bool from_prev = seg_start == 0 && skey[0] == key;
+            float* dst = from_prev ? first + (size_t)pc * d + col : last + (size_t)pc * d + col;
+#pragma unroll
+            for (int e = 0; e < VW; ++e) dst[e] = acc[e];
+        }
+    }
+}
+
+// One workgroup per chunk pc whose last run starts in pc and continues into pc+1: add last[pc], then
+// first[q] for q = pc+1, pc+2, ... while the run goes on, and add the total to sum_E[key].
+__global__ __launch_bounds__(256) void segment_fixup_kernel(const uint32_t* __restrict__ keys, int N, int d, int V,
+                                                            int nchunks, const float* __restrict__ first,
+                                                            const float* __restrict__ last,
+                                                            float* __restrict__ sum_E) {
+    const int pc = blockIdx.x;
+    const int pend = (pc + 1) * SEG_CHUNK;  // first position of the next chunk
+    if (pend >= N) return;
+    const uint32_t key = keys[pend - 1];
+    if (key >= (uint32_t)V || keys[pend] != key) return;             // no run crosses this boundary
+    const int p0 = pc * SEG_CHUNK;
+    if (p0 > 0 && keys[p0 - 1] == key && keys[p0] == key) return;    // the run started earlier: not its head
+    for (int col = threadIdx.x; col < d; col += 256) {
+        float acc = last[(size_t)pc * d + col];
+        for (int q = pc + 1; q < nchunks; ++q) {
+            if (keys[q * SEG_CHUNK] != key) break;
+            acc += first[(size_t)q * d + col];
+            const int qend = (q + 1) * SEG_CHUNK;
+            if (qend >= N || keys[qend - 1] != key) break;  // (cheap early exit; the next test would fail too)
+        }
+        sum_E[(size_t)key * d + col] += acc;
+    }
+}
+
+inline int bit_length(uint32_t v) {
+    int b = 0;
+    while (v) {
+        ++b;
+        v >>= 1;
+    }
+    return b;
+}
+
+inline bool vec4_ok(dp_dtype dt, int d, const void* p, const void* q) {
+    if (dt == DP_BF16) return true;  // d % 8 == 0 and 16-byte alignment are checked at the API
+    return d % 4 == 0 && (((uintptr_t)p | (uintptr_t)q) & 15) == 0;
+}
+
+}  // namespace
+
+// ================================================================================================
+// host launchers
+// ================================================================================================
+dp_status dpk_reduce_partials(dp_ctx* ctx, const float* part, int R, size_t stride, size_t n, float* out) {
+    if (n == 0) return DP_OK;
+    if (n % 4 == 0 && stride % 4 == 0 && (((uintptr_t)part | (uintptr_t)out) & 15) == 0) {
+        const size_t n4 = n / 4;
+        hipLaunchKernelGGL(reduce_partials_vec4_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, ctx->stream,
+                           reinterpret_cast<const float4*>(part), R, stride / 4, n4, reinterpret_cast<float4*>(out));
+    } else {
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ctx->stream, part,
+                           R, stride, n, out);
+    }
+    DP_LAUNCH_CHECK(ctx, "reduce_partials");
+    return DP_OK;
+}
+
+template <bool BF16, int VW>
+static dp_status colstat_sqnorms_launch(dp_ctx* ctx, const void* X, const void* G, int B, int T, int d, int use_x,
+                                        int use_1, float* sqnorms) {
+    const int J = (d + 64 * VW - 1) / (64 * VW);
+    float* out = sqnorms;
+    int direct = 1;
+    if (J > 1) {
+        dp_ws_alloc ws(ctx);
+        out = ws.get<float>((size_t)B * J);
+        if (!out) {
+            DP_SET_ERR(ctx, "workspace too small for %d x %d norm partials", B, J);
+            return DP_ERR_WORKSPACE;
+        }
+        direct = 0;
+    }
+    dim3 grid(B, J);
+    if (use_x && use_1)
+        hipLaunchKernelGGL((colstat_sqnorms_kernel<BF16, VW, true, true>), grid, dim3(256), 0, ctx->stream, X, G, T, d, out, J, direct);
+    else if (use_x)
+        hipLaunchKernelGGL((colstat_sqnorms_kernel<BF16, VW, true, false>), grid, dim3(256), 0, ctx->stream, X, G, T, d, out, J, direct);
+    else
+        hipLaunchKernelGGL((colstat_sqnorms_kernel<BF16, VW, false, true>), grid, dim3(256), 0, ctx->stream, X, G, T, d, out, J, direct);
+    DP_LAUNCH_CHECK(ctx, "colstat_sqnorms");
+    if (!direct) return dpk_finish_partials(ctx, out, B, J, sqnorms);
+    return DP_OK;
+}
+
+dp_status dpk_colstat_sqnorms(dp_ctx* ctx, const void* X, const void* G, dp_dtype dt, int B, int T, int d, int use_x,
+                              int use_1, float* sqnorms) {
+    if (B == 0 || T == 0 || d == 0 || (!use_x && !use_1)) return DP_OK;
+    if (dt == DP_BF16) return colstat_sqnorms_launch<true, 4>(ctx, X, G, B, T, d, use_x, use_1, sqnorms);
+    if (vec4_ok(dt, d, use_x ? X : G, G)) return colstat_sqnorms_launch<false, 4>(ctx, X, G, B, T, d, use_x, use_1, sqnorms);
+    return colstat_sqnorms_launch<false, 1>(ctx, X, G, B, T, d, use_x, use_1, sqnorms);
+}
+
+template <bool BF16, int VW>
+static dp_status colstat_sums_launch(dp_ctx* ctx, const void* X, const void* G, int B, int T, int d, const float* c,
+                                     float* out_x, float* out_1) {
+    const long nrows = (long)B * T;
+    const int J = (d + 64 * VW - 1) / (64 * VW);
+    long R = 2048 / J;
+    if (R < 1) R = 1;
+    const long maxR = (nrows + 63) / 64;
+    if (R > maxR) R = maxR;
+    const int rows_per = (int)((nrows + R - 1) / R);
+    R = (nrows + rows_per - 1) / rows_per;
+    dp_ws_alloc ws(ctx);
+    float* part = ws.get<float>((size_t)R * 2 * d);
+    if (!part) {
+        DP_SET_ERR(ctx, "workspace too small for column-sum partials (%ld x 2 x %d floats)", R, d);
+        return DP_ERR_WORKSPACE;
+    }
+    dim3 grid((unsigned)R, J);
+    if (out_x)
+        hipLaunchKernelGGL((colstat_sums_kernel<BF16, VW, true>), grid, dim3(256), 0, ctx->stream, X, G, c, T, d, nrows, rows_per, part);
+    else
+        hipLaunchKernelGGL((colstat_sums_kernel<BF16, VW, false>), grid, dim3(256), 0, ctx->stream, X, G, c, T, d, nrows, rows_per, part);
+    DP_LAUNCH_CHECK(ctx, "colstat_sums");
+    dp_status st = DP_OK;
+    if (out_x) st = dpk_reduce_partials(ctx, part, (int)R, (size_t)2 * d, d, out_x);
+    if (st == DP_OK && out_1) st = dpk_reduce_partials(ctx, part + d, (int)R, (size_t)2 * d, d, out_1);
+    return st;
+}
+
+dp_status dpk_colstat_sums(dp_ctx* ctx, const void* X, const void* G, dp_dtype dt, int B, int T, int d, const float* c,
+                           float* out_x, float* out_1) {
+    if (B == 0 || T == 0 || d == 0 || (!out_x && !out_1)) return DP_OK;
+    if (dt == DP_BF16) return colstat_sums_launch<true, 4>(ctx, X, G, B, T, d, c, out_x, out_1);
+    if (vec4_ok(dt, d, out_x ? X : G, G)) return colstat_sums_launch<false, 4>(ctx, X, G, B, T, d, c, out_x, out_1);
+    return colstat_sums_launch<false, 1>(ctx, X, G, B, T, d, c, out_x, out_1);
+}
+
+template <bool BF16, int VW>
+static dp_status embedding_sqnorms_launch(dp_ctx* ctx, const int32_t* ids, const void* G, int B, int T, int d, int V,
+                                          int distinct, float* sqnorms) {
+    const int J = (d + 64 * VW - 1) / (64 * VW);
+    float* out = sqnorms;
+    int direct = 1;
+    if (J > 1) {
+        dp_ws_alloc ws(ctx);
+        out = ws.get<float>((size_t)B * J);
+        if (!out) {
+            DP_SET_ERR(ctx, "workspace too small for %d x %d norm partials", B, J);
+            return DP_ERR_WORKSPACE;
+        }
+        direct = 0;
+    }
+    dim3 grid(B, J);
+    const size_t lds = (size_t)2 * T * sizeof(int32_t);
+    if (distinct)
+        hipLaunchKernelGGL((embedding_sqnorms_kernel<BF16, VW, true>), grid, dim3(64), lds, ctx->stream, ids, G, T, d, V, out, J, direct, ctx->err_word);
+    else
+        hipLaunchKernelGGL((embedding_sqnorms_kernel<BF16, VW, false>), grid, dim3(64), lds, ctx->stream, ids, G, T, d, V, out, J, direct, ctx->err_word);
+    DP_LAUNCH_CHECK(ctx, "embedding_sqnorms");
+    if (!direct) return dpk_finish_partials(ctx, out, B, J, sqnorms);
+    return DP_OK;
+}
+
+dp_status dpk_embedding_sqnorms(dp_ctx* ctx, const int32_t* ids, const void* G, dp_dtype dt, int B, int T, int d, int V,
+                                int distinct, float* sqnorms) {
+    if (B == 0 || T == 0 || d == 0) return DP_OK;
+    if (T > 4096) {
+        DP_SET_ERR(ctx, "dp_sqnorms_embedding: T = %d exceeds the supported maximum of 4096", T);
+        return DP_ERR_SHAPE;
+    }
+    if (dt == DP_BF16) return embedding_sqnorms_launch<true, 4>(ctx, ids, G, B, T, d, V, distinct, sqnorms);
+    if (vec4_ok(dt, d, G, G)) return embedding_sqnorms_launch<false, 4>(ctx, ids, G, B, T, d, V, distinct, sqnorms);
+    return embedding_sqnorms_launch<false, 1>(ctx, ids, G, B, T, d, V, distinct, sqnorms);
+}
+
+template <bool BF16, int VW>
+static dp_status embedding_sums_launch(dp_ctx* ctx, const int32_t* ids, const void* G, int B, int T, int d, int V,
+                                       const float* c, float* sum_E) {
+    const long Nl = (long)B * T;
+    if (Nl > 0x7FFFFFFFl - SORT_CHUNK) {
+        DP_SET_ERR(ctx, "dp_clip_accumulate_embedding: B*T too large");
+        return DP_ERR_SHAPE;
+    }
+    const int N = (int)Nl;
+    const int nsort = (N + SORT_CHUNK - 1) / SORT_CHUNK;
+    const int nseg = (N + SEG_CHUNK - 1) / SEG_CHUNK;
+    dp_ws_alloc ws(ctx);
+    uint32_t* k0 = ws.get<uint32_t>(N);
+    uint32_t* k1 = ws.get<uint32_t>(N);
+    uint32_t* v0 = ws.get<uint32_t>(N);
+    uint32_t* v1 = ws.get<uint32_t>(N);
+    uint32_t* hist = ws.get<uint32_t>((size_t)256 * nsort);
+    float* first = ws.get<float>((size_t)nseg * d);
+    float* last = ws.get<float>((size_t)nseg * d);
+    if (!k0 || !k1 || !v0 || !v1 || !hist || !first || !last) {
+        DP_SET_ERR(ctx, "workspace too small for the embedding sort of %d tokens", N);
+        return DP_ERR_WORKSPACE;
+    }
+    hipLaunchKernelGGL(sort_keys_init, dim3((N + 255) / 256), dim3(256), 0, ctx->stream, ids, N, V, k0, v0, ctx->err_word);
+    DP_LAUNCH_CHECK(ctx, "sort_keys_init");
+    const int bits = bit_length((uint32_t)V);  // the sentinel V itself must be representable
+    for (int shift = 0; shift < bits; shift += 8) {
+        hipLaunchKernelGGL(sort_hist, dim3(nsort), dim3(256), 0, ctx->stream, k0, N, shift, hist, nsort);
+        hipLaunchKernelGGL(sort_scan, dim3(1), dim3(256), 0, ctx->stream, hist, 256 * nsort);
+        hipLaunchKernelGGL(sort_scatter, dim3(nsort), dim3(256), 0, ctx->stream, k0, v0, N, shift, hist, nsort, k1, v1);
+        DP_LAUNCH_CHECK(ctx, "radix sort pass");
+        uint32_t* t = k0; k0 = k1; k1 = t;
+        t = v0; v0 = v1; v1 = t;
+    }
+    const int J = (d + 64 * VW - 1) / (64 * VW);
+    hipLaunchKernelGGL((segment_sums_kernel<BF16, VW>), dim3(nseg, J), dim3(64), 0, ctx->stream, k0, v0, G, c, N, T, d, V, sum_E, first, last);
+    DP_LAUNCH_CHECK(ctx, "segment_sums");
+    if (nseg > 1) {
+        hipLaunchKernelGGL(segment_fixup_kernel, dim3(nseg - 1), dim3(256), 0, ctx->stream, k0, N, d, V, nseg, first, last, sum_E);
+        DP_LAUNCH_CHECK(ctx, "segment_fixup");
+    }
+    return DP_OK;
+}
+
+dp_status dpk_embedding_sums(dp_ctx* ctx, const int32_t* ids, const void* G, dp_dtype dt, int B, int T, int d, int V,
+                             const float* c, float* sum_E) {
+    if (B == 0 || T == 0 || d == 0) return DP_OK;
+    if (dt == DP_BF16) return embedding_sums_launch<true, 4>(ctx, ids, G, B, T, d, V, c, sum_E);
+    if (vec4_ok(dt, d, G, G)) return embedding_sums_launch<false, 4>(ctx, ids, G, B, T, d, V, c, sum_E);
+    return embedding_sums_launch<false, 1>(ctx, ids, G, B, T, d, V, c, sum_E);
+}

@@ -1,0 +1,287 @@
+// Noise + Adam-with-decoupled-weight-decay streaming kernel (Algorithm 1, g_t line to theta_t line),
+// the counter-based Philox4x32-10 generator it draws from, and small utility kernels.
+//
+// Roofline: HBM.  Per parameter the kernel reads theta, m, v, sum (16 B) and writes theta, m, v (12 B),
+// plus 4 B when it also clears the sum: 28 (32) algorithmic bytes.  One thread owns one Philox block,
+// i.e. four consecutive elements, so every access is a 16-byte vector and a wave covers 1 KiB per array.
+#include "dp_common.h"
+
+namespace {
+
+constexpr uint32_t PHILOX_M0 = 0xD2511F53u;
+constexpr uint32_t PHILOX_M1 = 0xCD9E8D57u;
+constexpr uint32_t PHILOX_W0 = 0x9E3779B9u;
+constexpr uint32_t PHILOX_W1 = 0xBB67AE85u;
+
+struct u32x4 {
+    uint32_t x, y, z, w;
+};
+
+// Philox-4x32 with ten rounds (Salmon, Moraes, Dror, Shaw, SC'11): each round multiplies words 0 and 2 by
+// fixed odd constants, keeps the low halves as words 3 and 1 and xors the high halves with words 3 / 1 and
+// the round key; the key advances by Weyl constants between rounds.
+__device__ __forceinline__ u32x4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                               uint32_t k1) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(PHILOX_M0, c0), lo0 = PHILOX_M0 * c0;
+        const uint32_t hi1 = __umulhi(PHILOX_M1, c2), lo1 = PHILOX_M1 * c2;
+        const uint32_t n0 = hi1 ^ c1 ^ k0;
+        const uint32_t n2 = hi0 ^ c3 ^ k1;
+        c0 = n0;
+        c1 = lo1;
+        c2 = n2;
+        c3 = lo0;
+        k0 += PHILOX_W0;
+        k1 += PHILOX_W1;
+    }
+    return {c0, c1, c2, c3};
+}
+
+__device__ __forceinline__ u32x4 philox_block(uint64_t block, uint64_t seed, uint64_t step) {
+    return philox4x32_10((uint32_t)block, (uint32_t)(block >> 32), (uint32_t)step, (uint32_t)(step >> 32),
+                         (uint32_t)seed, (uint32_t)(seed >> 32));
+}
+
+// 23-bit uniform in (0,1): ((r >> 9) + 1/2) * 2^-23, exact in fp32.
+__device__ __forceinline__ float u01(uint32_t r) { return ((float)(r >> 9) + 0.5f) * 1.1920928955078125e-07f; }
+
+// Box-Muller on one word pair: (rho cos(2 pi u1), rho sin(2 pi u1)), rho = sqrt(-2 ln u0).
+__device__ __forceinline__ void box_muller(uint32_t r0, uint32_t r1, float& z0, float& z1) {
+    const float rho = sqrtf(-2.0f * logf(u01(r0)));
+    float s, c;
+    sincospif(2.0f * u01(r1), &s, &c);
+    z0 = rho * c;
+    z1 = rho * s;
+}
+
+__device__ __forceinline__ void block_normals(uint64_t block, uint64_t seed, uint64_t step, float z[4]) {
+    const u32x4 r = philox_block(block, seed, step);
+    box_muller(r.x, r.y, z[0], z[1]);
+    box_muller(r.z, r.w, z[2], z[3]);
+}
+
+struct AdamArgs {
+    float noise_scale;  // sigma * C
+    float inv_batch;    // 1 / |B_t|
+    float beta1, beta2;
+    float inv_bc1, inv_bc2;  // 1 / (1 - beta^t)
+    float lr, eps, wd;
+};
+
+__device__ __forceinline__ void adam_elem(float& th, float& m, float& v, float s, float z, const AdamArgs& a) {
+    const float g = (s + a.noise_scale * z) * a.inv_batch;
+    m = a.beta1 * m + (1.0f - a.beta1) * g;
+    v = a.beta2 * v + (1.0f - a.beta2) * (g * g);
+    const float mh = m * a.inv_bc1;
+    const float vh = v * a.inv_bc2;
+    th = th - a.lr * (mh / (sqrtf(vh) + a.eps) + a.wd * th);
+}
+
+// Fast path: elem_offset % 4 == 0 and 16-byte aligned pointers.  Thread i owns local elements 4i .. 4i+3.
+template <bool NOISE, bool ZERO>
+__global__ __launch_bounds__(256) void noise_adamw_vec4(float* __restrict__ params, float* __restrict__ m,
+                                                        float* __restrict__ v, float* __restrict__ sum,
+                                                        uint64_t nblocks4, uint64_t block0, uint64_t seed,
+                                                        uint64_t step, AdamArgs a) {
+    const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= nblocks4) return;
+    float4 th = reinterpret_cast<float4*>(params)[i];
+    float4 mm = reinterpret_cast<float4*>(m)[i];
+    float4 vv = reinterpret_cast<float4*>(v)[i];
+    const float4 ss = reinterpret_cast<const float4*>(sum)[i];
+    float z[4] = {0.f, 0.f, 0.f, 0.f};
+    if (NOISE) block_normals(block0 + i, seed, step, z);
+    adam_elem(th.x, mm.x, vv.x, ss.x, z[0], a);
+    adam_elem(th.y, mm.y, vv.y, ss.y, z[1], a);
+    adam_elem(th.z, mm.z, vv.z, ss.z, z[2], a);
+    adam_elem(th.w, mm.w, vv.w, ss.w, z[3], a);
+    reinterpret_cast<float4*>(params)[i] = th;
+    reinterpret_cast<float4*>(m)[i] = mm;
+    reinterpret_cast<float4*>(v)[i] = vv;
+    if (ZERO) reinterpret_cast<float4*>(sum)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+// General path: any offset / alignment, and the ragged tail of the fast path.  Thread i owns the Philox
+// block first_block + i and touches only those of its four elements that fall inside [e_lo, e_hi).
+// `base_elem` is the global index of params[0].
+template <bool NOISE, bool ZERO>
+__global__ __launch_bounds__(256) void noise_adamw_scalar(float* __restrict__ params, float* __restrict__ m,
+                                                          float* __restrict__ v, float* __restrict__ sum,
+                                                          uint64_t base_elem, uint64_t e_lo, uint64_t e_hi,
+                                                          uint64_t first_block, uint64_t nblocks, uint64_t seed,
+                                                          uint64_t step, AdamArgs a) {
+    const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= nblocks) return;
+    const uint64_t blk = first_block + i;
+    float z[4] = {0.f, 0.f, 0.f, 0.f};
+    if (NOISE) block_normals(blk, seed, step, z);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint64_t e = blk * 4 + k;
+        if (e >= e_lo && e < e_hi) {
+            const uint64_t j = e - base_elem;
+            float th = params[j], mm = m[j], vv = v[j];
+            adam_elem(th, mm, vv, sum[j], z[k], a);
+            params[j] = th;
+            m[j] = mm;
+            v[j] = vv;
+            if (ZERO) sum[j] = 0.f;
+        }
+    }
+}
+
+// mode 0: raw words, mode 1: normals
+template <int MODE>
+__global__ __launch_bounds__(256) void philox_dump(void* __restrict__ out, uint64_t off, uint64_t n,
+                                                   uint64_t first_block, uint64_t nblocks, uint64_t seed,
+                                                   uint64_t step) {
+    const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= nblocks) return;
+    const uint64_t blk = first_block + i;
+    uint32_t w[4];
+    float z[4];
+    if (MODE == 0) {
+        const u32x4 r = philox_block(blk, seed, step);
+        w[0] = r.x; w[1] = r.y; w[2] = r.z; w[3] = r.w;
+    } else {
+        block_normals(blk, seed, step, z);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint64_t e = blk * 4 + k;
+        if (e >= off && e < off + n) {
+            if (MODE == 0) reinterpret_cast<uint32_t*>(out)[e - off] = w[k];
+            else reinterpret_cast<float*>(out)[e - off] = z[k];
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void zero_f32_kernel(float* __restrict__ p, uint64_t n) {
+    const uint64_t i = ((uint64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i + 4 <= n && (reinterpret_cast<uintptr_t>(p) & 15) == 0) {
+        *reinterpret_cast<float4*>(p + i) = make_float4(0.f, 0.f, 0.f, 0.f);
+    } else {
+        for (uint64_t k = i; k < n && k < i + 4; ++k) p[k] = 0.f;
+    }
+}
+
+// sqnorms[i] += partial[i*J + 0] + ... + partial[i*J + J-1], in index order.
+__global__ __launch_bounds__(256) void finish_partials_kernel(const float* __restrict__ partial, int B, int J,
+                                                              float* __restrict__ sqnorms) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= B) return;
+    float t = 0.f;
+    for (int j = 0; j < J; ++j) t += partial[(size_t)i * J + j];
+    sqnorms[i] += t;
+}
+
+__global__ __launch_bounds__(256) void clip_factors_kernel(const float* __restrict__ sqnorms, int B, float C,
+                                                           float* __restrict__ c) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < B) c[i] = dp_clip_factor(sqnorms[i], C);
+}
+
+template <bool NOISE, bool ZERO>
+dp_status launch_adamw(dp_ctx* ctx, float* params, float* m, float* v, float* sum, uint64_t n, uint64_t off,
+                       uint64_t seed, uint64_t step, const AdamArgs& a) {
+    const bool aligned = (off % 4 == 0) && (((uintptr_t)params | (uintptr_t)m | (uintptr_t)v | (uintptr_t)sum) & 15) == 0;
+    uint64_t done = 0;
+    if (aligned && n >= 4) {
+        const uint64_t nb4 = n / 4;
+        const uint64_t grid = (nb4 + 255) / 256;
+        if (grid > 0x7FFFFFFFull) {
+            DP_SET_ERR(ctx, "dp_noise_adamw: slice too large for one launch");
+            return DP_ERR_SHAPE;
+        }
+        hipLaunchKernelGGL((noise_adamw_vec4<NOISE, ZERO>), dim3((unsigned)grid), dim3(256), 0, ctx->stream, params, m,
+                           v, sum, nb4, off / 4, seed, step, a);
+        DP_LAUNCH_CHECK(ctx, "noise_adamw_vec4");
+        done = nb4 * 4;
+    }
+    if (done < n) {
+        const uint64_t e_lo = off + done, e_hi = off + n;
+        const uint64_t first = e_lo / 4, last = (e_hi - 1) / 4;
+        const uint64_t nblocks = last - first + 1;
+        const uint64_t grid = (nblocks + 255) / 256;
+        if (grid > 0x7FFFFFFFull) {
+            DP_SET_ERR(ctx, "dp_noise_adamw: slice too large for one launch");
+            return DP_ERR_SHAPE;
+        }
+        hipLaunchKernelGGL((noise_adamw_scalar<NOISE, ZERO>), dim3((unsigned)grid), dim3(256), 0, ctx->stream, params,
+                           m, v, sum, off, e_lo, e_hi, first, nblocks, seed, step, a);
+        DP_LAUNCH_CHECK(ctx, "noise_adamw_scalar");
+    }
+    return DP_OK;
+}
+
+}  // namespace
+
+dp_status dpk_noise_adamw(dp_ctx* ctx, float* params, float* m, float* v, float* sum, uint64_t n, uint64_t off,
+                          float sigma, float C, uint64_t seed, uint64_t step, uint64_t batch, float lr, float b1,
+                          float b2, float eps, float wd, int zero_sum) {
+    if (n == 0) return DP_OK;
+    AdamArgs a;
+    a.noise_scale = sigma * C;
+    a.inv_batch = (float)(1.0 / (double)batch);
+    a.beta1 = b1;
+    a.beta2 = b2;
+    a.inv_bc1 = (float)(1.0 / (1.0 - pow((double)b1, (double)step)));
+    a.inv_bc2 = (float)(1.0 / (1.0 - pow((double)b2, (double)step)));
+    a.lr = lr;
+    a.eps = eps;
+    a.wd = wd;
+    const bool noise = sigma != 0.f;
+    if (noise && zero_sum) return launch_adamw<true, true>(ctx, params, m, v, sum, n, off, seed, step, a);
+    if (noise) return launch_adamw<true, false>(ctx, params, m, v, sum, n, off, seed, step, a);
+    if (zero_sum) return launch_adamw<false, true>(ctx, params, m, v, sum, n, off, seed, step, a);
+    return launch_adamw<false, false>(ctx, params, m, v, sum, n, off, seed, step, a);
+}
+
+template <int MODE>
+static dp_status philox_dump_launch(dp_ctx* ctx, void* out, uint64_t n, uint64_t off, uint64_t seed, uint64_t step) {
+    if (n == 0) return DP_OK;
+    const uint64_t first = off / 4, last = (off + n - 1) / 4;
+    const uint64_t nblocks = last - first + 1;
+    const uint64_t grid = (nblocks + 255) / 256;
+    if (grid > 0x7FFFFFFFull) {
+        DP_SET_ERR(ctx, "philox dump: too many elements for one launch");
+        return DP_ERR_SHAPE;
+    }
+    hipLaunchKernelGGL((philox_dump<MODE>), dim3((unsigned)grid), dim3(256), 0, ctx->stream, out, off, n, first,
+                       nblocks, seed, step);
+    DP_LAUNCH_CHECK(ctx, "philox_dump");
+    return DP_OK;
+}
+
+dp_status dpk_philox_u32(dp_ctx* ctx, uint32_t* out, uint64_t n, uint64_t off, uint64_t seed, uint64_t step) {
+    return philox_dump_launch<0>(ctx, out, n, off, seed, step);
+}
+dp_status dpk_normal_f32(dp_ctx* ctx, float* out, uint64_t n, uint64_t off, uint64_t seed, uint64_t step) {
+    return philox_dump_launch<1>(ctx, out, n, off, seed, step);
+}
+
+dp_status dpk_zero_f32(dp_ctx* ctx, float* p, uint64_t n) {
+    if (n == 0) return DP_OK;
+    const uint64_t grid = (n + 1023) / 1024;
+    if (grid > 0x7FFFFFFFull) {
+        DP_SET_ERR(ctx, "dp_zero_f32: too many elements for one launch");
+        return DP_ERR_SHAPE;
+    }
+    hipLaunchKernelGGL(zero_f32_kernel, dim3((unsigned)grid), dim3(256), 0, ctx->stream, p, n);
+    DP_LAUNCH_CHECK(ctx, "zero_f32");
+    return DP_OK;
+}
+
+dp_status dpk_finish_partials(dp_ctx* ctx, const float* partial, int B, int J, float* sqnorms) {
+    hipLaunchKernelGGL(finish_partials_kernel, dim3((B + 255) / 256), dim3(256), 0, ctx->stream, partial, B, J,
+                       sqnorms);
+    DP_LAUNCH_CHECK(ctx, "finish_partials");
+    return DP_OK;
+}
+
+dp_status dpk_clip_factors(dp_ctx* ctx, const float* sqnorms, int B, float C, float* c) {
+    hipLaunchKernelGGL(clip_factors_kernel, dim3((B + 255) / 256), dim3(256), 0, ctx->stream, sqnorms, B, C, c);
+    DP_LAUNCH_CHECK(ctx, "clip_factors");
+    return DP_OK;
+}

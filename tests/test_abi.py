@@ -1,0 +1,81 @@
+"""CPU-side checks of the boundary: the library loads, exports every symbol the header declares, the
+Python binding declares the same set, and the host-only entry points behave."""
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2108_01624_amd as pkg
+    from paper_2108_01624_amd import build
+
+    if not os.path.exists(build.LIB_PATH):
+        build.build_library()
+    return pkg.load_library()
+
+
+def _declared():
+    src = open(os.path.join(ROOT, "include", "dpclip.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(dp_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_header_symbols_are_exported(lib):
+    names = _declared()
+    assert len(names) >= 17
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in dpclip.h but not exported"
+
+
+def test_binding_matches_header(lib):
+    from paper_2108_01624_amd import binding
+
+    assert sorted(binding.SIGNATURES) == _declared()
+    for n in _declared():
+        assert callable(getattr(binding, n)), n
+
+
+def test_status_strings(lib):
+    from paper_2108_01624_amd import binding
+
+    for code, name in binding.STATUS_NAMES.items():
+        assert binding.dp_status_str(code) == name
+    assert binding.dp_status_str(-99) == "DP_ERR_UNKNOWN"
+    assert binding.dp_last_error(None) == "no context"
+
+
+def test_choose_path_rule(lib):
+    import paper_2108_01624_amd as pkg
+
+    # Gram iff (T+1)/2 * (d_in + d_out) <= d_in * d_out (symmetric Gram flops against materialisation flops)
+    assert pkg.dp_choose_path(128, 1024, 1024) == pkg.DP_PATH_GRAM
+    assert pkg.dp_choose_path(128, 1024, 4096) == pkg.DP_PATH_GRAM
+    assert pkg.dp_choose_path(128, 768, 768) == pkg.DP_PATH_GRAM
+    assert pkg.dp_choose_path(512, 1024, 1024) == pkg.DP_PATH_GRAM   # the flop tie goes to the symmetric Gram
+    assert pkg.dp_choose_path(512, 1024, 4096) == pkg.DP_PATH_GRAM
+    assert pkg.dp_choose_path(512, 128, 128) == pkg.DP_PATH_MATERIALISE
+    assert pkg.dp_choose_path(128, 64, 64) == pkg.DP_PATH_MATERIALISE
+    assert pkg.dp_choose_path(16, 64, 64, pkg.DP_F32) == pkg.DP_PATH_GRAM
+    with pytest.raises(pkg.DpError):
+        pkg.dp_choose_path(-1, 4, 4)
+    with pytest.raises(pkg.DpError):
+        pkg.dp_choose_path(1, 4, 4, 5)
+
+
+def test_null_context_is_rejected_without_a_gpu(lib):
+    assert lib.dp_sync(None) == -1
+    assert lib.dp_destroy(None) == -1
+    assert lib.dp_zero_f32(None, None, 0) == -1
+    assert lib.dp_create(None, None, 0) == -1
+
+
+def test_manifest_counts():
+    import dp_synth as syn
+
+    assert syn.manifest_param_count(syn.CONFIGS["C1"]["manifest"]()) == 4096
+    assert syn.manifest_param_count(syn.CONFIGS["C2"]["manifest"]()) == 85_054_464
+    assert syn.manifest_param_count(syn.CONFIGS["C3"]["manifest"]()) == 334_088_192

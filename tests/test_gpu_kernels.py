@@ -1,0 +1,479 @@
+"""GPU parity tests: every entry point of the C ABI against the CPU oracle, element by element, on the
+same seeded inputs, at sizes that span several tiles and a ragged tail.
+
+Tolerances (derived in the design notes): Philox words and embedding indexing bit-exact; fp32 inputs
+rel 1e-5 on norms and sums; bf16 inputs (fp32 accumulation) rel 2e-2, with the observed error printed
+so that a regression to low-precision accumulation (~1e-2) is visible long before the bound."""
+import numpy as np
+import pytest
+import torch
+
+import dp_synth as syn
+from oracle import dp_oracle as orc
+
+from gpu_util import DEV, assert_norms_close, assert_sums_close, bf16_dev, f32_dev, host, to_dev
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-5
+TOL_BF16 = 2e-2
+
+
+def gen(shape, std, seed, dtype):
+    return syn.normal_bf16_bits(shape, std, seed) if dtype == "bf16" else syn.normal_f32(shape, std, seed)
+
+
+def tol_of(dtype):
+    return TOL_BF16 if dtype == "bf16" else TOL_F32
+
+
+# ------------------------------------------------------------------------------------------------
+# Philox stream and normals
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("off,n,seed,step", [(0, 4096, 0, 1), (1, 1000, 1234, 1), (5, 3, 7, 2), (4 * 2 ** 32 - 6, 50, 99, 3),
+                                             (123456789012, 777, 2 ** 63 + 11, 2 ** 32 + 9), (0, 1, 5, 1), (3, 1, 5, 1)])
+def test_philox_words_bit_exact(dp, off, n, seed, step):
+    import paper_2108_01624_amd as pkg
+
+    out = torch.zeros(n, dtype=torch.int32, device=DEV)
+    dp.philox_u32(out, off, seed, step)
+    dp.sync()
+    got = host(out).view(np.uint32)
+    np.testing.assert_array_equal(got, orc.philox_u32(n, off, seed, step))
+
+
+def test_philox_empty(dp):
+    out = torch.zeros(4, dtype=torch.int32, device=DEV)
+    dp.philox_u32(out, 0, 1, 1, n=0)
+    dp.sync()
+    assert host(out).tolist() == [0, 0, 0, 0]
+
+
+@pytest.mark.parametrize("off,n", [(0, 1 << 16), (3, 1001)])
+def test_normals_match_oracle(dp, off, n):
+    out = torch.zeros(n, device=DEV)
+    dp.normal_f32(out, off, 1234, 1)
+    dp.sync()
+    z = host(out).astype(np.float64)
+    ref = orc.normals(n, off, 1234, 1)
+    # fp32 log / sqrt / sincos against fp64: |z| <= 5.8, a few ulp of fp32
+    assert np.abs(z - ref).max() < 1e-5, np.abs(z - ref).max()
+
+
+def test_normals_full_u_range(dp):
+    """Scan many blocks and check the extreme uniforms (u near 0 and near 1), where log is most delicate."""
+    n = 1 << 22
+    out = torch.zeros(n, device=DEV)
+    dp.normal_f32(out, 0, 42, 1)
+    dp.sync()
+    z = host(out).astype(np.float64)
+    ref = orc.normals(n, 0, 42, 1)
+    assert np.abs(z - ref).max() < 1e-5
+    assert np.isfinite(z).all()
+
+
+# ------------------------------------------------------------------------------------------------
+# noise + AdamW
+# ------------------------------------------------------------------------------------------------
+def _adam_case(dp, n, off, sigma, seed, step, steps=1, zero_sum=False, batch=32, lr=1e-3, b1=0.9, b2=0.999, wd=0.01, C=1.0,
+               misalign=0):
+    th0 = syn.normal_f32((n,), 0.02, 50)
+    pad = misalign
+    th = f32_dev(np.concatenate([np.zeros(pad, np.float32), th0]))[pad:]
+    m = torch.zeros(n + pad, device=DEV)[pad:]
+    v = torch.zeros(n + pad, device=DEV)[pad:]
+    r_th, r_m, r_v = th0.astype(np.float64), np.zeros(n), np.zeros(n)
+    for k in range(steps):
+        S = syn.normal_f32((n,), 3.0, 60 + k)
+        S_d = f32_dev(np.concatenate([np.zeros(pad, np.float32), S]))[pad:]
+        dp.noise_adamw(th, m, v, S_d, n=n, elem_offset=off, sigma=sigma, C=C, seed=seed, step=step + k, batch_size=batch,
+                       lr=lr, beta1=b1, beta2=b2, eps=1e-11, weight_decay=wd, zero_sum=zero_sum)
+        dp.sync()
+        r_th, r_m, r_v, g = orc.noise_adamw(r_th.astype(np.float32), r_m.astype(np.float32), r_v.astype(np.float32), S,
+                                            elem_offset=off, sigma=sigma, C=C, seed=seed, step=step + k, batch_size=batch,
+                                            lr=lr, beta1=b1, beta2=b2, eps=1e-11, weight_decay=wd)
+        # the oracle restarts each step from the fp32 state the GPU holds, so errors do not compound
+        gm, gv, gth = host(m).astype(np.float64), host(v).astype(np.float64), host(th).astype(np.float64)
+        np.testing.assert_allclose(gm, r_m, rtol=1e-5, atol=1e-6 * np.abs(r_m).max())
+        np.testing.assert_allclose(gv, r_v, rtol=2e-5, atol=1e-6 * np.abs(r_v).max())
+        # the Adam term is bounded by lr and ill-conditioned where g ~ 0
+        assert np.all(np.abs(gth - r_th) <= 1e-5 * np.abs(r_th) + 1e-3 * lr), np.abs(gth - r_th).max()
+        if zero_sum:
+            assert not host(S_d).any()
+        else:
+            np.testing.assert_array_equal(host(S_d), S)
+        r_th, r_m, r_v = gth, gm, gv
+    return gth
+
+
+def test_adamw_c1_sigma0(dp):
+    _adam_case(dp, 64 * 64, 0, 0.0, 0, 1)
+
+
+def test_adamw_c1_sigma1_seed0(dp):
+    _adam_case(dp, 64 * 64, 0, 1.0, 0, 1)
+
+
+@pytest.mark.parametrize("n,off,misalign", [(1, 0, 0), (3, 0, 0), (4099, 0, 0), (1000, 5, 0), (1000, 4, 1), (7, 2, 3),
+                                            (100003, 8, 0)])
+def test_adamw_ragged_and_offset(dp, n, off, misalign):
+    _adam_case(dp, n, off, 0.6, 1234, 1, misalign=misalign)
+
+
+def test_adamw_multi_step_and_zero_sum(dp):
+    _adam_case(dp, 5000, 0, 0.6, 1234, 1, steps=4, zero_sum=True, b1=0.75, b2=0.9, wd=1.0, lr=6.0902e-4, C=3.2429e-3)
+
+
+def test_adamw_slicing_invariance(dp):
+    """The noise depends on the global element index only: updating two slices equals updating the whole."""
+    n = 10007
+    th0 = syn.normal_f32((n,), 0.02, 70)
+    S = syn.normal_f32((n,), 3.0, 71)
+    kw = dict(sigma=0.6, C=1.0, seed=9, step=3, batch_size=64, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-11, weight_decay=0.5)
+    res = []
+    for cut in (None, 4000, 4001):
+        th, m, v, S_d = f32_dev(th0), torch.zeros(n, device=DEV), torch.zeros(n, device=DEV), f32_dev(S)
+        if cut is None:
+            dp.noise_adamw(th, m, v, S_d, elem_offset=100, **kw)
+        else:
+            dp.noise_adamw(th[:cut], m[:cut], v[:cut], S_d[:cut], n=cut, elem_offset=100, **kw)
+            dp.noise_adamw(th[cut:], m[cut:], v[cut:], S_d[cut:], n=n - cut, elem_offset=100 + cut, **kw)
+        dp.sync()
+        res.append((host(th), host(m), host(v)))
+    for r in res[1:]:
+        for a, b in zip(res[0], r):
+            np.testing.assert_array_equal(a, b)
+
+
+def test_adamw_untouched_row_is_pure_decay(dp):
+    n = 256
+    th0 = syn.normal_f32((n,), 0.02, 72)
+    th, m, v, S = f32_dev(th0), torch.zeros(n, device=DEV), torch.zeros(n, device=DEV), torch.zeros(n, device=DEV)
+    dp.noise_adamw(th, m, v, S, sigma=0.0, C=1.0, seed=0, step=1, batch_size=8, lr=1e-3, beta1=0.9, beta2=0.999,
+                   eps=1e-11, weight_decay=0.5)
+    dp.sync()
+    np.testing.assert_allclose(host(th), th0.astype(np.float64) * (1 - float(np.float32(1e-3)) * 0.5), rtol=2e-7)
+    assert not host(m).any() and not host(v).any()
+
+
+# ------------------------------------------------------------------------------------------------
+# dense layers: norms
+# ------------------------------------------------------------------------------------------------
+DENSE_SHAPES = [
+    # dtype, B, T, d_in, d_out
+    ("f32", 32, 16, 64, 64),      # the single-dense-layer workload
+    ("f32", 3, 5, 7, 6),          # ragged everything
+    ("f32", 2, 33, 20, 12),
+    ("bf16", 5, 128, 256, 384),   # one Gram block, big GEMM tiles
+    ("bf16", 3, 100, 72, 136),    # ragged T and widths
+    ("bf16", 2, 16, 64, 64),      # T far below one block
+    ("bf16", 9, 300, 264, 128),   # 3 x 3 Gram blocks with a ragged last block, 9 examples over 8 XCD lanes
+    ("bf16", 2, 512, 128, 1024),  # 4 x 4 Gram blocks
+    ("bf16", 1, 1, 8, 8),         # T = 1
+]
+
+
+@pytest.mark.parametrize("dtype,B,T,d_in,d_out", DENSE_SHAPES)
+@pytest.mark.parametrize("has_bias", [False, True])
+def test_sqnorms_dense_paths(dp, dtype, B, T, d_in, d_out, has_bias):
+    import paper_2108_01624_amd as pkg
+
+    A = gen((B, T, d_in), 1.0, 100, dtype)
+    G = gen((B, T, d_out), 0.1, 101, dtype)
+    ref = orc.sqnorms_dense(A, G, has_bias)
+    A_d, G_d = to_dev(A), to_dev(G)
+    errs = {}
+    for path in (pkg.DP_PATH_GRAM, pkg.DP_PATH_MATERIALISE, pkg.DP_PATH_AUTO):
+        n = torch.zeros(B, device=DEV)
+        dp.sqnorms_dense(A_d, G_d, has_bias, path, n)
+        dp.sync()
+        errs[path] = assert_norms_close(host(n), ref, tol_of(dtype), f"path {path}")
+    if dtype == "bf16":
+        # fp32 accumulation of exact bf16 products: the real error is ~1e-6, far inside the 2e-2 bound
+        assert max(errs.values()) < 1e-4, errs
+
+
+def test_sqnorms_accumulate_over_layers(dp):
+    """Each call ADDS to sqnorms: two layers in sequence give the sum of both contributions."""
+    import paper_2108_01624_amd as pkg
+
+    B, T = 4, 128
+    A1, G1 = gen((B, T, 64), 1.0, 110, "bf16"), gen((B, T, 128), 0.1, 111, "bf16")
+    A2, G2 = gen((B, T, 128), 1.0, 112, "bf16"), gen((B, T, 64), 0.1, 113, "bf16")
+    n = torch.zeros(B, device=DEV)
+    dp.sqnorms_dense(to_dev(A1), to_dev(G1), True, pkg.DP_PATH_GRAM, n)
+    dp.sqnorms_dense(to_dev(A2), to_dev(G2), False, pkg.DP_PATH_MATERIALISE, n)
+    dp.sync()
+    ref = orc.sqnorms_dense(A1, G1, True) + orc.sqnorms_dense(A2, G2, False)
+    assert_norms_close(host(n), ref, 1e-4)
+
+
+# ------------------------------------------------------------------------------------------------
+# dense layers: clip-weighted sums
+# ------------------------------------------------------------------------------------------------
+ACC_SHAPES = [
+    ("f32", 32, 16, 64, 64),
+    ("f32", 3, 5, 7, 6),
+    ("f32", 4, 40, 70, 130),
+    ("bf16", 8, 128, 256, 384),    # 256 x 256 tiles, ragged second tile column, split over rows
+    ("bf16", 6, 96, 72, 136),      # 128 x 128 tiles, ragged
+    ("bf16", 64, 128, 256, 256),   # 8192 rows: several XCD-interleaved splits
+    ("bf16", 3, 50, 512, 264),     # rows not a multiple of the staged tile height
+    ("bf16", 2, 7, 8, 8),
+]
+
+
+@pytest.mark.parametrize("dtype,B,T,d_in,d_out", ACC_SHAPES)
+def test_clip_accumulate_dense(dp, dtype, B, T, d_in, d_out):
+    A = gen((B, T, d_in), 1.0, 120, dtype)
+    G = gen((B, T, d_out), 0.1, 121, dtype)
+    C = 1.0
+    sq = syn.synthetic_sqnorms(B, C, 122)           # both clip branches occur
+    c = orc.clip_factors(sq.astype(np.float64), C)
+    assert (c == 1).any() and (c < 1).any() or B < 3
+    SW_ref, Sb_ref = orc.clip_accumulate_dense(A, G, c, True)
+    init_W = syn.normal_f32((d_in, d_out), float(np.abs(SW_ref).mean()), 123)   # the call must ADD to the buffer
+    init_b = syn.normal_f32((d_out,), float(np.abs(Sb_ref).mean()), 124)
+    S_W, S_b = f32_dev(init_W), f32_dev(init_b)
+    dp.clip_accumulate_dense(to_dev(A), to_dev(G), C, f32_dev(sq), S_W, S_b)
+    dp.sync()
+    rel = assert_sums_close(host(S_W) - init_W.astype(np.float64), SW_ref, tol_of(dtype) + 1e-6, "sum_W")
+    assert_sums_close(host(S_b) - init_b.astype(np.float64), Sb_ref, tol_of(dtype) + 1e-6, "sum_b")
+    if dtype == "bf16":
+        assert rel < 5e-3, rel  # re-rounding c*g to bf16 costs ~2^-9 per term, averaged over the sum
+
+
+def test_clip_accumulate_dense_noop_clip_is_flat_gemm(dp):
+    """With no example clipped the bf16 path multiplies by 1 exactly: the result is the plain A^T G."""
+    B, T, d_in, d_out = 4, 64, 128, 128
+    A, G = gen((B, T, d_in), 1.0, 130, "bf16"), gen((B, T, d_out), 0.1, 131, "bf16")
+    sq = np.full(B, 1e-6, np.float32)
+    S_W = torch.zeros(d_in, d_out, device=DEV)
+    dp.clip_accumulate_dense(to_dev(A), to_dev(G), 1.0, f32_dev(sq), S_W, None)
+    dp.sync()
+    ref, _ = orc.clip_accumulate_dense(A, G, np.ones(B), False)
+    assert_sums_close(host(S_W), ref, 1e-5, "unclipped sum")
+
+
+def test_clip_factors(dp):
+    sq = np.array([0.0, 1e-12, 0.25, 1.0, 4.0, 1e12], np.float32)
+    c = torch.zeros(6, device=DEV)
+    dp.clip_factors(f32_dev(sq), 1.0, c)
+    dp.sync()
+    np.testing.assert_allclose(host(c), orc.clip_factors(sq.astype(np.float64), 1.0), rtol=1e-6)
+    assert host(c)[0] == 1.0 and host(c)[3] == 1.0
+
+
+def test_dense_pipeline_clip_invariant_and_determinism(dp):
+    """Norms from pass 1 feed pass 2; c_i^2 n_i <= C^2; a second run gives the same bits."""
+    import paper_2108_01624_amd as pkg
+
+    B, T, d_in, d_out = 16, 128, 256, 256
+    scale = syn.example_scales(B, 1e-3, 1.0, 140)
+    A = gen((B, T, d_in), 1.0, 141, "bf16")
+    G = syn.f32_to_bf16_bits(syn.normal_f32((B, T, d_out), 1e-2, 142) * scale[:, None, None])
+    A_d, G_d = to_dev(A), to_dev(G)
+    n_ref = orc.sqnorms_dense(A, G, True)
+    C = float(np.sqrt(np.median(n_ref)))
+    c_ref = orc.clip_factors(n_ref, C)
+    assert (c_ref == 1).any() and (c_ref < 1).any()
+    outs = []
+    for _ in range(2):
+        n = torch.zeros(B, device=DEV)
+        S_W, S_b = torch.zeros(d_in, d_out, device=DEV), torch.zeros(d_out, device=DEV)
+        dp.sqnorms_dense(A_d, G_d, True, pkg.DP_PATH_AUTO, n)
+        dp.clip_accumulate_dense(A_d, G_d, C, n, S_W, S_b)
+        c = torch.zeros(B, device=DEV)
+        dp.clip_factors(n, C, c)
+        dp.sync()
+        outs.append((host(n), host(S_W), host(S_b), host(c)))
+    for a, b in zip(*outs):
+        np.testing.assert_array_equal(a, b)
+    n, S_W, S_b, c = outs[0]
+    assert_norms_close(n, n_ref, 1e-4)
+    assert np.all(c.astype(np.float64) ** 2 * n <= C * C * (1 + 1e-5))
+    SW_ref, Sb_ref = orc.clip_accumulate_dense(A, G, c_ref, True)
+    assert_sums_close(S_W, SW_ref, TOL_BF16, "sum_W")
+    assert_sums_close(S_b, Sb_ref, TOL_BF16, "sum_b")
+
+
+# ------------------------------------------------------------------------------------------------
+# LayerNorm
+# ------------------------------------------------------------------------------------------------
+LN_SHAPES = [("f32", 32, 16, 64), ("f32", 3, 5, 6), ("f32", 2, 9, 260), ("bf16", 6, 128, 768), ("bf16", 3, 100, 1024),
+             ("bf16", 2, 17, 8), ("bf16", 40, 128, 264)]
+
+
+@pytest.mark.parametrize("dtype,B,T,d", LN_SHAPES)
+def test_layernorm_norms_and_sums(dp, dtype, B, T, d):
+    X = gen((B, T, d), 1.0, 150, dtype)
+    G = gen((B, T, d), 0.1, 151, dtype)
+    X_d, G_d = to_dev(X), to_dev(G)
+    n = f32_dev(np.full(B, 0.5, np.float32))
+    dp.sqnorms_layernorm(X_d, G_d, n)
+    dp.sync()
+    assert_norms_close(host(n).astype(np.float64) - 0.5, orc.sqnorms_layernorm(X, G), 1e-5 if dtype == "f32" else 1e-4)
+    C = 1.0
+    sq = syn.synthetic_sqnorms(B, C, 152)
+    c = orc.clip_factors(sq.astype(np.float64), C)
+    Sg_ref, Sb_ref = orc.clip_accumulate_layernorm(X, G, c)
+    S_g, S_b = torch.ones(d, device=DEV), torch.ones(d, device=DEV)
+    dp.clip_accumulate_layernorm(X_d, G_d, C, f32_dev(sq), S_g, S_b)
+    dp.sync()
+    t = 1e-5 if dtype == "f32" else 1e-4
+    assert_sums_close(host(S_g).astype(np.float64) - 1.0, Sg_ref, t, "sum_gamma")
+    assert_sums_close(host(S_b).astype(np.float64) - 1.0, Sb_ref, t, "sum_beta")
+
+
+# ------------------------------------------------------------------------------------------------
+# embeddings
+# ------------------------------------------------------------------------------------------------
+EMB_SHAPES = [("f32", 6, 20, 4, 13), ("f32", 3, 7, 6, 11), ("bf16", 8, 128, 1024, 30522), ("bf16", 5, 100, 264, 300),
+              ("bf16", 70, 128, 64, 50), ("bf16", 3, 512, 256, 1000)]
+
+
+@pytest.mark.parametrize("dtype,B,T,d,V", EMB_SHAPES)
+def test_embedding_norms_and_sums(dp, dtype, B, T, d, V):
+    ids = syn.zipf_ids(B, T, V, 1.1, 160)
+    G = gen((B, T, d), 0.1, 161, dtype)
+    ids_d, G_d = to_dev(ids), to_dev(G)
+    n = torch.zeros(B, device=DEV)
+    dp.sqnorms_embedding(ids_d, G_d, V, False, n)
+    dp.sync()
+    assert_norms_close(host(n), orc.sqnorms_embedding(ids, G, V), 1e-5 if dtype == "f32" else 1e-4, "token norms")
+    C = 1.0
+    sq = syn.synthetic_sqnorms(B, C, 162)
+    c = orc.clip_factors(sq.astype(np.float64), C)
+    ref = orc.clip_accumulate_embedding(ids, G, c, V)
+    S = torch.zeros(V, d, device=DEV)
+    dp.clip_accumulate_embedding(ids_d, G_d, V, C, f32_dev(sq), S)
+    dp.sync()
+    got = host(S)
+    # indexing is exact: the rows written are exactly the ids present
+    np.testing.assert_array_equal(np.nonzero(np.abs(got).sum(axis=1))[0], np.unique(ids))
+    assert_sums_close(got, ref, 1e-5 if dtype == "f32" else 1e-4, "sum_E")
+    # a second micro-batch accumulates on top
+    dp.clip_accumulate_embedding(ids_d, G_d, V, C, f32_dev(sq), S)
+    dp.sync()
+    assert_sums_close(host(S), 2 * ref, 1e-5 if dtype == "f32" else 1e-4, "sum_E twice")
+
+
+@pytest.mark.parametrize("B,T,V", [(8, 128, 30522), (70, 128, 5), (3, 1000, 2), (1, 1, 1)])
+def test_embedding_counts_are_exact(dp, B, T, V):
+    """All-ones gradients and no clipping: sum_E[v, :] is the count of v (small integers, exact in fp32)."""
+    d = 8
+    ids = syn.zipf_ids(B, T, V, 1.1, 170)
+    G = syn.f32_to_bf16_bits(np.ones((B, T, d), np.float32))
+    S = torch.zeros(V, d, device=DEV)
+    dp.clip_accumulate_embedding(to_dev(ids), to_dev(G), V, 1.0, f32_dev(np.full(B, 1e-9, np.float32)), S)
+    n = torch.zeros(B, device=DEV)
+    dp.sqnorms_embedding(to_dev(ids), to_dev(G), V, False, n)
+    dp.sync()
+    cnt = np.bincount(ids.reshape(-1), minlength=V).astype(np.float32)
+    np.testing.assert_array_equal(host(S), np.repeat(cnt[:, None], d, axis=1))
+    ref_n = np.array([d * float((np.bincount(r, minlength=V).astype(np.float64) ** 2).sum()) for r in ids])
+    np.testing.assert_array_equal(host(n).astype(np.float64), ref_n)
+
+
+@pytest.mark.parametrize("dtype,B,T,d", [("bf16", 6, 128, 1024), ("f32", 4, 9, 5), ("bf16", 300, 16, 64)])
+def test_position_embedding(dp, dtype, B, T, d):
+    V = T + 3
+    ids = syn.position_ids(B, T)
+    G = gen((B, T, d), 0.1, 180, dtype)
+    n = torch.zeros(B, device=DEV)
+    dp.sqnorms_embedding(to_dev(ids), to_dev(G), V, True, n)
+    n2 = torch.zeros(B, device=DEV)
+    dp.sqnorms_embedding(to_dev(ids), to_dev(G), V, False, n2)   # the general path agrees on distinct ids
+    dp.sync()
+    ref = orc.sqnorms_embedding(ids, G, V)
+    t = 1e-5 if dtype == "f32" else 1e-4
+    assert_norms_close(host(n), ref, t)
+    assert_norms_close(host(n2), ref, t)
+    sq = syn.synthetic_sqnorms(B, 1.0, 181)
+    c = orc.clip_factors(sq.astype(np.float64), 1.0)
+    S = torch.zeros(V, d, device=DEV)
+    dp.clip_accumulate_embedding(to_dev(ids), to_dev(G), V, 1.0, f32_dev(sq), S)
+    dp.sync()
+    got = host(S)
+    assert not got[T:].any()
+    assert_sums_close(got, orc.clip_accumulate_embedding(ids, G, c, V), t, "sum_pos")
+
+
+def test_embedding_out_of_range_id_is_reported(dp):
+    import paper_2108_01624_amd as pkg
+
+    B, T, d, V = 2, 8, 8, 10
+    ids = syn.zipf_ids(B, T, V, 1.1, 190)
+    ids[1, 3] = V
+    G = gen((B, T, d), 0.1, 191, "bf16")
+    n = torch.zeros(B, device=DEV)
+    dp.sqnorms_embedding(to_dev(ids), to_dev(G), V, False, n)
+    with pytest.raises(pkg.DpError) as e:
+        dp.sync()
+    assert e.value.status == -6
+    dp.sync()  # the error word is cleared
+    ids[1, 3] = -1
+    S = torch.zeros(V, d, device=DEV)
+    dp.clip_accumulate_embedding(to_dev(ids), to_dev(G), V, 1.0, f32_dev(np.ones(B, np.float32)), S)
+    with pytest.raises(pkg.DpError):
+        dp.sync()
+    # the valid tokens were still accumulated, the bad one skipped
+    ids_ok = ids.copy()
+    got = host(S)
+    ref = np.zeros((V, d))
+    Gf = orc.to_f64(G)
+    for i in range(B):
+        for t in range(T):
+            if 0 <= ids_ok[i, t] < V:
+                ref[ids_ok[i, t]] += Gf[i, t]
+    assert_sums_close(got, ref, 1e-5)
+
+
+# ------------------------------------------------------------------------------------------------
+# argument errors (host side: nothing is launched)
+# ------------------------------------------------------------------------------------------------
+def test_argument_errors(dp):
+    import paper_2108_01624_amd as pkg
+
+    lib = pkg.load_library()
+    h = dp.handle
+    x = torch.zeros(64, device=DEV)
+    p = x.data_ptr()
+    assert lib.dp_sqnorms_dense(h, None, p, 0, 1, 1, 4, 4, 0, 0, p) == -1
+    assert lib.dp_sqnorms_dense(h, p, p, 7, 1, 1, 4, 4, 0, 0, p) == -3
+    assert lib.dp_sqnorms_dense(h, p, p, 0, 1, 1, 4, 4, 0, 9, p) == -3
+    assert lib.dp_sqnorms_dense(h, p, p, 0, -1, 1, 4, 4, 0, 0, p) == -2
+    assert lib.dp_sqnorms_dense(h, p, p, 1, 1, 1, 4, 8, 0, 0, p) == -2      # bf16 width not a multiple of 8
+    assert lib.dp_sqnorms_dense(h, p + 2, p, 1, 1, 1, 8, 8, 0, 0, p) == -4  # bf16 pointer not 16-byte aligned
+    assert lib.dp_sqnorms_dense(h, p, p, 0, 0, 5, 4, 4, 0, 0, p) == 0       # empty batch: no-op
+    assert lib.dp_sqnorms_dense(None, p, p, 0, 1, 1, 4, 4, 0, 0, p) == -1
+    assert lib.dp_clip_accumulate_dense(h, p, p, 0, 1, 1, 4, 4, 0.0, p, p, None) == -5
+    assert lib.dp_clip_accumulate_dense(h, p, p, 0, 1, 1, 4, 4, float("nan"), p, p, None) == -5
+    assert lib.dp_sqnorms_embedding(h, p, p, 0, 1, 1, 4, 0, 0, p) == -2
+    assert lib.dp_sqnorms_embedding(h, p, p, 0, 1, 5000, 4, 10, 0, p) == -2   # T above the supported maximum
+    kw = (p, p, p, p, 4, 0)
+    assert lib.dp_noise_adamw(h, *kw, -1.0, 1.0, 0, 1, 8, 1e-3, 0.9, 0.999, 1e-11, 0.0, 0) == -5
+    assert lib.dp_noise_adamw(h, *kw, 0.0, 1.0, 0, 0, 8, 1e-3, 0.9, 0.999, 1e-11, 0.0, 0) == -5   # step 0
+    assert lib.dp_noise_adamw(h, *kw, 0.0, 1.0, 0, 1, 0, 1e-3, 0.9, 0.999, 1e-11, 0.0, 0) == -5   # batch 0
+    assert lib.dp_noise_adamw(h, *kw, 0.0, 1.0, 0, 1, 8, 1e-3, 1.0, 0.999, 1e-11, 0.0, 0) == -5   # beta1 = 1
+    assert lib.dp_noise_adamw(h, p, p, None, p, 4, 0, 0.0, 1.0, 0, 1, 8, 1e-3, 0.9, 0.999, 1e-11, 0.0, 0) == -1
+    assert "beta" in pkg.dp_last_error(h) or pkg.dp_last_error(h)
+    dp.sync()
+    assert not host(x).any()
+
+
+def test_zero_and_empty_calls(dp):
+    import paper_2108_01624_amd as pkg
+
+    x = torch.ones(1003, device=DEV)
+    dp.zero_f32(x[1:], n=1001)
+    dp.sync()
+    h = host(x)
+    assert h[0] == 1 and h[-1] == 1 and not h[1:1002].any()
+    n = torch.ones(4, device=DEV)
+    e = torch.zeros(0, 16, 8, dtype=torch.bfloat16, device=DEV)
+    lib = pkg.load_library()
+    assert lib.dp_sqnorms_layernorm(dp.handle, n.data_ptr(), n.data_ptr(), 1, 0, 16, 8, n.data_ptr()) == 0
+    assert lib.dp_clip_accumulate_layernorm(dp.handle, n.data_ptr(), n.data_ptr(), 1, 4, 0, 8, 1.0, n.data_ptr(), n.data_ptr(), n.data_ptr()) == 0
+    dp.sync()
+    assert host(n).tolist() == [1, 1, 1, 1]
