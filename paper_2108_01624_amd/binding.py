@@ -54,6 +54,10 @@ def load_library():
     global _lib
     if _lib is not None:
         return _lib
+    # torch ships its own HIP runtime: import it first so that the library binds to the runtime that owns
+    # the tensors' memory and streams instead of pulling in a second copy.
+    import torch  # noqa: F401
+
     if not os.path.exists(_LIB_PATH):
         raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2108_01624_amd.build` "
                            "(there is no fallback path)")
@@ -71,6 +75,27 @@ def _ptr(t):
         return None
     if isinstance(t, int):
         return t
+    return t.data_ptr()
+
+
+def _f32(t):
+    """Device pointer of an fp32 tensor (sums, norms, parameters); refuses any other element type."""
+    if t is None or isinstance(t, int):
+        return t
+    import torch
+
+    if t.dtype != torch.float32:
+        raise TypeError(f"expected a float32 tensor, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _i32(t):
+    if t is None or isinstance(t, int):
+        return t
+    import torch
+
+    if t.dtype != torch.int32:
+        raise TypeError(f"expected an int32 tensor, got {t.dtype}")
     return t.data_ptr()
 
 
@@ -119,67 +144,67 @@ def dp_sqnorms_dense(ctx, A, G, has_bias, path, sqnorms, *, B=None, T=None):
     B = A.shape[0] if B is None else B
     T = A.shape[1] if T is None else T
     st = load_library().dp_sqnorms_dense(ctx, _ptr(A), _ptr(G), _dtype_of(A), B, T, A.shape[-1], G.shape[-1],
-                                         int(has_bias), int(path), _ptr(sqnorms))
+                                         int(has_bias), int(path), _f32(sqnorms))
     _check(ctx, st, "dp_sqnorms_dense")
 
 
 def dp_sqnorms_layernorm(ctx, Xhat, G, sqnorms):
     B, T, d = Xhat.shape
-    _check(ctx, load_library().dp_sqnorms_layernorm(ctx, _ptr(Xhat), _ptr(G), _dtype_of(G), B, T, d, _ptr(sqnorms)),
+    _check(ctx, load_library().dp_sqnorms_layernorm(ctx, _ptr(Xhat), _ptr(G), _dtype_of(G), B, T, d, _f32(sqnorms)),
            "dp_sqnorms_layernorm")
 
 
 def dp_sqnorms_embedding(ctx, ids, G, V, distinct_per_example, sqnorms):
     B, T, d = G.shape
-    st = load_library().dp_sqnorms_embedding(ctx, _ptr(ids), _ptr(G), _dtype_of(G), B, T, d, int(V),
-                                             int(distinct_per_example), _ptr(sqnorms))
+    st = load_library().dp_sqnorms_embedding(ctx, _i32(ids), _ptr(G), _dtype_of(G), B, T, d, int(V),
+                                             int(distinct_per_example), _f32(sqnorms))
     _check(ctx, st, "dp_sqnorms_embedding")
 
 
 def dp_clip_factors(ctx, sqnorms, C, c):
-    _check(ctx, load_library().dp_clip_factors(ctx, _ptr(sqnorms), sqnorms.shape[0], float(C), _ptr(c)), "dp_clip_factors")
+    _check(ctx, load_library().dp_clip_factors(ctx, _f32(sqnorms), sqnorms.shape[0], float(C), _f32(c)), "dp_clip_factors")
 
 
 def dp_clip_accumulate_dense(ctx, A, G, C, sqnorms, sum_W, sum_b=None):
     B, T, d_in = A.shape
     st = load_library().dp_clip_accumulate_dense(ctx, _ptr(A), _ptr(G), _dtype_of(A), B, T, d_in, G.shape[-1], float(C),
-                                                 _ptr(sqnorms), _ptr(sum_W), _ptr(sum_b))
+                                                 _f32(sqnorms), _f32(sum_W), _f32(sum_b))
     _check(ctx, st, "dp_clip_accumulate_dense")
 
 
 def dp_clip_accumulate_layernorm(ctx, Xhat, G, C, sqnorms, sum_gamma, sum_beta):
     B, T, d = Xhat.shape
     st = load_library().dp_clip_accumulate_layernorm(ctx, _ptr(Xhat), _ptr(G), _dtype_of(G), B, T, d, float(C),
-                                                     _ptr(sqnorms), _ptr(sum_gamma), _ptr(sum_beta))
+                                                     _f32(sqnorms), _f32(sum_gamma), _f32(sum_beta))
     _check(ctx, st, "dp_clip_accumulate_layernorm")
 
 
 def dp_clip_accumulate_embedding(ctx, ids, G, V, C, sqnorms, sum_E):
     B, T, d = G.shape
-    st = load_library().dp_clip_accumulate_embedding(ctx, _ptr(ids), _ptr(G), _dtype_of(G), B, T, d, int(V), float(C),
-                                                     _ptr(sqnorms), _ptr(sum_E))
+    st = load_library().dp_clip_accumulate_embedding(ctx, _i32(ids), _ptr(G), _dtype_of(G), B, T, d, int(V), float(C),
+                                                     _f32(sqnorms), _f32(sum_E))
     _check(ctx, st, "dp_clip_accumulate_embedding")
 
 
 def dp_noise_adamw(ctx, params, m, v, sum_, *, n=None, elem_offset=0, sigma, C, seed, step, batch_size, lr, beta1, beta2,
                    eps=1e-11, weight_decay, zero_sum=False):
     n = params.numel() if n is None else n
-    st = load_library().dp_noise_adamw(ctx, _ptr(params), _ptr(m), _ptr(v), _ptr(sum_), n, elem_offset, sigma, C, seed,
+    st = load_library().dp_noise_adamw(ctx, _f32(params), _f32(m), _f32(v), _f32(sum_), n, elem_offset, sigma, C, seed,
                                        step, batch_size, lr, beta1, beta2, eps, weight_decay, int(zero_sum))
     _check(ctx, st, "dp_noise_adamw")
 
 
 def dp_zero_f32(ctx, p, n=None):
-    _check(ctx, load_library().dp_zero_f32(ctx, _ptr(p), p.numel() if n is None else n), "dp_zero_f32")
+    _check(ctx, load_library().dp_zero_f32(ctx, _f32(p), p.numel() if n is None else n), "dp_zero_f32")
 
 
 def dp_philox_u32(ctx, out, elem_offset, seed, step, n=None):
-    _check(ctx, load_library().dp_philox_u32(ctx, _ptr(out), out.numel() if n is None else n, elem_offset, seed, step),
+    _check(ctx, load_library().dp_philox_u32(ctx, _i32(out), out.numel() if n is None else n, elem_offset, seed, step),
            "dp_philox_u32")
 
 
 def dp_normal_f32(ctx, out, elem_offset, seed, step, n=None):
-    _check(ctx, load_library().dp_normal_f32(ctx, _ptr(out), out.numel() if n is None else n, elem_offset, seed, step),
+    _check(ctx, load_library().dp_normal_f32(ctx, _f32(out), out.numel() if n is None else n, elem_offset, seed, step),
            "dp_normal_f32")
 
 

@@ -51,7 +51,7 @@ def test_philox_empty(dp):
 
 @pytest.mark.parametrize("off,n", [(0, 1 << 16), (3, 1001)])
 def test_normals_match_oracle(dp, off, n):
-    out = torch.zeros(n, device=DEV)
+    out = torch.zeros(n, dtype=torch.float32, device=DEV)
     dp.normal_f32(out, off, 1234, 1)
     dp.sync()
     z = host(out).astype(np.float64)
@@ -63,7 +63,7 @@ def test_normals_match_oracle(dp, off, n):
 def test_normals_full_u_range(dp):
     """Scan many blocks and check the extreme uniforms (u near 0 and near 1), where log is most delicate."""
     n = 1 << 22
-    out = torch.zeros(n, device=DEV)
+    out = torch.zeros(n, dtype=torch.float32, device=DEV)
     dp.normal_f32(out, 0, 42, 1)
     dp.sync()
     z = host(out).astype(np.float64)
@@ -80,8 +80,8 @@ def _adam_case(dp, n, off, sigma, seed, step, steps=1, zero_sum=False, batch=32,
     th0 = syn.normal_f32((n,), 0.02, 50)
     pad = misalign
     th = f32_dev(np.concatenate([np.zeros(pad, np.float32), th0]))[pad:]
-    m = torch.zeros(n + pad, device=DEV)[pad:]
-    v = torch.zeros(n + pad, device=DEV)[pad:]
+    m = torch.zeros(n + pad, dtype=torch.float32, device=DEV)[pad:]
+    v = torch.zeros(n + pad, dtype=torch.float32, device=DEV)[pad:]
     r_th, r_m, r_v = th0.astype(np.float64), np.zeros(n), np.zeros(n)
     for k in range(steps):
         S = syn.normal_f32((n,), 3.0, 60 + k)
@@ -132,7 +132,7 @@ def test_adamw_slicing_invariance(dp):
     kw = dict(sigma=0.6, C=1.0, seed=9, step=3, batch_size=64, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-11, weight_decay=0.5)
     res = []
     for cut in (None, 4000, 4001):
-        th, m, v, S_d = f32_dev(th0), torch.zeros(n, device=DEV), torch.zeros(n, device=DEV), f32_dev(S)
+        th, m, v, S_d = f32_dev(th0), torch.zeros(n, dtype=torch.float32, device=DEV), torch.zeros(n, dtype=torch.float32, device=DEV), f32_dev(S)
         if cut is None:
             dp.noise_adamw(th, m, v, S_d, elem_offset=100, **kw)
         else:
@@ -148,7 +148,7 @@ def test_adamw_slicing_invariance(dp):
 def test_adamw_untouched_row_is_pure_decay(dp):
     n = 256
     th0 = syn.normal_f32((n,), 0.02, 72)
-    th, m, v, S = f32_dev(th0), torch.zeros(n, device=DEV), torch.zeros(n, device=DEV), torch.zeros(n, device=DEV)
+    th, m, v, S = f32_dev(th0), torch.zeros(n, dtype=torch.float32, device=DEV), torch.zeros(n, dtype=torch.float32, device=DEV), torch.zeros(n, dtype=torch.float32, device=DEV)
     dp.noise_adamw(th, m, v, S, sigma=0.0, C=1.0, seed=0, step=1, batch_size=8, lr=1e-3, beta1=0.9, beta2=0.999,
                    eps=1e-11, weight_decay=0.5)
     dp.sync()
@@ -184,7 +184,7 @@ def test_sqnorms_dense_paths(dp, dtype, B, T, d_in, d_out, has_bias):
     A_d, G_d = to_dev(A), to_dev(G)
     errs = {}
     for path in (pkg.DP_PATH_GRAM, pkg.DP_PATH_MATERIALISE, pkg.DP_PATH_AUTO):
-        n = torch.zeros(B, device=DEV)
+        n = torch.zeros(B, dtype=torch.float32, device=DEV)
         dp.sqnorms_dense(A_d, G_d, has_bias, path, n)
         dp.sync()
         errs[path] = assert_norms_close(host(n), ref, tol_of(dtype), f"path {path}")
@@ -200,7 +200,7 @@ def test_sqnorms_accumulate_over_layers(dp):
     B, T = 4, 128
     A1, G1 = gen((B, T, 64), 1.0, 110, "bf16"), gen((B, T, 128), 0.1, 111, "bf16")
     A2, G2 = gen((B, T, 128), 1.0, 112, "bf16"), gen((B, T, 64), 0.1, 113, "bf16")
-    n = torch.zeros(B, device=DEV)
+    n = torch.zeros(B, dtype=torch.float32, device=DEV)
     dp.sqnorms_dense(to_dev(A1), to_dev(G1), True, pkg.DP_PATH_GRAM, n)
     dp.sqnorms_dense(to_dev(A2), to_dev(G2), False, pkg.DP_PATH_MATERIALISE, n)
     dp.sync()
@@ -248,7 +248,7 @@ def test_clip_accumulate_dense_noop_clip_is_flat_gemm(dp):
     B, T, d_in, d_out = 4, 64, 128, 128
     A, G = gen((B, T, d_in), 1.0, 130, "bf16"), gen((B, T, d_out), 0.1, 131, "bf16")
     sq = np.full(B, 1e-6, np.float32)
-    S_W = torch.zeros(d_in, d_out, device=DEV)
+    S_W = torch.zeros(d_in, d_out, dtype=torch.float32, device=DEV)
     dp.clip_accumulate_dense(to_dev(A), to_dev(G), 1.0, f32_dev(sq), S_W, None)
     dp.sync()
     ref, _ = orc.clip_accumulate_dense(A, G, np.ones(B), False)
@@ -257,7 +257,7 @@ def test_clip_accumulate_dense_noop_clip_is_flat_gemm(dp):
 
 def test_clip_factors(dp):
     sq = np.array([0.0, 1e-12, 0.25, 1.0, 4.0, 1e12], np.float32)
-    c = torch.zeros(6, device=DEV)
+    c = torch.zeros(6, dtype=torch.float32, device=DEV)
     dp.clip_factors(f32_dev(sq), 1.0, c)
     dp.sync()
     np.testing.assert_allclose(host(c), orc.clip_factors(sq.astype(np.float64), 1.0), rtol=1e-6)
@@ -279,11 +279,11 @@ def test_dense_pipeline_clip_invariant_and_determinism(dp):
     assert (c_ref == 1).any() and (c_ref < 1).any()
     outs = []
     for _ in range(2):
-        n = torch.zeros(B, device=DEV)
-        S_W, S_b = torch.zeros(d_in, d_out, device=DEV), torch.zeros(d_out, device=DEV)
+        n = torch.zeros(B, dtype=torch.float32, device=DEV)
+        S_W, S_b = torch.zeros(d_in, d_out, dtype=torch.float32, device=DEV), torch.zeros(d_out, dtype=torch.float32, device=DEV)
         dp.sqnorms_dense(A_d, G_d, True, pkg.DP_PATH_AUTO, n)
         dp.clip_accumulate_dense(A_d, G_d, C, n, S_W, S_b)
-        c = torch.zeros(B, device=DEV)
+        c = torch.zeros(B, dtype=torch.float32, device=DEV)
         dp.clip_factors(n, C, c)
         dp.sync()
         outs.append((host(n), host(S_W), host(S_b), host(c)))
@@ -317,7 +317,7 @@ def test_layernorm_norms_and_sums(dp, dtype, B, T, d):
     sq = syn.synthetic_sqnorms(B, C, 152)
     c = orc.clip_factors(sq.astype(np.float64), C)
     Sg_ref, Sb_ref = orc.clip_accumulate_layernorm(X, G, c)
-    S_g, S_b = torch.ones(d, device=DEV), torch.ones(d, device=DEV)
+    S_g, S_b = torch.ones(d, dtype=torch.float32, device=DEV), torch.ones(d, dtype=torch.float32, device=DEV)
     dp.clip_accumulate_layernorm(X_d, G_d, C, f32_dev(sq), S_g, S_b)
     dp.sync()
     t = 1e-5 if dtype == "f32" else 1e-4
@@ -337,7 +337,7 @@ def test_embedding_norms_and_sums(dp, dtype, B, T, d, V):
     ids = syn.zipf_ids(B, T, V, 1.1, 160)
     G = gen((B, T, d), 0.1, 161, dtype)
     ids_d, G_d = to_dev(ids), to_dev(G)
-    n = torch.zeros(B, device=DEV)
+    n = torch.zeros(B, dtype=torch.float32, device=DEV)
     dp.sqnorms_embedding(ids_d, G_d, V, False, n)
     dp.sync()
     assert_norms_close(host(n), orc.sqnorms_embedding(ids, G, V), 1e-5 if dtype == "f32" else 1e-4, "token norms")
@@ -345,7 +345,7 @@ def test_embedding_norms_and_sums(dp, dtype, B, T, d, V):
     sq = syn.synthetic_sqnorms(B, C, 162)
     c = orc.clip_factors(sq.astype(np.float64), C)
     ref = orc.clip_accumulate_embedding(ids, G, c, V)
-    S = torch.zeros(V, d, device=DEV)
+    S = torch.zeros(V, d, dtype=torch.float32, device=DEV)
     dp.clip_accumulate_embedding(ids_d, G_d, V, C, f32_dev(sq), S)
     dp.sync()
     got = host(S)
@@ -364,9 +364,9 @@ def test_embedding_counts_are_exact(dp, B, T, V):
     d = 8
     ids = syn.zipf_ids(B, T, V, 1.1, 170)
     G = syn.f32_to_bf16_bits(np.ones((B, T, d), np.float32))
-    S = torch.zeros(V, d, device=DEV)
+    S = torch.zeros(V, d, dtype=torch.float32, device=DEV)
     dp.clip_accumulate_embedding(to_dev(ids), to_dev(G), V, 1.0, f32_dev(np.full(B, 1e-9, np.float32)), S)
-    n = torch.zeros(B, device=DEV)
+    n = torch.zeros(B, dtype=torch.float32, device=DEV)
     dp.sqnorms_embedding(to_dev(ids), to_dev(G), V, False, n)
     dp.sync()
     cnt = np.bincount(ids.reshape(-1), minlength=V).astype(np.float32)
@@ -380,9 +380,9 @@ def test_position_embedding(dp, dtype, B, T, d):
     V = T + 3
     ids = syn.position_ids(B, T)
     G = gen((B, T, d), 0.1, 180, dtype)
-    n = torch.zeros(B, device=DEV)
+    n = torch.zeros(B, dtype=torch.float32, device=DEV)
     dp.sqnorms_embedding(to_dev(ids), to_dev(G), V, True, n)
-    n2 = torch.zeros(B, device=DEV)
+    n2 = torch.zeros(B, dtype=torch.float32, device=DEV)
     dp.sqnorms_embedding(to_dev(ids), to_dev(G), V, False, n2)   # the general path agrees on distinct ids
     dp.sync()
     ref = orc.sqnorms_embedding(ids, G, V)
@@ -391,7 +391,7 @@ def test_position_embedding(dp, dtype, B, T, d):
     assert_norms_close(host(n2), ref, t)
     sq = syn.synthetic_sqnorms(B, 1.0, 181)
     c = orc.clip_factors(sq.astype(np.float64), 1.0)
-    S = torch.zeros(V, d, device=DEV)
+    S = torch.zeros(V, d, dtype=torch.float32, device=DEV)
     dp.clip_accumulate_embedding(to_dev(ids), to_dev(G), V, 1.0, f32_dev(sq), S)
     dp.sync()
     got = host(S)
@@ -406,14 +406,14 @@ def test_embedding_out_of_range_id_is_reported(dp):
     ids = syn.zipf_ids(B, T, V, 1.1, 190)
     ids[1, 3] = V
     G = gen((B, T, d), 0.1, 191, "bf16")
-    n = torch.zeros(B, device=DEV)
+    n = torch.zeros(B, dtype=torch.float32, device=DEV)
     dp.sqnorms_embedding(to_dev(ids), to_dev(G), V, False, n)
     with pytest.raises(pkg.DpError) as e:
         dp.sync()
     assert e.value.status == -6
     dp.sync()  # the error word is cleared
     ids[1, 3] = -1
-    S = torch.zeros(V, d, device=DEV)
+    S = torch.zeros(V, d, dtype=torch.float32, device=DEV)
     dp.clip_accumulate_embedding(to_dev(ids), to_dev(G), V, 1.0, f32_dev(np.ones(B, np.float32)), S)
     with pytest.raises(pkg.DpError):
         dp.sync()
@@ -437,7 +437,7 @@ def test_argument_errors(dp):
 
     lib = pkg.load_library()
     h = dp.handle
-    x = torch.zeros(64, device=DEV)
+    x = torch.zeros(64, dtype=torch.float32, device=DEV)
     p = x.data_ptr()
     assert lib.dp_sqnorms_dense(h, None, p, 0, 1, 1, 4, 4, 0, 0, p) == -1
     assert lib.dp_sqnorms_dense(h, p, p, 7, 1, 1, 4, 4, 0, 0, p) == -3
@@ -465,12 +465,12 @@ def test_argument_errors(dp):
 def test_zero_and_empty_calls(dp):
     import paper_2108_01624_amd as pkg
 
-    x = torch.ones(1003, device=DEV)
+    x = torch.ones(1003, dtype=torch.float32, device=DEV)
     dp.zero_f32(x[1:], n=1001)
     dp.sync()
     h = host(x)
     assert h[0] == 1 and h[-1] == 1 and not h[1:1002].any()
-    n = torch.ones(4, device=DEV)
+    n = torch.ones(4, dtype=torch.float32, device=DEV)
     e = torch.zeros(0, 16, 8, dtype=torch.bfloat16, device=DEV)
     lib = pkg.load_library()
     assert lib.dp_sqnorms_layernorm(dp.handle, n.data_ptr(), n.data_ptr(), 1, 0, 16, 8, n.data_ptr()) == 0

@@ -9,7 +9,6 @@ import torch
 import dp_synth as syn
 from oracle import dp_oracle as orc
 
-torch.set_default_dtype(torch.float64)
 
 
 # ----------------------------------------------------------------------------------------------
@@ -252,7 +251,7 @@ def test_embedding_counts_and_index_add():
     G = syn.normal_f32((B, T, d), 1.0, 8)
     c = np.linspace(0.1, 1.0, B)
     S = orc.clip_accumulate_embedding(ids, G, c, V)
-    ref = torch.zeros(V, d)
+    ref = torch.zeros(V, d, dtype=torch.float64)
     ref.index_add_(0, torch.from_numpy(ids.reshape(-1).astype(np.int64)),
                    torch.from_numpy((G.astype(np.float64) * c[:, None, None]).reshape(-1, d)))
     np.testing.assert_allclose(S, ref.numpy(), rtol=1e-12, atol=1e-14)
