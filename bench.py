@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the DP-SGD clipped-gradient hot path on one MI355X.
+
+A "step" is one pass of the whole path over one micro-batch of synthetic BERT-Large-shaped input that
+is already resident in HBM: zero the norm buffer, pass 1 (per-example squared norms of every layer),
+pass 2 (clip-weighted sums of every layer into the fp32 sum buffer), and the noise + AdamW update over
+all parameters.  Prints ONE JSON line with the throughput (examples/s), the roofline of the dominant
+kernel (the clip-weighted MFMA GEMM) measured with HIP events inside the timed region, and the CPU oracle
+timed on a bounded sample of the same workload on the host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="C3", choices=["C2", "C3", "C5"])
+    ap.add_argument("--batch", type=int, default=0, help="override the micro-batch size (parity/debug only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-examples", type=int, default=0, help="examples in the oracle sample (0 = auto)")
+    return ap.parse_args()
+
+
+def cpu_baseline(layers, cfg, n_examples):
+    """Time the oracle, as it stands, on the first n_examples examples over the full manifest."""
+    import numpy as np
+
+    import dp_synth as syn
+    from oracle import dp_oracle as orc
+
+    try:
+        from threadpoolctl import threadpool_info
+
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    host = syn.host_layer_slice(layers, range(n_examples))
+    t0 = time.perf_counter()
+    sums, sq, c = orc.microbatch_clip_sum(host, cfg["C"])
+    dt = time.perf_counter() - t0
+    return dict(value=n_examples / dt, unit="examples/s", cores=int(threads), kind="oracle",
+                sample=f"first {n_examples} examples of the workload, full layer manifest, norms + clip + sum "
+                       f"(numpy fp64, {dt:.1f} s)"), sq
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no collectives, no sharding here)",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import dp_synth as syn
+    import paper_2108_01624_amd as pkg
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU path", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    cfg = syn.CONFIGS[args.workload]
+    B = args.batch or cfg["B"]
+    T = cfg["T"]
+    manifest = cfg["manifest"]()
+    upd = syn.CONFIGS["C4"]  # update hyper-parameters of the mega-batch workload
+    t_gen = time.perf_counter()
+    layers = syn.device_layer_inputs(manifest, B, T, dtype=cfg["dtype"], act_std=cfg["act_std"],
+                                     grad_std=cfg["grad_std"], data_seed=cfg["data_seed"], device=dev)
+    torch.cuda.synchronize()
+    t_gen = time.perf_counter() - t_gen
+    in_bytes = sum(t.numel() * t.element_size() for l in layers for k, t in l.items() if k in ("A", "G", "X", "ids"))
+
+    ctx = pkg.Context()
+    run = pkg.StepRunner(ctx, manifest, B, device=dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(cfg["data_seed"] + 1)
+    run.theta.copy_(torch.randn(run.P, generator=gen, device=dev) * 0.02)
+
+    def step(t):
+        run.pass1(layers)
+        run.pass2(layers, cfg["C"])
+        run.update(sigma=upd["sigma"], C=cfg["C"], seed=upd["noise_seed"], step=t, batch_size=B, lr=upd["lr"],
+                   beta1=upd["beta1"], beta2=upd["beta2"], weight_decay=upd["weight_decay"], zero_sum=True)
+
+    for w in range(args.warmup):
+        step(w + 1)
+    ctx.sync()
+    torch.cuda.synchronize()
+    ctx.profile_enable(True)
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        t = args.warmup + k + 1
+        ev = evs[k]
+        ev[0].record()
+        run.pass1(layers)
+        ev[1].record()
+        run.pass2(layers, cfg["C"])
+        ev[2].record()
+        run.update(sigma=upd["sigma"], C=cfg["C"], seed=upd["noise_seed"], step=t, batch_size=B, lr=upd["lr"],
+                   beta1=upd["beta1"], beta2=upd["beta2"], weight_decay=upd["weight_decay"], zero_sum=True)
+        ev[3].record()
+    ctx.sync()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    phase_ms = [sum(ev[j].elapsed_time(ev[j + 1]) for ev in evs) for j in range(3)]
+    ms_per_step = dt * 1e3 / args.steps
+    g_ms, g_n, g_flops = ctx.profile_read(pkg.DP_PROF_WGEMM)
+    n_ms, n_n, n_bytes = ctx.profile_read(pkg.DP_PROF_GRAM)
+    a_ms, a_n, a_bytes = ctx.profile_read(pkg.DP_PROF_ADAMW)
+    ctx.profile_enable(False)
+
+    achieved = g_flops / (g_ms * 1e-3) / 1e12 if g_ms > 0 else 0.0
+    out = {
+        "metric": "clipped per-example grads/sec (examples/s), BERT-Large seq128; MFMA util %",
+        "value": B / (ms_per_step * 1e-3),
+        "unit": "examples/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if cfg["dtype"] == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: BERT-Large-shaped full parameter set "
+                               f"(24 blocks, hidden 1024, FFN 4096, token emb 30522x1024 Zipf(1.1), pos emb 512x1024), "
+                               f"micro-batch B={B}, seq T={T}, bf16 inputs / fp32 accumulation, C={cfg['C']}; "
+                               f"one step = norms + clip-accumulate over all layers + noise/AdamW over all params"
+                               if args.workload != "C2" else f"C2: BERT-Base-shaped stack, B={B}, T={T}",
+                   "params": int(run.P), "micro_batch": B, "seq_len": T, "input_bytes": int(in_bytes)},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "kernel": "wgemm_bf16_kernel (clip-weighted A^T diag(c) G)",
+                     "avg_launch_ms": g_ms / max(1, g_n), "launches": int(g_n)},
+        "kernels": {
+            "gram_sqnorms": {"bound": "hbm", "achieved_GBps": n_bytes / (n_ms * 1e-3) / 1e9 if n_ms else 0.0,
+                             "frac": n_bytes / (n_ms * 1e-3) / 1e9 / PEAK_HBM_GBS if n_ms else 0.0,
+                             "avg_launch_ms": n_ms / max(1, n_n), "launches": int(n_n)},
+            "noise_adamw": {"bound": "hbm", "achieved_GBps": a_bytes / (a_ms * 1e-3) / 1e9 if a_ms else 0.0,
+                            "frac": a_bytes / (a_ms * 1e-3) / 1e9 / PEAK_HBM_GBS if a_ms else 0.0,
+                            "avg_launch_ms": a_ms / max(1, a_n), "launches": int(a_n)},
+        },
+        "phase_ms": {"pass1_norms": phase_ms[0] / args.steps, "pass2_clip_accumulate": phase_ms[1] / args.steps,
+                     "noise_adamw": phase_ms[2] / args.steps, "input_gen_s": t_gen},
+    }
+    if not args.no_cpu_baseline:
+        # ~155 GFLOP of fp64 work per BERT-Large example at T=128: a handful of examples is 10-30 s
+        n_ex = args.cpu_examples or max(1, min(B, 16 * 128 // T))
+        base, _ = cpu_baseline(layers, cfg, n_ex)
+        out["cpu_baseline"] = base
+    ctx.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -22,3 +22,4 @@ from .manifest import (  # noqa: F401
     manifest_param_count,
     CONFIGS,
 )
+from .device import device_layer_inputs, host_layer_slice  # noqa: F401,E402

@@ -153,6 +153,19 @@ dp_status dp_normal_f32(dp_ctx* ctx, float* out, uint64_t n, uint64_t elem_offse
 /* Host-only, pure: the path DP_PATH_AUTO takes for this shape (HOST pointer out). */
 dp_status dp_choose_path(int T, int d_in, int d_out, dp_dtype dtype, dp_path* out);
 
+
+/* ---------------------------------------------------------------------------------------------------
+ * Kernel timing (for benchmarks): while enabled, the library brackets each launch of its three main
+ * kernels with HIP events on the context's stream.  dp_profile_read synchronises the stream and returns,
+ * for one kernel kind, the summed launch duration in milliseconds, the launch count and the summed
+ * algorithmic work (flops for DP_PROF_WGEMM: 2*B*T*d_in*d_out per launch; bytes for DP_PROF_GRAM:
+ * B*T*(d_in+d_out)*elem, and for DP_PROF_ADAMW: 28 or 32 per element), then clears that kind's records.
+ * All out pointers are HOST pointers and may be NULL.  At most 65536 launches are kept per enable.
+ * ------------------------------------------------------------------------------------------------- */
+typedef enum { DP_PROF_WGEMM = 0, DP_PROF_GRAM = 1, DP_PROF_ADAMW = 2 } dp_prof_kind;
+dp_status dp_profile_enable(dp_ctx* ctx, int enable);
+dp_status dp_profile_read(dp_ctx* ctx, dp_prof_kind kind, double* ms_total, uint64_t* launches, double* work_total);
+
 #ifdef __cplusplus
 }
 #endif

@@ -12,6 +12,7 @@ _lib = None
 
 DP_F32, DP_BF16 = 0, 1
 DP_PATH_AUTO, DP_PATH_GRAM, DP_PATH_MATERIALISE = 0, 1, 2
+DP_PROF_WGEMM, DP_PROF_GRAM, DP_PROF_ADAMW = 0, 1, 2
 DP_OK = 0
 STATUS_NAMES = {0: "DP_OK", -1: "DP_ERR_NULL", -2: "DP_ERR_SHAPE", -3: "DP_ERR_DTYPE", -4: "DP_ERR_ALIGN",
                 -5: "DP_ERR_VALUE", -6: "DP_ERR_INDEX", -7: "DP_ERR_WORKSPACE", -8: "DP_ERR_HIP"}
@@ -39,6 +40,9 @@ SIGNATURES = {
     "dp_philox_u32": [c_void_p, c_void_p, c_uint64, c_uint64, c_uint64, c_uint64],
     "dp_normal_f32": [c_void_p, c_void_p, c_uint64, c_uint64, c_uint64, c_uint64],
     "dp_choose_path": [c_int, c_int, c_int, c_int, ctypes.POINTER(c_int)],
+    "dp_profile_enable": [c_void_p, c_int],
+    "dp_profile_read": [c_void_p, c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_uint64),
+                        ctypes.POINTER(ctypes.c_double)],
 }
 _RESTYPES = {"dp_status_str": c_char_p, "dp_last_error": c_char_p}
 
@@ -214,6 +218,18 @@ def dp_choose_path(T, d_in, d_out, dtype=DP_BF16) -> int:
     if st != DP_OK:
         raise DpError(st, "dp_choose_path")
     return out.value
+
+
+def dp_profile_enable(ctx, enable: bool):
+    _check(ctx, load_library().dp_profile_enable(ctx, int(enable)), "dp_profile_enable")
+
+
+def dp_profile_read(ctx, kind: int):
+    """-> (milliseconds, launches, work) summed over the launches of `kind` since the last read."""
+    ms, cnt, work = ctypes.c_double(), c_uint64(), ctypes.c_double()
+    st = load_library().dp_profile_read(ctx, kind, ctypes.byref(ms), ctypes.byref(cnt), ctypes.byref(work))
+    _check(ctx, st, "dp_profile_read")
+    return ms.value, cnt.value, work.value
 
 
 class Context:

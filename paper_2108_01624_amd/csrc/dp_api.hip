@@ -71,6 +71,11 @@ dp_status dp_create(dp_ctx** out, void* hip_stream, size_t workspace_bytes) {
     ctx->stream = (hipStream_t)hip_stream;
     ctx->ws_bytes = workspace_bytes ? workspace_bytes : DEFAULT_WORKSPACE;
     ctx->cbuf_cap = CBUF_CAP;
+    ctx->prof = (dp_prof_rec*)calloc(DP_PROF_CAP, sizeof(dp_prof_rec));
+    if (!ctx->prof) {
+        free(ctx);
+        return DP_ERR_HIP;
+    }
     hipError_t e = hipGetDevice(&ctx->device);
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->ws, ctx->ws_bytes);
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->err_word, sizeof(int));
@@ -80,6 +85,7 @@ dp_status dp_create(dp_ctx** out, void* hip_stream, size_t workspace_bytes) {
         if (ctx->ws) (void)hipFree(ctx->ws);
         if (ctx->err_word) (void)hipFree(ctx->err_word);
         if (ctx->cbuf) (void)hipFree(ctx->cbuf);
+        free(ctx->prof);
         free(ctx);
         return DP_ERR_HIP;
     }
@@ -93,7 +99,55 @@ dp_status dp_destroy(dp_ctx* ctx) {
     (void)hipFree(ctx->ws);
     (void)hipFree(ctx->err_word);
     (void)hipFree(ctx->cbuf);
+    for (int i = 0; i < ctx->prof_made; ++i) {
+        (void)hipEventDestroy(ctx->prof[i].start);
+        (void)hipEventDestroy(ctx->prof[i].stop);
+    }
+    free(ctx->prof);
     free(ctx);
+    return DP_OK;
+}
+
+dp_status dp_profile_enable(dp_ctx* ctx, int enable) {
+    REQUIRE_CTX(ctx);
+    DP_HIP_CHECK(ctx, hipStreamSynchronize(ctx->stream));
+    ctx->prof_on = enable ? 1 : 0;
+    ctx->prof_n = 0;
+    return DP_OK;
+}
+
+dp_status dp_profile_read(dp_ctx* ctx, dp_prof_kind kind, double* ms_total, uint64_t* launches, double* work_total) {
+    REQUIRE_CTX(ctx);
+    if ((int)kind < 0 || (int)kind > (int)DP_PROF_ADAMW) FAIL(ctx, DP_ERR_DTYPE, "unknown profile kind %d", (int)kind);
+    DP_HIP_CHECK(ctx, hipStreamSynchronize(ctx->stream));
+    double ms = 0.0, work = 0.0;
+    uint64_t cnt = 0;
+    int keep = 0;
+    for (int i = 0; i < ctx->prof_n; ++i) {
+        dp_prof_rec r = ctx->prof[i];
+        if (r.kind == (int)kind) {
+            float t = 0.f;
+            DP_HIP_CHECK(ctx, hipEventElapsedTime(&t, r.start, r.stop));
+            ms += t;
+            work += r.work;
+            ++cnt;
+        }
+    }
+    // compact: drop the records just read, keep the others (event objects are swapped, never leaked)
+    for (int i = 0; i < ctx->prof_n; ++i) {
+        if (ctx->prof[i].kind != (int)kind) {
+            if (i != keep) {
+                dp_prof_rec t = ctx->prof[keep];
+                ctx->prof[keep] = ctx->prof[i];
+                ctx->prof[i] = t;
+            }
+            ++keep;
+        }
+    }
+    ctx->prof_n = keep;
+    if (ms_total) *ms_total = ms;
+    if (launches) *launches = cnt;
+    if (work_total) *work_total = work;
     return DP_OK;
 }
 

@@ -6,6 +6,13 @@
 
 #include "dpclip.h"
 
+struct dp_prof_rec {
+    hipEvent_t start, stop;
+    int kind;
+    double work;
+};
+constexpr int DP_PROF_CAP = 65536;
+
 struct dp_ctx {
     hipStream_t stream;
     int device;
@@ -14,7 +21,34 @@ struct dp_ctx {
     int* err_word;    // device: bit 0 = token id out of range
     float* cbuf;      // device: clip factors of the current micro-batch
     int cbuf_cap;     // capacity of cbuf in floats
+    int prof_on;
+    dp_prof_rec* prof;  // DP_PROF_CAP records; events are created on first use and reused
+    int prof_n;         // records in use
+    int prof_made;      // records whose events exist
     char msg[256];
+};
+
+// Brackets one kernel launch with events when profiling is on (no-op otherwise).
+struct dp_prof_scope {
+    dp_ctx* ctx;
+    dp_prof_rec* rec;
+    dp_prof_scope(dp_ctx* c, int kind, double work) : ctx(c), rec(nullptr) {
+        if (!c->prof_on || c->prof_n >= DP_PROF_CAP) return;
+        dp_prof_rec* r = &c->prof[c->prof_n];
+        if (c->prof_n >= c->prof_made) {
+            if (hipEventCreate(&r->start) != hipSuccess) return;
+            if (hipEventCreate(&r->stop) != hipSuccess) { (void)hipEventDestroy(r->start); return; }
+            c->prof_made = c->prof_n + 1;
+        }
+        r->kind = kind;
+        r->work = work;
+        if (hipEventRecord(r->start, c->stream) != hipSuccess) return;
+        rec = r;
+        c->prof_n++;
+    }
+    ~dp_prof_scope() {
+        if (rec) (void)hipEventRecord(rec->stop, ctx->stream);
+    }
 };
 
 #define DP_SET_ERR(ctx, ...) snprintf((ctx)->msg, sizeof((ctx)->msg), __VA_ARGS__)

@@ -242,7 +242,9 @@ dp_status dpk_gram_sqnorms(dp_ctx* ctx, const void* A, const void* G, dp_dtype d
                                               2 * 2 * GB * GLD * (int)sizeof(uint16_t)));
         lds_attr_set = true;
     }
+    const double bytes = 2.0 * (double)B * T * ((double)d_in + d_out);
     if (npairs == 1) {
+        dp_prof_scope prof(ctx, DP_PROF_GRAM, bytes);
         hipLaunchKernelGGL(gram_bf16_kernel, dim3(B), dim3(256), lds, ctx->stream, (const uint16_t*)A,
                            (const uint16_t*)G, B, T, d_in, d_out, has_bias, nblk, 1, sqnorms, 1);
         DP_LAUNCH_CHECK(ctx, "gram_bf16");
@@ -260,8 +262,11 @@ dp_status dpk_gram_sqnorms(dp_ctx* ctx, const void* A, const void* G, dp_dtype d
         DP_SET_ERR(ctx, "workspace too small for %d x %ld Gram partials", B, npairs);
         return DP_ERR_WORKSPACE;
     }
-    hipLaunchKernelGGL(gram_bf16_kernel, dim3((unsigned)nwg), dim3(256), lds, ctx->stream, (const uint16_t*)A,
-                       (const uint16_t*)G, B, T, d_in, d_out, has_bias, nblk, (int)npairs, part, 0);
+    {
+        dp_prof_scope prof(ctx, DP_PROF_GRAM, bytes);
+        hipLaunchKernelGGL(gram_bf16_kernel, dim3((unsigned)nwg), dim3(256), lds, ctx->stream, (const uint16_t*)A,
+                           (const uint16_t*)G, B, T, d_in, d_out, has_bias, nblk, (int)npairs, part, 0);
+    }
     DP_LAUNCH_CHECK(ctx, "gram_bf16");
     return dpk_finish_partials(ctx, part, B, (int)npairs, sqnorms);
 }

@@ -147,12 +147,23 @@ __global__ __launch_bounds__(256) void reduce_partials_vec4_kernel(const float4*
                                                                    float4* __restrict__ out) {
     const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (j >= n4) return;
+    float4 o = out[j];
     float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int r = 0; r < R; ++r) {
+    int r = 0;
+    // eight independent 16-byte loads in flight per thread; the additions keep the order r = 0, 1, 2, ...
+    for (; r + 8 <= R; r += 8) {
+        float4 p[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) p[u] = part[(size_t)(r + u) * stride4 + j];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            t.x += p[u].x; t.y += p[u].y; t.z += p[u].z; t.w += p[u].w;
+        }
+    }
+    for (; r < R; ++r) {
         const float4 p = part[(size_t)r * stride4 + j];
         t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
     }
-    float4 o = out[j];
     o.x += t.x; o.y += t.y; o.z += t.z; o.w += t.w;
     out[j] = o;
 }

@@ -232,6 +232,7 @@ dp_status dpk_noise_adamw(dp_ctx* ctx, float* params, float* m, float* v, float*
     a.eps = eps;
     a.wd = wd;
     const bool noise = sigma != 0.f;
+    dp_prof_scope prof(ctx, DP_PROF_ADAMW, (zero_sum ? 32.0 : 28.0) * (double)n);
     if (noise && zero_sum) return launch_adamw<true, true>(ctx, params, m, v, sum, n, off, seed, step, a);
     if (noise) return launch_adamw<true, false>(ctx, params, m, v, sum, n, off, seed, step, a);
     if (zero_sum) return launch_adamw<false, true>(ctx, params, m, v, sum, n, off, seed, step, a);

@@ -5,98 +5,85 @@
 //
 // Both are "TN" contractions: the contraction index (token row k) is the SLOW index of both operands in
 // memory, while v_mfma_f32_32x32x16_bf16 wants each lane to hold 8 consecutive k for one output row/column.
-// The kernel stages [k][p] tiles in LDS exactly as they lie in memory (16-byte coalesced global loads,
-// 16-byte LDS stores), and each lane then reads, for 8 consecutive k rows, the MI (NI) adjacent columns it
-// owns (one 8-byte LDS read per row when MI = 4) and regroups them with v_perm_b32 into MI fragments.
-// Lane m of fragment j therefore holds column  MI*m + j  of the wave tile: the MFMA row index is a
-// permutation of the tile's columns, undone for free in the epilogue, where a lane ends up with NI
-// consecutive output columns per row and stores them as one 16-byte vector.
+// Tiles are staged in LDS as they lie in memory ([k][column], 16-byte chunks) and fragments are fetched
+// with the gfx950 transposing LDS read (ds_read_b64_tr_b16): inside a group of 16 lanes, lane i supplies
+// the address of 4 adjacent columns of row k0 + i/4 and receives column i of rows k0..k0+3, so two reads
+// give a lane its 8 consecutive k.  No permute instructions, natural output layout.
 //
-// The clip factor c_i multiplies the rows of G in fp32 while the tile is staged (once per element per
-// workgroup) and the product is rounded to bf16 (nearest even); accumulation is fp32 in the MFMA.
+// LDS bank conflicts: the four rows a 16-lane group touches are one row pitch (512 B or 256 B) apart, i.e.
+// in the same banks.  The 16-byte chunk index is therefore XOR-ed with 4*(row % 4) when a chunk is stored,
+// which spreads the four rows of a group, and the two groups of a half-wave, over 256 distinct bytes.
+//
+// Pipeline per workgroup (4 waves as 2 x 2, one wave per SIMD because the 256 x 256 fp32 tile takes all
+// 256 accumulator registers of a lane): global -> registers up to four stages ahead (buffer loads: rows
+// past the split's range read as zero, so there is no branch around a load), registers -> LDS ring of
+// three stages, LDS -> fragments one 16-row step ahead of the MFMAs, also across the one barrier per stage.
+//
+// The clip factor c_i multiplies the rows of G in fp32 while they sit in registers between the global load
+// and the LDS store (once per element per workgroup); the product is rounded to bf16 (nearest even, by
+// v_cvt_pk_bf16_f32); accumulation is fp32 in the MFMA.
 //
 // Roofline: MFMA.  2*B*T*d_in*d_out flops per layer against (d_in + d_out)*B*T*2 bytes read once.
+#include <type_traits>
+
 #include "dp_common.h"
 
 namespace {
 
-constexpr int BK = 32;  // token rows per staged tile
+constexpr int BK = 32;      // token rows per staged tile
+constexpr int NSTAGE = 3;   // LDS ring
 
 enum { EPI_STORE = 0, EPI_ADD = 1, EPI_SQNORM = 2 };
 
 struct WgemmArgs {
     const uint16_t* A;   // [K, d_in]
     const uint16_t* G;   // [K, d_out]
-    const float* c;      // [B] clip factors (nullptr: weight 1)
+    const float* c;      // [B] clip factors (unused when the kernel is built without scaling)
     int T, d_in, d_out;
     long K;              // total rows
-    long rows_per_split; // multiple of BK
+    long rows_per_split; // multiple of BK (or T for the per-example materialisation)
     int tiles_m, tiles_n, nsplit;
     float* out;          // EPI_STORE: [nsplit][d_in][d_out]; EPI_ADD: [d_in][d_out]; EPI_SQNORM: [nsplit][ntiles]
     int xcd_map;         // 1: split index interleaved over the 8 XCDs
 };
 
-__device__ __forceinline__ uint32_t perm_lo(uint32_t hi_src, uint32_t lo_src) {
-    return __builtin_amdgcn_perm(hi_src, lo_src, 0x05040100u);  // [lo_src.lo16, hi_src.lo16]
-}
-__device__ __forceinline__ uint32_t perm_hi(uint32_t hi_src, uint32_t lo_src) {
-    return __builtin_amdgcn_perm(hi_src, lo_src, 0x07060302u);  // [lo_src.hi16, hi_src.hi16]
-}
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
 
-template <int NV>
-struct RawRow;  // NV 32-bit words = 2*NV adjacent bf16 columns of one k row
-template <>
-struct RawRow<1> {
-    uint32_t w[1];
-    __device__ __forceinline__ void load(const uint16_t* p) { w[0] = *reinterpret_cast<const uint32_t*>(p); }
-};
-template <>
-struct RawRow<2> {
-    uint32_t w[2];
-    __device__ __forceinline__ void load(const uint16_t* p) {
-        const uint2 v = *reinterpret_cast<const uint2*>(p);
-        w[0] = v.x;
-        w[1] = v.y;
-    }
-};
-
-// Build the NF (= 2 or 4) MFMA fragments of one operand for one 16-row k step.
-// tile: LDS tile [BK][LD]; col0: first of this lane's NF adjacent columns; krow0: first of its 8 k rows.
-template <int NF, int LD>
-__device__ __forceinline__ void build_frags(const uint16_t* __restrict__ tile, int col0, int krow0, bf16x8_t frag[NF]) {
-    RawRow<NF / 2> raw[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) raw[e].load(tile + (krow0 + e) * LD + col0);
-#pragma unroll
-    for (int j2 = 0; j2 < NF / 2; ++j2) {
-        uint32_t lo[4], hi[4];
-#pragma unroll
-        for (int e2 = 0; e2 < 4; ++e2) {
-            lo[e2] = perm_lo(raw[2 * e2 + 1].w[j2], raw[2 * e2].w[j2]);
-            hi[e2] = perm_hi(raw[2 * e2 + 1].w[j2], raw[2 * e2].w[j2]);
-        }
-        frag[2 * j2] = __builtin_bit_cast(bf16x8_t, make_uint4(lo[0], lo[1], lo[2], lo[3]));
-        frag[2 * j2 + 1] = __builtin_bit_cast(bf16x8_t, make_uint4(hi[0], hi[1], hi[2], hi[3]));
-    }
+__device__ __forceinline__ uint32_t scale_pair(uint32_t w, float s) {
+    const f32x2_t x = {dp_bf16_lo(w) * s, dp_bf16_hi(w) * s};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2_t));  // v_cvt_pk_bf16_f32 (RNE)
 }
-
-__device__ __forceinline__ uint4 scale_bf16x8(uint4 v, float s) {
-    uint4 o;
-    o.x = dp_pack_bf16x2(dp_bf16_lo(v.x) * s, dp_bf16_hi(v.x) * s);
-    o.y = dp_pack_bf16x2(dp_bf16_lo(v.y) * s, dp_bf16_hi(v.y) * s);
-    o.z = dp_pack_bf16x2(dp_bf16_lo(v.z) * s, dp_bf16_hi(v.z) * s);
-    o.w = dp_pack_bf16x2(dp_bf16_lo(v.w) * s, dp_bf16_hi(v.w) * s);
+__device__ __forceinline__ u32x4_t scale_bf16x8(u32x4_t v, float s) {
+    u32x4_t o;
+    o[0] = scale_pair(v[0], s);
+    o[1] = scale_pair(v[1], s);
+    o[2] = scale_pair(v[2], s);
+    o[3] = scale_pair(v[3], s);
     return o;
 }
 
+// 8 consecutive k (rows) of one column, as an MFMA operand: two transposing reads of 4 rows each.
+__device__ __forceinline__ bf16x8_t read_frag(const uint16_t* lds_lane_ptr, int row_pitch_elems) {
+    typedef s16x4_t __attribute__((address_space(3))) * lptr;
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(lds_lane_ptr));
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(lds_lane_ptr + 4 * row_pitch_elems));
+    const s16x8_t v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8_t, v);
+}
+
 // Workgroup = 4 waves as 2 x 2; wave tile (32*MI) x (32*NI); block tile BM x BN = (64*MI) x (64*NI).
-template <int MI, int NI, int EPI>
+// SCALE: multiply G rows by c.  UNIFORM_C: T % BK == 0, so all rows of a stage belong to one example.
+template <int MI, int NI, int EPI, bool SCALE, bool UNIFORM_C>
 __global__ __launch_bounds__(256) void wgemm_bf16_kernel(WgemmArgs a) {
     constexpr int BM = 64 * MI, BN = 64 * NI;
     constexpr int WM = 32 * MI, WN = 32 * NI;
-    constexpr int LDA = BM + 8, LDG = BN + 8;  // bf16 elements; +16 B keeps 16-byte alignment of every row
-    __shared__ __attribute__((aligned(16))) uint16_t As[2][BK * LDA];
-    __shared__ __attribute__((aligned(16))) uint16_t Gs[2][BK * LDG];
+    constexpr int CA = BM / 8, CG = BN / 8;  // 16-byte chunks per tile row
+    __shared__ __attribute__((aligned(16))) uint16_t As[NSTAGE][BK * BM];
+    __shared__ __attribute__((aligned(16))) uint16_t Gs[NSTAGE][BK * BN];
     __shared__ float wred[4];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -116,7 +103,49 @@ __global__ __launch_bounds__(256) void wgemm_bf16_kernel(WgemmArgs a) {
     const int p0 = pm * BM, q0 = qn * BN;
     const long k_lo = (long)split * a.rows_per_split;
     const long k_hi = k_lo + a.rows_per_split < a.K ? k_lo + a.rows_per_split : a.K;
-    const int nsteps = k_hi > k_lo ? (int)((k_hi - k_lo + BK - 1) / BK) : 0;
+    const int nrows = k_hi > k_lo ? (int)(k_hi - k_lo) : 0;
+    const int nsteps = (nrows + BK - 1) / BK;
+
+    // Buffer resources over this split's rows: any access past the last row returns zero.
+    const __amdgpu_buffer_rsrc_t rA = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(a.A + (size_t)k_lo * a.d_in), 0, (int)((size_t)nrows * a.d_in * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rG = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(a.G + (size_t)k_lo * a.d_out), 0, (int)((size_t)nrows * a.d_out * 2), 0x00020000);
+
+    // Per-thread staging slots: slot j moves the 16-byte chunk at tile row `row`, LDS chunk position `cpos`;
+    // the global chunk it holds is cpos ^ swizzle(row).  Columns past the layer width read neighbouring
+    // (valid or zero) data and only feed output columns that are never stored.
+    int voffA[MI], ldsA[MI], voffG[NI], ldsG[NI], rowG[NI];
+#pragma unroll
+    for (int j = 0; j < MI; ++j) {
+        const int id = tid + 256 * j, row = id / CA, cpos = id % CA;
+        const int cg = cpos ^ ((row & 3) << 2);
+        voffA[j] = (row * a.d_in + p0 + cg * 8) * 2;
+        ldsA[j] = row * BM + cpos * 8;
+    }
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+        const int id = tid + 256 * j, row = id / CG, cpos = id % CG;
+        const int cg = cpos ^ ((row & 3) << 2);
+        voffG[j] = (row * a.d_out + q0 + cg * 8) * 2;
+        ldsG[j] = row * BN + cpos * 8;
+        rowG[j] = row;
+    }
+    // Fragment read offsets (elements) inside a stage for k step 0: lane l reads row 8*(l/32) + (l%16)/4
+    // (+4 for its second read), columns 32*i + 16*((l/16)%2) + 4*(l%4) .. +3 of operand tile i.
+    const int frow = 8 * (lane >> 5) + ((lane & 15) >> 2);
+    const int fsw = frow & 3;
+    int foffA[MI], foffG[NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+        const int col = wr * WM + 32 * i + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+        foffA[i] = frow * BM + (((col >> 3) ^ (fsw << 2)) << 3) + (col & 7);
+    }
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int col = wc * WN + 32 * i + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+        foffG[i] = frow * BN + (((col >> 3) ^ (fsw << 2)) << 3) + (col & 7);
+    }
 
     f32x16_t acc[MI][NI];
 #pragma unroll
@@ -126,115 +155,131 @@ __global__ __launch_bounds__(256) void wgemm_bf16_kernel(WgemmArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    uint4 ra[MI], rg[NI];
-    auto gload = [&](long kbase) {
+    u32x4_t ra[2][MI], rg[2][NI];
+    float cs[2][NI];
+    auto gload = [&](int set, int st) {  // stage st -> register set
+        const int soffA = st * BK * a.d_in * 2, soffG = st * BK * a.d_out * 2;
 #pragma unroll
-        for (int j = 0; j < MI; ++j) {
-            const int id = tid + 256 * j;
-            const int row = id / (BM / 8), cc = (id % (BM / 8)) * 8;
-            const long k = kbase + row;
-            if (k < k_hi && p0 + cc < a.d_in)
-                ra[j] = *reinterpret_cast<const uint4*>(a.A + (size_t)k * a.d_in + p0 + cc);
-            else
-                ra[j] = make_uint4(0u, 0u, 0u, 0u);
-        }
+        for (int j = 0; j < MI; ++j) ra[set][j] = __builtin_amdgcn_raw_buffer_load_b128(rA, voffA[j], soffA, 0);
 #pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            const int id = tid + 256 * j;
-            const int row = id / (BN / 8), cc = (id % (BN / 8)) * 8;
-            const long k = kbase + row;
-            if (k < k_hi && q0 + cc < a.d_out) {
-                const uint4 v = *reinterpret_cast<const uint4*>(a.G + (size_t)k * a.d_out + q0 + cc);
-                rg[j] = a.c ? scale_bf16x8(v, a.c[(uint32_t)k / (uint32_t)a.T]) : v;
+        for (int j = 0; j < NI; ++j) rg[set][j] = __builtin_amdgcn_raw_buffer_load_b128(rG, voffG[j], soffG, 0);
+        if constexpr (SCALE) {
+            if constexpr (UNIFORM_C) {
+                const long k = k_lo + (long)st * BK;
+                const float s = a.c[(uint32_t)(k < a.K ? k : a.K - 1) / (uint32_t)a.T];
+#pragma unroll
+                for (int j = 0; j < NI; ++j) cs[set][j] = s;
             } else {
-                rg[j] = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    long k = k_lo + (long)st * BK + rowG[j];
+                    if (k >= a.K) k = a.K - 1;
+                    cs[set][j] = a.c[(uint32_t)k / (uint32_t)a.T];
+                }
             }
         }
     };
-    auto lstore = [&](int stage) {
+    auto lstore = [&](int set, int buf) {
 #pragma unroll
-        for (int j = 0; j < MI; ++j) {
-            const int id = tid + 256 * j;
-            const int row = id / (BM / 8), cc = (id % (BM / 8)) * 8;
-            *reinterpret_cast<uint4*>(&As[stage][row * LDA + cc]) = ra[j];
-        }
+        for (int j = 0; j < MI; ++j) *reinterpret_cast<u32x4_t*>(&As[buf][ldsA[j]]) = ra[set][j];
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
-            const int id = tid + 256 * j;
-            const int row = id / (BN / 8), cc = (id % (BN / 8)) * 8;
-            *reinterpret_cast<uint4*>(&Gs[stage][row * LDG + cc]) = rg[j];
+            u32x4_t v = rg[set][j];
+            if constexpr (SCALE) v = scale_bf16x8(v, cs[set][j]);
+            *reinterpret_cast<u32x4_t*>(&Gs[buf][ldsG[j]]) = v;
         }
     };
-
-    if (nsteps > 0) {
-        gload(k_lo);
-        lstore(0);
-    }
-    __syncthreads();
-    for (int s = 0; s < nsteps; ++s) {
-        const int cur = s & 1;
-        const bool more = s + 1 < nsteps;
-        if (more) gload(k_lo + (long)(s + 1) * BK);
+    auto load_frags = [&](int buf, int kk, bf16x8_t* fa, bf16x8_t* fg) {
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            const int krow0 = kk * 16 + (lane >> 5) * 8;
-            bf16x8_t fa[MI], fg[NI];
-            build_frags<MI, LDA>(As[cur], wr * WM + MI * (lane & 31), krow0, fa);
-            build_frags<NI, LDG>(Gs[cur], wc * WN + NI * (lane & 31), krow0, fg);
+        for (int i = 0; i < MI; ++i) fa[i] = read_frag(&As[buf][kk * 16 * BM + foffA[i]], BM);
 #pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int j = 0; j < NI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fg[j], acc[i][j], 0, 0, 0);
-        }
-        if (more) lstore(cur ^ 1);
-        __syncthreads();
-    }
-
-    if (EPI == EPI_SQNORM) {
-        float s = 0.f;
+        for (int i = 0; i < NI; ++i) fg[i] = read_frag(&Gs[buf][kk * 16 * BN + foffG[i]], BN);
+    };
+    auto mma = [&](const bf16x8_t* fa, const bf16x8_t* fg) {
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
             for (int j = 0; j < NI; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fg[j], acc[i][j], 0, 0, 0);
+    };
+
+    // The stage count is rounded up to even so that the loop body can be unrolled twice with the register
+    // sets fixed at compile time; stages past the range load zeros (buffer bounds) and add nothing.
+    const int nsteps2 = (nsteps + 1) & ~1;
+
+    // ---- prologue: stages 0 and 1 into LDS, stages 2 and 3 in flight in registers ----
+    bf16x8_t fa0[MI], fg0[NI], fa1[MI], fg1[NI];
+    gload(0, 0);
+    gload(1, 1);
+    lstore(0, 0);
+    gload(0, 2);
+    lstore(1, 1);
+    gload(1, 3);
+    __syncthreads();
+    load_frags(0, 0, fa0, fg0);
+
+    // ---- main loop: iteration s computes stage s from LDS[s % 3]; stage s+1 is already visible in
+    // LDS[(s+1) % 3]; stage s+2 moves from register set s % 2 into LDS[(s+2) % 3] (the buffer read in
+    // iteration s-1, released by that iteration's barrier) and the set is reloaded with stage s+4.
+    // There is no branch in the body: everything past the last stage is zeros. ----
+    int buf = 0;
+    auto body = [&](int s, auto setc) {
+        constexpr int SET = decltype(setc)::value;
+        const int buf1 = buf == NSTAGE - 1 ? 0 : buf + 1;
+        const int buf2 = buf1 == NSTAGE - 1 ? 0 : buf1 + 1;
+        load_frags(buf, 1, fa1, fg1);
+        mma(fa0, fg0);
+        lstore(SET, buf2);
+        gload(SET, s + 4);
+        load_frags(buf1, 0, fa0, fg0);
+        mma(fa1, fg1);
+        __syncthreads();
+        buf = buf1;
+    };
+    for (int s = 0; s < nsteps2; s += 2) {
+        body(s, std::integral_constant<int, 0>());
+        body(s + 1, std::integral_constant<int, 1>());
+    }
+
+    // MFMA tile (i, j): accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+    if (EPI == EPI_SQNORM) {
+        // rows / columns past the layer's widths hold products of neighbouring data: leave them out
+        float s = 0.f;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) s += acc[i][j][r] * acc[i][j][r];
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int p = p0 + wr * WM + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    const int q = q0 + wc * WN + 32 * j + (lane & 31);
+                    const float v = (p < a.d_in && q < a.d_out) ? acc[i][j][r] : 0.f;
+                    s += v * v;
+                }
+            }
         const float tot = dp_block_sum<256>(s, wred);
         if (tid == 0) a.out[(size_t)split * ntiles + tile] = tot;
         return;
     }
 
-    // MFMA tile (i, j), accumulator register r of lane l holds output row m = 8*(r/4) + 4*(l/32) + r%4 and
-    // column n = l%32 of that tile, i.e. p = p0 + wr*WM + MI*m + i and q = q0 + wc*WN + NI*n + j.
     float* base = a.out + (EPI == EPI_STORE ? (size_t)split * a.d_in * a.d_out : (size_t)0);
-    const int qcol = q0 + wc * WN + NI * (lane & 31);
-    if (qcol < a.d_out) {  // d_out % 8 == 0 and NI divides 8: a lane's NI columns are all in or all out
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                const int p = p0 + wr * WM + MI * m + i;
-                if (p < a.d_in) {
-                    float* dst = base + (size_t)p * a.d_out + qcol;
-                    if constexpr (NI == 4) {
-                        float4 v = make_float4(acc[i][0][r], acc[i][1][r], acc[i][2][r], acc[i][3][r]);
-                        if (EPI == EPI_ADD) {
-                            const float4 o = *reinterpret_cast<const float4*>(dst);
-                            v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
-                        }
-                        *reinterpret_cast<float4*>(dst) = v;
-                    } else {
-                        float2 v = make_float2(acc[i][0][r], acc[i][1][r]);
-                        if (EPI == EPI_ADD) {
-                            const float2 o = *reinterpret_cast<const float2*>(dst);
-                            v.x += o.x; v.y += o.y;
-                        }
-                        *reinterpret_cast<float2*>(dst) = v;
+        for (int r = 0; r < 16; ++r) {
+            const int p = p0 + wr * WM + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            if (p < a.d_in) {
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    const int q = q0 + wc * WN + 32 * j + (lane & 31);
+                    if (q < a.d_out) {
+                        float* dst = base + (size_t)p * a.d_out + q;
+                        if (EPI == EPI_ADD) *dst += acc[i][j][r];
+                        else *dst = acc[i][j][r];
                     }
                 }
             }
-    }
+        }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -284,15 +329,32 @@ __global__ __launch_bounds__(256) void wgemm_f32_kernel(const float* __restrict_
         }
 }
 
-template <int MI, int NI, int EPI>
+template <int MI, int NI, int EPI, bool SCALE, bool UNIFORM_C>
 void wgemm_launch(dp_ctx* ctx, const WgemmArgs& a, unsigned grid) {
-    hipLaunchKernelGGL((wgemm_bf16_kernel<MI, NI, EPI>), dim3(grid), dim3(256), 0, ctx->stream, a);
+    hipLaunchKernelGGL((wgemm_bf16_kernel<MI, NI, EPI, SCALE, UNIFORM_C>), dim3(grid), dim3(256), 0, ctx->stream, a);
+}
+
+template <int EPI, bool SCALE>
+void wgemm_dispatch(dp_ctx* ctx, const WgemmArgs& a, unsigned grid, bool big, bool uniform) {
+    if (big) {
+        if (uniform) wgemm_launch<4, 4, EPI, SCALE, true>(ctx, a, grid);
+        else wgemm_launch<4, 4, EPI, SCALE, false>(ctx, a, grid);
+    } else {
+        if (uniform) wgemm_launch<2, 2, EPI, SCALE, true>(ctx, a, grid);
+        else wgemm_launch<2, 2, EPI, SCALE, false>(ctx, a, grid);
+    }
 }
 
 }  // namespace
 
 // Tile shape: 256 x 256 when both dimensions are at least that large, otherwise 128 x 128.
 static inline bool big_tile(int d_in, int d_out) { return d_in >= 256 && d_out >= 256; }
+
+// A split's rows of one operand must stay below 2^31 bytes (32-bit buffer offsets).
+static inline bool range_ok(long rows, int d_in, int d_out) {
+    const long w = d_in > d_out ? d_in : d_out;
+    return (rows + 4 * BK) * w * 2 < (1l << 31);
+}
 
 dp_status dpk_weighted_gemm(dp_ctx* ctx, const void* A, const void* G, dp_dtype dt, int B, int T, int d_in, int d_out,
                             const float* c, float* sum_W) {
@@ -329,6 +391,7 @@ dp_status dpk_weighted_gemm(dp_ctx* ctx, const void* A, const void* G, dp_dtype 
         if (nsplit >= 8) nsplit = (nsplit / 8) * 8;
         if (nsplit < 1) nsplit = 1;
     }
+    while (!range_ok((ksteps + nsplit - 1) / nsplit * BK, d_in, d_out)) nsplit *= 2;
     dp_ws_alloc ws(ctx);
     float* part = nullptr;
     while (nsplit > 1) {
@@ -338,6 +401,10 @@ dp_status dpk_weighted_gemm(dp_ctx* ctx, const void* A, const void* G, dp_dtype 
     }
     const long steps_per = (ksteps + nsplit - 1) / nsplit;
     a.rows_per_split = steps_per * BK;
+    if (!range_ok(a.rows_per_split, d_in, d_out)) {
+        DP_SET_ERR(ctx, "dp_clip_accumulate_dense: workspace too small to split %ld rows", K);
+        return DP_ERR_WORKSPACE;
+    }
     nsplit = (ksteps + steps_per - 1) / steps_per;
     a.nsplit = (int)nsplit;
     a.xcd_map = nsplit >= 8 ? 1 : 0;
@@ -346,16 +413,20 @@ dp_status dpk_weighted_gemm(dp_ctx* ctx, const void* A, const void* G, dp_dtype 
         DP_SET_ERR(ctx, "dp_clip_accumulate_dense: too many tiles");
         return DP_ERR_SHAPE;
     }
+    const bool uniform = T % BK == 0;
+    const double flops = 2.0 * (double)K * d_in * d_out;
     if (nsplit == 1) {
         a.out = sum_W;
-        if (big) wgemm_launch<4, 4, EPI_ADD>(ctx, a, (unsigned)nwg);
-        else wgemm_launch<2, 2, EPI_ADD>(ctx, a, (unsigned)nwg);
+        dp_prof_scope prof(ctx, DP_PROF_WGEMM, flops);
+        wgemm_dispatch<EPI_ADD, true>(ctx, a, (unsigned)nwg, big, uniform);
         DP_LAUNCH_CHECK(ctx, "wgemm_bf16");
         return DP_OK;
     }
     a.out = part;
-    if (big) wgemm_launch<4, 4, EPI_STORE>(ctx, a, (unsigned)nwg);
-    else wgemm_launch<2, 2, EPI_STORE>(ctx, a, (unsigned)nwg);
+    {
+        dp_prof_scope prof(ctx, DP_PROF_WGEMM, flops);
+        wgemm_dispatch<EPI_STORE, true>(ctx, a, (unsigned)nwg, big, uniform);
+    }
     DP_LAUNCH_CHECK(ctx, "wgemm_bf16");
     return dpk_reduce_partials(ctx, part, (int)nsplit, (size_t)d_in * d_out, (size_t)d_in * d_out, sum_W);
 }
@@ -381,6 +452,10 @@ dp_status dpk_materialise_sqnorms(dp_ctx* ctx, const void* A, const void* G, dp_
         a.nsplit = B;  // one "split" per example: rows [i*T, (i+1)*T)
         a.rows_per_split = T;
         a.xcd_map = 0;
+        if (!range_ok(T, d_in, d_out)) {
+            DP_SET_ERR(ctx, "dp_sqnorms_dense: one example's activations exceed 2 GiB");
+            return DP_ERR_SHAPE;
+        }
         const int ntiles = a.tiles_m * a.tiles_n;
         const long nwg = (long)B * ntiles;
         if (nwg > 0x7FFFFFFFl) {
@@ -394,8 +469,7 @@ dp_status dpk_materialise_sqnorms(dp_ctx* ctx, const void* A, const void* G, dp_
             return DP_ERR_WORKSPACE;
         }
         a.out = part;
-        if (big) wgemm_launch<4, 4, EPI_SQNORM>(ctx, a, (unsigned)nwg);
-        else wgemm_launch<2, 2, EPI_SQNORM>(ctx, a, (unsigned)nwg);
+        wgemm_dispatch<EPI_SQNORM, false>(ctx, a, (unsigned)nwg, big, true);
         DP_LAUNCH_CHECK(ctx, "wgemm_bf16 (materialise)");
         st = dpk_finish_partials(ctx, part, B, ntiles, sqnorms);
     }

@@ -1,0 +1,76 @@
+"""Host-side step driver: walks a layer manifest and issues the C-ABI calls of one DP-SGD step
+(Algorithm 1: per-example clip, sum over the micro-batch, accumulate over micro-batches, then noise
+and the Adam update with decoupled weight decay).  Host logic only: every computation is a library call."""
+from __future__ import annotations
+
+from . import binding as B_
+
+
+class StepRunner:
+    """Owns the flat fp32 state (theta, m, v, clip-weighted sum S) of a manifest and the per-example
+    squared-norm buffer.  Tensors of the flat space follow the manifest order (LayerSpec.tensors())."""
+
+    def __init__(self, ctx, manifest, max_batch, device="cuda:0"):
+        import torch
+
+        self.ctx = ctx
+        self.manifest = manifest
+        self.offsets = []  # per layer: list of (offset, shape)
+        off = 0
+        for spec in manifest:
+            cur = []
+            for _, shp in spec.tensors():
+                n = 1
+                for s in shp:
+                    n *= s
+                off = (off + 3) // 4 * 4  # keep every tensor 16-byte aligned inside the flat buffers
+                cur.append((off, shp))
+                off += n
+            self.offsets.append(cur)
+        self.P = off
+        self.S = torch.zeros(self.P, dtype=torch.float32, device=device)
+        self.theta = torch.zeros(self.P, dtype=torch.float32, device=device)
+        self.m = torch.zeros(self.P, dtype=torch.float32, device=device)
+        self.v = torch.zeros(self.P, dtype=torch.float32, device=device)
+        self.sqnorms = torch.zeros(max_batch, dtype=torch.float32, device=device)
+
+    def view(self, buf, layer, k):
+        off, shp = self.offsets[layer][k]
+        n = 1
+        for s in shp:
+            n *= s
+        return buf[off:off + n].view(*shp)
+
+    def pass1(self, layers, path=B_.DP_PATH_AUTO):
+        """Per-example squared global norms of one micro-batch: sqnorms[:B] = sum over all layers."""
+        ctx = self.ctx
+        nB = layers[0]["G"].shape[0]
+        n = self.sqnorms[:nB]
+        ctx.zero_f32(n)
+        for l in layers:
+            if l["kind"] == "dense":
+                ctx.sqnorms_dense(l["A"], l["G"], l["has_bias"], path, n)
+            elif l["kind"] == "layernorm":
+                ctx.sqnorms_layernorm(l["X"], l["G"], n)
+            else:
+                ctx.sqnorms_embedding(l["ids"], l["G"], l["V"], l["distinct"], n)
+        return n
+
+    def pass2(self, layers, C):
+        """S += sum_i clip(grad_i, C) for one micro-batch, using the norms left by pass1."""
+        ctx = self.ctx
+        nB = layers[0]["G"].shape[0]
+        n = self.sqnorms[:nB]
+        for k, l in enumerate(layers):
+            if l["kind"] == "dense":
+                sb = self.view(self.S, k, 1) if l["has_bias"] else None
+                ctx.clip_accumulate_dense(l["A"], l["G"], C, n, self.view(self.S, k, 0), sb)
+            elif l["kind"] == "layernorm":
+                ctx.clip_accumulate_layernorm(l["X"], l["G"], C, n, self.view(self.S, k, 0), self.view(self.S, k, 1))
+            else:
+                ctx.clip_accumulate_embedding(l["ids"], l["G"], l["V"], C, n, self.view(self.S, k, 0))
+
+    def update(self, *, sigma, C, seed, step, batch_size, lr, beta1, beta2, eps=1e-11, weight_decay, zero_sum=True):
+        self.ctx.noise_adamw(self.theta, self.m, self.v, self.S, sigma=sigma, C=C, seed=seed, step=step,
+                             batch_size=batch_size, lr=lr, beta1=beta1, beta2=beta2, eps=eps,
+                             weight_decay=weight_decay, zero_sum=zero_sum)
