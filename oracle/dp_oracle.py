@@ -160,6 +160,20 @@ def clip_accumulate_dense(A, G, c, has_bias: bool):
     return S_W, (S_b if has_bias else None)
 
 
+def clip_accumulate_dense_entries(A_cols, G_cols, c) -> np.ndarray:
+    """Selected entries of the clip-weighted dense sum, one by one: A_cols[i, t, k] = A[i, t, p_k] and
+    G_cols[i, t, k] = G[i, t, q_k] for the k-th sampled entry (p_k, q_k).  For every example the entry
+    of its own gradient, sum_t A[i,t,p] G[i,t,q], is formed explicitly and added with weight c_i.
+    (For full-size workloads, where the whole d_in x d_out sum is out of the oracle's reach.)"""
+    A_cols = to_f64(A_cols)
+    G_cols = to_f64(G_cols)
+    out = np.zeros(A_cols.shape[2], dtype=np.float64)
+    for i in range(A_cols.shape[0]):
+        entry_i = np.sum(A_cols[i] * G_cols[i], axis=0)
+        out += c[i] * entry_i
+    return out
+
+
 def clip_accumulate_layernorm(X, G, c):
     d = X.shape[2]
     S_g = np.zeros(d, dtype=np.float64)

@@ -216,6 +216,15 @@ def test_clip_noop_equals_flat_gemm():
     np.testing.assert_allclose(S_b, Gf.sum(0).numpy(), rtol=1e-11, atol=1e-13)
 
 
+def test_sampled_entries_equal_full_sum():
+    A, G = _c1_like(B=5, T=7, d_in=6, d_out=4, seed=40)
+    c = np.linspace(0.2, 1.0, 5)
+    S_W, _ = orc.clip_accumulate_dense(A, G, c, False)
+    ps, qs = np.array([0, 5, 2, 3]), np.array([3, 0, 2, 1])
+    got = orc.clip_accumulate_dense_entries(A[:, :, ps], G[:, :, qs], c)
+    np.testing.assert_allclose(got, S_W[ps, qs], rtol=1e-12)
+
+
 def test_clip_mixed_branches():
     B = 16
     scale = syn.example_scales(B, 1e-4, 1.0, 5)
