@@ -261,10 +261,7 @@ dp_status dp_clip_accumulate_dense(dp_ctx* ctx, const void* A, const void* G, dp
     if (dtype == DP_BF16 && ((uintptr_t)sum_W & 15)) FAIL(ctx, DP_ERR_ALIGN, "sum_W is not 16-byte aligned");
     TRY(check_clip(ctx, C, B));
     if (B == 0 || T == 0 || d_out == 0) return DP_OK;
-    TRY(dpk_clip_factors(ctx, sqnorms, B, C, ctx->cbuf));
-    if (d_in > 0) TRY(dpk_weighted_gemm(ctx, A, G, dtype, B, T, d_in, d_out, ctx->cbuf, sum_W));
-    if (sum_b) TRY(dpk_colstat_sums(ctx, nullptr, G, dtype, B, T, d_out, ctx->cbuf, nullptr, sum_b));
-    return DP_OK;
+    return dpk_weighted_gemm(ctx, A, G, dtype, B, T, d_in, d_out, sqnorms, C, sum_W, sum_b);
 }
 
 dp_status dp_clip_accumulate_layernorm(dp_ctx* ctx, const void* Xhat, const void* G, dp_dtype dtype, int B, int T,

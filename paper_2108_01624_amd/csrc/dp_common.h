@@ -162,8 +162,9 @@ dp_status dpk_gram_sqnorms(dp_ctx*, const void* A, const void* G, dp_dtype, int 
                            int has_bias, float* sqnorms);
 dp_status dpk_materialise_sqnorms(dp_ctx*, const void* A, const void* G, dp_dtype, int B, int T, int d_in, int d_out,
                                   int has_bias, float* sqnorms);
+// sum_W += sum_i c_i A_i^T G_i and, if sum_b, sum_b += sum_i c_i sum_t G_i[t,:], with c_i from (sqnorms, C)
 dp_status dpk_weighted_gemm(dp_ctx*, const void* A, const void* G, dp_dtype, int B, int T, int d_in, int d_out,
-                            const float* c, float* sum_W);
+                            const float* sqnorms, float C, float* sum_W, float* sum_b);
 
 // column statistics shared by LayerNorm and dense-bias terms:
 //   sqnorms:  n[i] += [use_x] sum_j (sum_t g x)^2 + [use_1] sum_j (sum_t g)^2

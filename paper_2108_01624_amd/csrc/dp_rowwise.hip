@@ -168,6 +168,44 @@ __global__ __launch_bounds__(256) void reduce_partials_vec4_kernel(const float4*
     out[j] = o;
 }
 
+// Few outputs, many partials (column sums): 256 threads = 64 float4 columns x 4 partial groups.  Group g adds
+// the partials r = g, g+4, g+8, ... in ascending order; the four group sums are added as (0+1)+(2+3): fixed order.
+__global__ __launch_bounds__(256) void reduce_partials_tall_kernel(const float4* __restrict__ part, int R,
+                                                                   size_t stride4, size_t n4,
+                                                                   float4* __restrict__ out) {
+    __shared__ float4 red[4][64];
+    const int lane = threadIdx.x & 63, g = threadIdx.x >> 6;
+    const size_t j = (size_t)blockIdx.x * 64 + lane;
+    float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (j < n4) {
+        int r = g;
+        for (; r + 28 < R; r += 32) {
+            float4 p[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) p[u] = part[(size_t)(r + 4 * u) * stride4 + j];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                t.x += p[u].x; t.y += p[u].y; t.z += p[u].z; t.w += p[u].w;
+            }
+        }
+        for (; r < R; r += 4) {
+            const float4 p = part[(size_t)r * stride4 + j];
+            t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
+        }
+    }
+    red[g][lane] = t;
+    __syncthreads();
+    if (g == 0 && j < n4) {
+        const float4 a = red[0][lane], b = red[1][lane], c = red[2][lane], d = red[3][lane];
+        float4 o = out[j];
+        o.x += (a.x + b.x) + (c.x + d.x);
+        o.y += (a.y + b.y) + (c.y + d.y);
+        o.z += (a.z + b.z) + (c.z + d.z);
+        o.w += (a.w + b.w) + (c.w + d.w);
+        out[j] = o;
+    }
+}
+
 // ------------------------------------------------------------------------------------------------
 // embedding, per-example norms (pass 1): grid (B, ceil(d/(64*VW))), one wave per workgroup.
 // The wave ranks the example's T ids (stable counting rank in LDS), walks the rows in id order and adds
@@ -458,8 +496,13 @@ dp_status dpk_reduce_partials(dp_ctx* ctx, const float* part, int R, size_t stri
     if (n == 0) return DP_OK;
     if (n % 4 == 0 && stride % 4 == 0 && (((uintptr_t)part | (uintptr_t)out) & 15) == 0) {
         const size_t n4 = n / 4;
-        hipLaunchKernelGGL(reduce_partials_vec4_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, ctx->stream,
-                           reinterpret_cast<const float4*>(part), R, stride / 4, n4, reinterpret_cast<float4*>(out));
+        if (R >= 32 && n4 <= 16384)
+            hipLaunchKernelGGL(reduce_partials_tall_kernel, dim3((unsigned)((n4 + 63) / 64)), dim3(256), 0, ctx->stream,
+                               reinterpret_cast<const float4*>(part), R, stride / 4, n4, reinterpret_cast<float4*>(out));
+        else
+            hipLaunchKernelGGL(reduce_partials_vec4_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0,
+                               ctx->stream, reinterpret_cast<const float4*>(part), R, stride / 4, n4,
+                               reinterpret_cast<float4*>(out));
     } else {
         hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ctx->stream, part,
                            R, stride, n, out);
@@ -508,7 +551,7 @@ static dp_status colstat_sums_launch(dp_ctx* ctx, const void* X, const void* G, 
                                      float* out_x, float* out_1) {
     const long nrows = (long)B * T;
     const int J = (d + 64 * VW - 1) / (64 * VW);
-    long R = 2048 / J;
+    long R = 1024 / J;  // about 1024 workgroups
     if (R < 1) R = 1;
     const long maxR = (nrows + 63) / 64;
     if (R > maxR) R = maxR;

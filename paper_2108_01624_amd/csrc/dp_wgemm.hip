@@ -24,6 +24,8 @@
 // v_cvt_pk_bf16_f32); accumulation is fp32 in the MFMA.
 //
 // Roofline: MFMA.  2*B*T*d_in*d_out flops per layer against (d_in + d_out)*B*T*2 bytes read once.
+#include <stdlib.h>
+
 #include <type_traits>
 
 #include "dp_common.h"
@@ -38,7 +40,9 @@ enum { EPI_STORE = 0, EPI_ADD = 1, EPI_SQNORM = 2 };
 struct WgemmArgs {
     const uint16_t* A;   // [K, d_in]
     const uint16_t* G;   // [K, d_out]
-    const float* c;      // [B] clip factors (unused when the kernel is built without scaling)
+    const float* sqnorms;  // [B] squared norms; c_i = min(1, C / sqrt(sqnorms[i])) (unused without scaling)
+    float C;
+    float* bias_part;    // [nsplit][d_out] column sums of the scaled G rows (written by the tile row 0), or nullptr
     int T, d_in, d_out;
     long K;              // total rows
     long rows_per_split; // multiple of BK (or T for the per-example materialisation)
@@ -77,17 +81,20 @@ __device__ __forceinline__ bf16x8_t read_frag(const uint16_t* lds_lane_ptr, int 
 
 // Workgroup = 4 waves as 2 x 2; wave tile (32*MI) x (32*NI); block tile BM x BN = (64*MI) x (64*NI).
 // SCALE: multiply G rows by c.  UNIFORM_C: T % BK == 0, so all rows of a stage belong to one example.
-template <int MI, int NI, int EPI, bool SCALE, bool UNIFORM_C>
-__global__ __launch_bounds__(256) void wgemm_bf16_kernel(WgemmArgs a) {
-    constexpr int BM = 64 * MI, BN = 64 * NI;
+template <int MI, int NI, int WVM, int WVN, int EPI, bool SCALE, bool UNIFORM_C>
+__global__ __launch_bounds__(64 * WVM * WVN) void wgemm_bf16_kernel(WgemmArgs a) {
+    constexpr int NT = 64 * WVM * WVN;
     constexpr int WM = 32 * MI, WN = 32 * NI;
+    constexpr int BM = WM * WVM, BN = WN * WVN;
     constexpr int CA = BM / 8, CG = BN / 8;  // 16-byte chunks per tile row
+    constexpr int SA = BK * CA / NT, SG = BK * CG / NT;  // staging slots (16-byte chunks) per thread
+    static_assert(SA * NT == BK * CA && SG * NT == BK * CG, "tile must divide evenly over the threads");
     __shared__ __attribute__((aligned(16))) uint16_t As[NSTAGE][BK * BM];
     __shared__ __attribute__((aligned(16))) uint16_t Gs[NSTAGE][BK * BN];
-    __shared__ float wred[4];
+    __shared__ float wred[NT / 64];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wr = wave >> 1, wc = wave & 1;
+    const int wr = wave / WVN, wc = wave % WVN;
     const int ntiles = a.tiles_m * a.tiles_n;
     int tile, split;
     if (a.xcd_map) {
@@ -115,17 +122,17 @@ __global__ __launch_bounds__(256) void wgemm_bf16_kernel(WgemmArgs a) {
     // Per-thread staging slots: slot j moves the 16-byte chunk at tile row `row`, LDS chunk position `cpos`;
     // the global chunk it holds is cpos ^ swizzle(row).  Columns past the layer width read neighbouring
     // (valid or zero) data and only feed output columns that are never stored.
-    int voffA[MI], ldsA[MI], voffG[NI], ldsG[NI], rowG[NI];
+    int voffA[SA], ldsA[SA], voffG[SG], ldsG[SG], rowG[SG];
 #pragma unroll
-    for (int j = 0; j < MI; ++j) {
-        const int id = tid + 256 * j, row = id / CA, cpos = id % CA;
+    for (int j = 0; j < SA; ++j) {
+        const int id = tid + NT * j, row = id / CA, cpos = id % CA;
         const int cg = cpos ^ ((row & 3) << 2);
         voffA[j] = (row * a.d_in + p0 + cg * 8) * 2;
         ldsA[j] = row * BM + cpos * 8;
     }
 #pragma unroll
-    for (int j = 0; j < NI; ++j) {
-        const int id = tid + 256 * j, row = id / CG, cpos = id % CG;
+    for (int j = 0; j < SG; ++j) {
+        const int id = tid + NT * j, row = id / CG, cpos = id % CG;
         const int cg = cpos ^ ((row & 3) << 2);
         voffG[j] = (row * a.d_out + q0 + cg * 8) * 2;
         ldsG[j] = row * BN + cpos * 8;
@@ -155,37 +162,57 @@ __global__ __launch_bounds__(256) void wgemm_bf16_kernel(WgemmArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    u32x4_t ra[2][MI], rg[2][NI];
-    float cs[2][NI];
+    u32x4_t ra[2][SA], rg[2][SG];
+    float cs[2][SG];
+    // Bias gradient: the workgroups of tile row 0 also sum the scaled G rows they stage, column by column.
+    const bool do_bias = SCALE && a.bias_part != nullptr && pm == 0;
+    float bsum[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) bsum[e] = 0.f;
     auto gload = [&](int set, int st) {  // stage st -> register set
         const int soffA = st * BK * a.d_in * 2, soffG = st * BK * a.d_out * 2;
 #pragma unroll
-        for (int j = 0; j < MI; ++j) ra[set][j] = __builtin_amdgcn_raw_buffer_load_b128(rA, voffA[j], soffA, 0);
+        for (int j = 0; j < SA; ++j) ra[set][j] = __builtin_amdgcn_raw_buffer_load_b128(rA, voffA[j], soffA, 0);
 #pragma unroll
-        for (int j = 0; j < NI; ++j) rg[set][j] = __builtin_amdgcn_raw_buffer_load_b128(rG, voffG[j], soffG, 0);
+        for (int j = 0; j < SG; ++j) rg[set][j] = __builtin_amdgcn_raw_buffer_load_b128(rG, voffG[j], soffG, 0);
         if constexpr (SCALE) {
             if constexpr (UNIFORM_C) {
                 const long k = k_lo + (long)st * BK;
-                const float s = a.c[(uint32_t)(k < a.K ? k : a.K - 1) / (uint32_t)a.T];
+                const float s = dp_clip_factor(a.sqnorms[(uint32_t)(k < a.K ? k : a.K - 1) / (uint32_t)a.T], a.C);
 #pragma unroll
-                for (int j = 0; j < NI; ++j) cs[set][j] = s;
+                for (int j = 0; j < SG; ++j) cs[set][j] = s;
             } else {
 #pragma unroll
-                for (int j = 0; j < NI; ++j) {
+                for (int j = 0; j < SG; ++j) {
                     long k = k_lo + (long)st * BK + rowG[j];
                     if (k >= a.K) k = a.K - 1;
-                    cs[set][j] = a.c[(uint32_t)k / (uint32_t)a.T];
+                    cs[set][j] = dp_clip_factor(a.sqnorms[(uint32_t)k / (uint32_t)a.T], a.C);
                 }
             }
         }
     };
     auto lstore = [&](int set, int buf) {
 #pragma unroll
-        for (int j = 0; j < MI; ++j) *reinterpret_cast<u32x4_t*>(&As[buf][ldsA[j]]) = ra[set][j];
+        for (int j = 0; j < SA; ++j) *reinterpret_cast<u32x4_t*>(&As[buf][ldsA[j]]) = ra[set][j];
 #pragma unroll
-        for (int j = 0; j < NI; ++j) {
+        for (int j = 0; j < SG; ++j) {
             u32x4_t v = rg[set][j];
-            if constexpr (SCALE) v = scale_bf16x8(v, cs[set][j]);
+            if constexpr (SCALE) {
+                if (do_bias) {
+                    // this thread always stages the same 8 columns (see the bias epilogue): add the fp32
+                    // products c*g to its running column sums before they are rounded to bf16
+#pragma unroll
+                    for (int w = 0; w < 4; ++w) {
+                        const float lo = dp_bf16_lo(v[w]) * cs[set][j], hi = dp_bf16_hi(v[w]) * cs[set][j];
+                        bsum[2 * w] += lo;
+                        bsum[2 * w + 1] += hi;
+                        const f32x2_t x = {lo, hi};
+                        v[w] = __builtin_bit_cast(uint32_t, __builtin_convertvector(x, bf16x2_t));
+                    }
+                } else {
+                    v = scale_bf16x8(v, cs[set][j]);
+                }
+            }
             *reinterpret_cast<u32x4_t*>(&Gs[buf][ldsG[j]]) = v;
         }
     };
@@ -209,12 +236,18 @@ __global__ __launch_bounds__(256) void wgemm_bf16_kernel(WgemmArgs a) {
 
     // ---- prologue: stages 0 and 1 into LDS, stages 2 and 3 in flight in registers ----
     bf16x8_t fa0[MI], fg0[NI], fa1[MI], fg1[NI];
+    // (the scheduling barriers keep the loads in program order: the compiler's wait counts for the loop
+    // are only as tight as the load order on entry is certain)
     gload(0, 0);
+    __builtin_amdgcn_sched_barrier(0);
     gload(1, 1);
+    __builtin_amdgcn_sched_barrier(0);
     lstore(0, 0);
     gload(0, 2);
+    __builtin_amdgcn_sched_barrier(0);
     lstore(1, 1);
     gload(1, 3);
+    __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
     load_frags(0, 0, fa0, fg0);
 
@@ -233,12 +266,58 @@ __global__ __launch_bounds__(256) void wgemm_bf16_kernel(WgemmArgs a) {
         gload(SET, s + 4);
         load_frags(buf1, 0, fa0, fg0);
         mma(fa1, fg1);
+        if constexpr (MI == 4 && NI == 4 && NT == 256) {
+            // Interleave: the wave is alone on its SIMD, so every run of non-MFMA instructions longer than
+            // one MFMA's 32 cycles leaves the matrix pipe idle.  First 16 MFMAs: one fragment read and the
+            // scaling arithmetic between them; last 16: LDS stores, global loads and the next fragment reads.
+#pragma unroll
+            for (int g = 0; g < 16; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+                __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);  // VALU
+            }
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // DS write
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // VMEM read
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+            }
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+            }
+        }
         __syncthreads();
+        // nothing of the next iteration may move above this point: its register set is still in flight
+        __builtin_amdgcn_sched_barrier(0);
         buf = buf1;
     };
     for (int s = 0; s < nsteps2; s += 2) {
         body(s, std::integral_constant<int, 0>());
         body(s + 1, std::integral_constant<int, 1>());
+    }
+
+    if constexpr (SCALE) {
+        if (do_bias) {
+            // Thread t staged LDS chunk position t % CG of rows t / CG (+ multiples of NT / CG, a multiple of 4),
+            // i.e. always the global chunk (t % CG) ^ 4*((t / CG) % 4).  Gather the NT / CG row classes of every
+            // column in a fixed order.  The stage buffers are free: the loop ended with a barrier.
+            float* scratch = reinterpret_cast<float*>(&As[0][0]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) scratch[tid * 8 + e] = bsum[e];
+            __syncthreads();
+            if (tid < BN && q0 + tid < a.d_out) {
+                const int cgl = tid >> 3, e = tid & 7;
+                float t = 0.f;
+#pragma unroll 4
+                for (int r = 0; r < NT / CG; ++r) t += scratch[(r * CG + (cgl ^ ((r & 3) << 2))) * 8 + e];
+                a.bias_part[(size_t)split * a.d_out + q0 + tid] = t;
+            }
+        }
     }
 
     // MFMA tile (i, j): accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
@@ -257,7 +336,7 @@ __global__ __launch_bounds__(256) void wgemm_bf16_kernel(WgemmArgs a) {
                     s += v * v;
                 }
             }
-        const float tot = dp_block_sum<256>(s, wred);
+        const float tot = dp_block_sum<NT>(s, wred);
         if (tid == 0) a.out[(size_t)split * ntiles + tile] = tot;
         return;
     }
@@ -329,19 +408,26 @@ __global__ __launch_bounds__(256) void wgemm_f32_kernel(const float* __restrict_
         }
 }
 
-template <int MI, int NI, int EPI, bool SCALE, bool UNIFORM_C>
+template <int MI, int NI, int WVM, int WVN, int EPI, bool SCALE, bool UNIFORM_C>
 void wgemm_launch(dp_ctx* ctx, const WgemmArgs& a, unsigned grid) {
-    hipLaunchKernelGGL((wgemm_bf16_kernel<MI, NI, EPI, SCALE, UNIFORM_C>), dim3(grid), dim3(256), 0, ctx->stream, a);
+    hipLaunchKernelGGL((wgemm_bf16_kernel<MI, NI, WVM, WVN, EPI, SCALE, UNIFORM_C>), dim3(grid),
+                       dim3(64 * WVM * WVN), 0, ctx->stream, a);
 }
 
+// Tile configurations: 0 = 128 x 128 (4 waves of 64 x 64), 1 = 256 x 256 with 4 waves of 128 x 128 (one wave per
+// SIMD), 2 = 256 x 256 with 8 waves of 128 x 64 (two waves per SIMD, which lets one wave's MFMAs run under the
+// other's loads, conversions and waits).
 template <int EPI, bool SCALE>
-void wgemm_dispatch(dp_ctx* ctx, const WgemmArgs& a, unsigned grid, bool big, bool uniform) {
-    if (big) {
-        if (uniform) wgemm_launch<4, 4, EPI, SCALE, true>(ctx, a, grid);
-        else wgemm_launch<4, 4, EPI, SCALE, false>(ctx, a, grid);
+void wgemm_dispatch(dp_ctx* ctx, const WgemmArgs& a, unsigned grid, int cfg, bool uniform) {
+    if (cfg == 2) {
+        if (uniform) wgemm_launch<4, 2, 2, 4, EPI, SCALE, true>(ctx, a, grid);
+        else wgemm_launch<4, 2, 2, 4, EPI, SCALE, false>(ctx, a, grid);
+    } else if (cfg == 1) {
+        if (uniform) wgemm_launch<4, 4, 2, 2, EPI, SCALE, true>(ctx, a, grid);
+        else wgemm_launch<4, 4, 2, 2, EPI, SCALE, false>(ctx, a, grid);
     } else {
-        if (uniform) wgemm_launch<2, 2, EPI, SCALE, true>(ctx, a, grid);
-        else wgemm_launch<2, 2, EPI, SCALE, false>(ctx, a, grid);
+        if (uniform) wgemm_launch<2, 2, 2, 2, EPI, SCALE, true>(ctx, a, grid);
+        else wgemm_launch<2, 2, 2, 2, EPI, SCALE, false>(ctx, a, grid);
     }
 }
 
@@ -349,6 +435,14 @@ void wgemm_dispatch(dp_ctx* ctx, const WgemmArgs& a, unsigned grid, bool big, bo
 
 // Tile shape: 256 x 256 when both dimensions are at least that large, otherwise 128 x 128.
 static inline bool big_tile(int d_in, int d_out) { return d_in >= 256 && d_out >= 256; }
+static inline int tile_cfg(int d_in, int d_out) {
+    static int big_cfg = -1;
+    if (big_cfg < 0) {  // DPCLIP_GEMM_WAVES=4 selects the one-wave-per-SIMD variant (tuning aid)
+        const char* e = getenv("DPCLIP_GEMM_WAVES");
+        big_cfg = (e && e[0] == '4') ? 1 : 2;
+    }
+    return big_tile(d_in, d_out) ? big_cfg : 0;
+}
 
 // A split's rows of one operand must stay below 2^31 bytes (32-bit buffer offsets).
 static inline bool range_ok(long rows, int d_in, int d_out) {
@@ -357,21 +451,33 @@ static inline bool range_ok(long rows, int d_in, int d_out) {
 }
 
 dp_status dpk_weighted_gemm(dp_ctx* ctx, const void* A, const void* G, dp_dtype dt, int B, int T, int d_in, int d_out,
-                            const float* c, float* sum_W) {
+                            const float* sqnorms, float C, float* sum_W, float* sum_b) {
     const long K = (long)B * T;
     if (dt == DP_F32) {
-        dim3 grid((d_out + 63) / 64, (d_in + 63) / 64);
-        hipLaunchKernelGGL(wgemm_f32_kernel, grid, dim3(256), 0, ctx->stream, (const float*)A, (const float*)G, c, T, K,
-                           d_in, d_out, sum_W);
-        DP_LAUNCH_CHECK(ctx, "wgemm_f32");
+        dp_status st = dpk_clip_factors(ctx, sqnorms, B, C, ctx->cbuf);
+        if (st != DP_OK) return st;
+        if (d_in > 0) {
+            dim3 grid((d_out + 63) / 64, (d_in + 63) / 64);
+            hipLaunchKernelGGL(wgemm_f32_kernel, grid, dim3(256), 0, ctx->stream, (const float*)A, (const float*)G,
+                               ctx->cbuf, T, K, d_in, d_out, sum_W);
+            DP_LAUNCH_CHECK(ctx, "wgemm_f32");
+        }
+        if (sum_b) return dpk_colstat_sums(ctx, nullptr, G, dt, B, T, d_out, ctx->cbuf, nullptr, sum_b);
         return DP_OK;
+    }
+    if (d_in == 0) {  // no weights: only the bias sums are left
+        if (!sum_b) return DP_OK;
+        dp_status st = dpk_clip_factors(ctx, sqnorms, B, C, ctx->cbuf);
+        if (st != DP_OK) return st;
+        return dpk_colstat_sums(ctx, nullptr, G, dt, B, T, d_out, ctx->cbuf, nullptr, sum_b);
     }
     const bool big = big_tile(d_in, d_out);
     const int BM = big ? 256 : 128, BN = BM;
     WgemmArgs a;
     a.A = (const uint16_t*)A;
     a.G = (const uint16_t*)G;
-    a.c = c;
+    a.sqnorms = sqnorms;
+    a.C = C;
     a.T = T;
     a.d_in = d_in;
     a.d_out = d_out;
@@ -395,6 +501,7 @@ dp_status dpk_weighted_gemm(dp_ctx* ctx, const void* A, const void* G, dp_dtype 
     dp_ws_alloc ws(ctx);
     float* part = nullptr;
     while (nsplit > 1) {
+        ws.off = 0;
         part = ws.get<float>((size_t)nsplit * d_in * d_out);
         if (part) break;
         nsplit = nsplit > 8 ? nsplit - 8 : nsplit / 2;  // shrink to what the workspace holds
@@ -408,6 +515,14 @@ dp_status dpk_weighted_gemm(dp_ctx* ctx, const void* A, const void* G, dp_dtype 
     nsplit = (ksteps + steps_per - 1) / steps_per;
     a.nsplit = (int)nsplit;
     a.xcd_map = nsplit >= 8 ? 1 : 0;
+    a.bias_part = nullptr;
+    if (sum_b) {
+        a.bias_part = ws.get<float>((size_t)nsplit * d_out);
+        if (!a.bias_part) {
+            DP_SET_ERR(ctx, "workspace too small for the bias partials");
+            return DP_ERR_WORKSPACE;
+        }
+    }
     const long nwg = a.xcd_map ? ((nsplit + 7) / 8) * 8 * ntiles : nsplit * ntiles;
     if (nwg > 0x7FFFFFFFl) {
         DP_SET_ERR(ctx, "dp_clip_accumulate_dense: too many tiles");
@@ -415,20 +530,22 @@ dp_status dpk_weighted_gemm(dp_ctx* ctx, const void* A, const void* G, dp_dtype 
     }
     const bool uniform = T % BK == 0;
     const double flops = 2.0 * (double)K * d_in * d_out;
+    const int cfg = tile_cfg(d_in, d_out);
     if (nsplit == 1) {
         a.out = sum_W;
         dp_prof_scope prof(ctx, DP_PROF_WGEMM, flops);
-        wgemm_dispatch<EPI_ADD, true>(ctx, a, (unsigned)nwg, big, uniform);
-        DP_LAUNCH_CHECK(ctx, "wgemm_bf16");
-        return DP_OK;
-    }
-    a.out = part;
-    {
+        wgemm_dispatch<EPI_ADD, true>(ctx, a, (unsigned)nwg, cfg, uniform);
+    } else {
+        a.out = part;
         dp_prof_scope prof(ctx, DP_PROF_WGEMM, flops);
-        wgemm_dispatch<EPI_STORE, true>(ctx, a, (unsigned)nwg, big, uniform);
+        wgemm_dispatch<EPI_STORE, true>(ctx, a, (unsigned)nwg, cfg, uniform);
     }
     DP_LAUNCH_CHECK(ctx, "wgemm_bf16");
-    return dpk_reduce_partials(ctx, part, (int)nsplit, (size_t)d_in * d_out, (size_t)d_in * d_out, sum_W);
+    dp_status st = DP_OK;
+    if (nsplit > 1)
+        st = dpk_reduce_partials(ctx, part, (int)nsplit, (size_t)d_in * d_out, (size_t)d_in * d_out, sum_W);
+    if (st == DP_OK && sum_b) st = dpk_reduce_partials(ctx, a.bias_part, (int)nsplit, (size_t)d_out, (size_t)d_out, sum_b);
+    return st;
 }
 
 dp_status dpk_materialise_sqnorms(dp_ctx* ctx, const void* A, const void* G, dp_dtype dt, int B, int T, int d_in,
@@ -442,7 +559,9 @@ dp_status dpk_materialise_sqnorms(dp_ctx* ctx, const void* A, const void* G, dp_
         WgemmArgs a;
         a.A = (const uint16_t*)A;
         a.G = (const uint16_t*)G;
-        a.c = nullptr;
+        a.sqnorms = nullptr;
+        a.C = 1.f;
+        a.bias_part = nullptr;
         a.T = T;
         a.d_in = d_in;
         a.d_out = d_out;
@@ -469,7 +588,7 @@ dp_status dpk_materialise_sqnorms(dp_ctx* ctx, const void* A, const void* G, dp_
             return DP_ERR_WORKSPACE;
         }
         a.out = part;
-        wgemm_dispatch<EPI_SQNORM, false>(ctx, a, (unsigned)nwg, big, true);
+        wgemm_dispatch<EPI_SQNORM, false>(ctx, a, (unsigned)nwg, tile_cfg(d_in, d_out), true);
         DP_LAUNCH_CHECK(ctx, "wgemm_bf16 (materialise)");
         st = dpk_finish_partials(ctx, part, B, ntiles, sqnorms);
     }
