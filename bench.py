@@ -31,6 +31,9 @@ def parse():
     ap.add_argument("--batch", type=int, default=0, help="override the micro-batch size (parity/debug only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-examples", type=int, default=0, help="examples in the oracle sample (0 = auto)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy before the timed region (reference for "
+                         "scaling the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     return ap.parse_args()
 
 
@@ -96,6 +99,12 @@ def main():
         run.update(sigma=upd["sigma"], C=cfg["C"], seed=upd["noise_seed"], step=t, batch_size=B, lr=upd["lr"],
                    beta1=upd["beta1"], beta2=upd["beta2"], weight_decay=upd["weight_decay"], zero_sum=True)
 
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)  # 1 GiB read + 1 GiB written
+        torch.cuda.synchronize()
+        del src, dst
     for w in range(args.warmup):
         step(w + 1)
     ctx.sync()

@@ -48,7 +48,9 @@ struct WgemmArgs {
     long rows_per_split; // multiple of BK (or T for the per-example materialisation)
     int tiles_m, tiles_n, nsplit;
     float* out;          // EPI_STORE: [nsplit][d_in][d_out]; EPI_ADD: [d_in][d_out]; EPI_SQNORM: [nsplit][ntiles]
-    int xcd_map;         // 1: split index interleaved over the 8 XCDs
+    int xcd_map;         // 0: plain; 1: split index interleaved over the 8 XCDs; 2: each XCD owns one split and a
+                         // rect_m x rect_n-th sub-rectangle of the tile grid
+    int rect_m, rect_n;  // mode 2: the tile grid is cut into rect_m x rect_n rectangles, 8 / nsplit per split
 };
 
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
@@ -96,12 +98,21 @@ __global__ __launch_bounds__(64 * WVM * WVN) void wgemm_bf16_kernel(WgemmArgs a)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wr = wave / WVN, wc = wave % WVN;
     const int ntiles = a.tiles_m * a.tiles_n;
+    // Workgroup ids are dealt to the 8 XCDs round-robin (id % 8), each XCD with its own L2: give the workgroups
+    // of one XCD work that shares operand rows and columns, so that A and G come from HBM about once.
     int tile, split;
-    if (a.xcd_map) {
+    if (a.xcd_map == 1) {
         const int g = blockIdx.x, slot = g >> 3;
         split = (slot / ntiles) * 8 + (g & 7);
         tile = slot % ntiles;
         if (split >= a.nsplit) return;
+    } else if (a.xcd_map == 2) {
+        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        const int nrect = a.rect_m * a.rect_n;
+        const int rect = xcd % nrect;
+        const int tm = a.tiles_m / a.rect_m, tn = a.tiles_n / a.rect_n;
+        split = xcd / nrect;
+        tile = ((rect / a.rect_n) * tm + slot / tn) * a.tiles_n + (rect % a.rect_n) * tn + slot % tn;
     } else {
         tile = blockIdx.x % ntiles;
         split = blockIdx.x / ntiles;
@@ -495,6 +506,9 @@ dp_status dpk_weighted_gemm(dp_ctx* ctx, const void* A, const void* G, dp_dtype 
         const long max_split = (ksteps + 7) / 8;
         if (nsplit > max_split) nsplit = max_split;
         if (nsplit >= 8) nsplit = (nsplit / 8) * 8;
+        else if (nsplit > 4) nsplit = max_split >= 8 ? 8 : 4;
+        else if (nsplit == 3) nsplit = 4;
+        if (nsplit > max_split) nsplit = max_split < 1 ? 1 : max_split;
         if (nsplit < 1) nsplit = 1;
     }
     while (!range_ok((ksteps + nsplit - 1) / nsplit * BK, d_in, d_out)) nsplit *= 2;
@@ -515,6 +529,24 @@ dp_status dpk_weighted_gemm(dp_ctx* ctx, const void* A, const void* G, dp_dtype 
     nsplit = (ksteps + steps_per - 1) / steps_per;
     a.nsplit = (int)nsplit;
     a.xcd_map = nsplit >= 8 ? 1 : 0;
+    a.rect_m = a.rect_n = 1;
+    if (nsplit < 8 && 8 % nsplit == 0) {
+        // 8 / nsplit rectangles per split: pick the cut with the smallest half-perimeter (operand bytes per XCD)
+        const int nrect = 8 / (int)nsplit;
+        int best = -1;
+        for (int rm = 1; rm <= nrect; ++rm) {
+            if (nrect % rm) continue;
+            const int rn = nrect / rm;
+            if (a.tiles_m % rm || a.tiles_n % rn) continue;
+            const int cost = a.tiles_m / rm + a.tiles_n / rn;
+            if (best < 0 || cost < best) {
+                best = cost;
+                a.rect_m = rm;
+                a.rect_n = rn;
+            }
+        }
+        if (best >= 0) a.xcd_map = 2;
+    }
     a.bias_part = nullptr;
     if (sum_b) {
         a.bias_part = ws.get<float>((size_t)nsplit * d_out);
@@ -523,7 +555,7 @@ dp_status dpk_weighted_gemm(dp_ctx* ctx, const void* A, const void* G, dp_dtype 
             return DP_ERR_WORKSPACE;
         }
     }
-    const long nwg = a.xcd_map ? ((nsplit + 7) / 8) * 8 * ntiles : nsplit * ntiles;
+    const long nwg = a.xcd_map == 1 ? ((nsplit + 7) / 8) * 8 * ntiles : nsplit * ntiles;
     if (nwg > 0x7FFFFFFFl) {
         DP_SET_ERR(ctx, "dp_clip_accumulate_dense: too many tiles");
         return DP_ERR_SHAPE;
@@ -571,6 +603,7 @@ dp_status dpk_materialise_sqnorms(dp_ctx* ctx, const void* A, const void* G, dp_
         a.nsplit = B;  // one "split" per example: rows [i*T, (i+1)*T)
         a.rows_per_split = T;
         a.xcd_map = 0;
+        a.rect_m = a.rect_n = 1;
         if (!range_ok(T, d_in, d_out)) {
             DP_SET_ERR(ctx, "dp_sqnorms_dense: one example's activations exceed 2 GiB");
             return DP_ERR_SHAPE;
