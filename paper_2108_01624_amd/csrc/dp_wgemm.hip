@@ -373,6 +373,240 @@ __global__ __launch_bounds__(64 * WVM * WVN) void wgemm_bf16_kernel(WgemmArgs a)
 }
 
 // ------------------------------------------------------------------------------------------------
+// Fast path of the clip-weighted sum (T a multiple of BK, both widths >= 256): 256 x 256 tile, 8 waves
+// (2 x 4, wave tile 128 x 64, accumulators in VGPRs, two waves per SIMD).
+//
+//  * Both operand tiles go from global memory straight into LDS (buffer_load ... lds, 16 bytes per lane, a wave
+//    fills two tile rows per instruction): no staging registers, no LDS store instructions, nothing for the
+//    VALU to do per element.  The loads are issued through inline assembly because the compiler would otherwise
+//    wait for ALL outstanding LDS-filling loads before every LDS read; here the wave waits (vmcnt) only for the
+//    stage it is about to publish and keeps the later stages in flight.  Ring of five 32 KiB stages: all of the CU's LDS.
+//  * The clip factor is not applied to the operands at all.  All rows of a stage belong to one example, so the
+//    accumulators carry sum_{j<=i} (c_j / c_i) A_j^T G_j: when the stage's example changes they are multiplied
+//    by c_prev / c_next (128 + 32 VALU multiplies per wave per example), and by the last c at the end.  The
+//    bf16 products are exact in fp32, so this path is more accurate than rounding c*g to bf16.
+//  * Bias gradient: column sums of G are one more MFMA with an all-ones A fragment.  Every wave takes that duty
+//    for one stage in 2*tiles_m (tile row pm, wave row wr: stages s with s % (2*tiles_m) == 2*pm + wr), so the
+//    extra work is spread evenly; the partial sums of (split, pm, wr) are added in a fixed order afterwards.
+// ------------------------------------------------------------------------------------------------
+constexpr int DMA_NS = 5;  // LDS ring stages (5 x 32 KiB = all 160 KiB of a CU's LDS)
+
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void dma_load16(i32x4_t rsrc, uint32_t lds_byte_addr, int voff, int soff) {
+    // LDS destination of lane l: M0 + 16*l.  voff: per-lane byte offset; soff: wave-uniform byte offset.
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_byte_addr), "v"(voff), "s"(rsrc), "s"(soff)
+                 : "memory");
+}
+
+__device__ __forceinline__ i32x4_t make_rsrc(const void* base, uint32_t bytes) {
+    const uint64_t p = (uint64_t)base;
+    i32x4_t r;
+    r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)p);
+    r[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)(p >> 32));  // stride 0
+    r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+    r[3] = 0x00020000;
+    return r;
+}
+
+template <int EPI>
+__global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmArgs a) {
+    constexpr int MI = 4, NI = 2, WVN = 4, NT = 512;
+    constexpr int WM = 128, WN = 64, BM = 256, BN = 256;
+    constexpr int LPS = 4;  // LDS-filling loads per wave per stage (2 for A, 2 for G)
+    __shared__ __attribute__((aligned(16))) uint16_t As[DMA_NS][BK * BM];
+    __shared__ __attribute__((aligned(16))) uint16_t Gs[DMA_NS][BK * BN];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wr = wave / WVN, wc = wave % WVN;
+    const int ntiles = a.tiles_m * a.tiles_n;
+    int tile, split;
+    if (a.xcd_map == 1) {
+        const int g = blockIdx.x, slot = g >> 3;
+        split = (slot / ntiles) * 8 + (g & 7);
+        tile = slot % ntiles;
+        if (split >= a.nsplit) return;
+    } else if (a.xcd_map == 2) {
+        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        const int nrect = a.rect_m * a.rect_n;
+        const int rect = xcd % nrect;
+        const int tm = a.tiles_m / a.rect_m, tn = a.tiles_n / a.rect_n;
+        split = xcd / nrect;
+        tile = ((rect / a.rect_n) * tm + slot / tn) * a.tiles_n + (rect % a.rect_n) * tn + slot % tn;
+    } else {
+        tile = blockIdx.x % ntiles;
+        split = blockIdx.x / ntiles;
+    }
+    const int pm = tile / a.tiles_n, qn = tile % a.tiles_n;
+    const int p0 = pm * BM, q0 = qn * BN;
+    const long k_lo = (long)split * a.rows_per_split;
+    const long k_hi = k_lo + a.rows_per_split < a.K ? k_lo + a.rows_per_split : a.K;
+    const int nrows = k_hi > k_lo ? (int)(k_hi - k_lo) : 0;
+    const int nsteps = (nrows + BK - 1) / BK;
+
+    const i32x4_t rA = make_rsrc(a.A + (size_t)k_lo * a.d_in, (uint32_t)((size_t)nrows * a.d_in * 2));
+    const i32x4_t rG = make_rsrc(a.G + (size_t)k_lo * a.d_out, (uint32_t)((size_t)nrows * a.d_out * 2));
+
+    // Load j (0, 1) of this wave fills tile rows 4*wave + 2*j and + 1: lane l -> row + l/32, LDS chunk l%32,
+    // which holds global chunk (l%32) ^ 4*(row%4) (bank swizzle, see the file header).
+    int voffA[2], voffG[2];
+    uint32_t ldsA[2], ldsG[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int row0 = 4 * wave + 2 * j, row = row0 + (lane >> 5);
+        const int cg = (lane & 31) ^ ((row & 3) << 2);
+        voffA[j] = (row * a.d_in + p0 + cg * 8) * 2;
+        voffG[j] = (row * a.d_out + q0 + cg * 8) * 2;
+        ldsA[j] = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)&As[0][row0 * BM];
+        ldsG[j] = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)&Gs[0][row0 * BN];
+    }
+    auto issue = [&](int st, int buf) {
+        const int soffA = __builtin_amdgcn_readfirstlane(st * BK * a.d_in * 2);
+        const int soffG = __builtin_amdgcn_readfirstlane(st * BK * a.d_out * 2);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            dma_load16(rA, __builtin_amdgcn_readfirstlane(ldsA[j] + buf * (BK * BM * 2)), voffA[j], soffA);
+            dma_load16(rG, __builtin_amdgcn_readfirstlane(ldsG[j] + buf * (BK * BN * 2)), voffG[j], soffG);
+        }
+    };
+
+    const int frow = 8 * (lane >> 5) + ((lane & 15) >> 2);
+    const int fsw = frow & 3;
+    int foffA[MI], foffG[NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+        const int col = wr * WM + 32 * i + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+        foffA[i] = frow * BM + (((col >> 3) ^ (fsw << 2)) << 3) + (col & 7);
+    }
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int col = wc * WN + 32 * i + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+        foffG[i] = frow * BN + (((col >> 3) ^ (fsw << 2)) << 3) + (col & 7);
+    }
+    auto load_frags = [&](int buf, int kk, bf16x8_t* fa, bf16x8_t* fg) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i) fa[i] = read_frag(&As[buf][kk * 16 * BM + foffA[i]], BM);
+#pragma unroll
+        for (int i = 0; i < NI; ++i) fg[i] = read_frag(&Gs[buf][kk * 16 * BN + foffG[i]], BN);
+    };
+
+    f32x16_t acc[MI][NI], bacc[NI];
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) bacc[j][r] = 0.f;
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    }
+    auto mma = [&](const bf16x8_t* fa, const bf16x8_t* fg) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fg[j], acc[i][j], 0, 0, 0);
+    };
+    const bool want_bias = a.bias_part != nullptr;
+    const int duty_mod = 2 * a.tiles_m, duty = 2 * pm + wr;
+    const uint32_t one2 = 0x3F803F80u;  // two bf16 ones
+    const bf16x8_t ones = __builtin_bit_cast(bf16x8_t, u32x4_t{one2, one2, one2, one2});
+    auto mma_bias = [&](const bf16x8_t* fg) {
+#pragma unroll
+        for (int j = 0; j < NI; ++j) bacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, fg[j], bacc[j], 0, 0, 0);
+    };
+    auto clip_of_stage = [&](int st) -> float {
+        long k = k_lo + (long)st * BK;
+        if (k >= a.K) k = a.K - 1;
+        // scalar load (the index is uniform): a vector load here would make the compiler drain every
+        // LDS-filling load in flight before it reads the value
+        const uint32_t off = __builtin_amdgcn_readfirstlane(((uint32_t)k / (uint32_t)a.T) * 4u);
+        float n;
+        asm volatile("s_load_dword %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=s"(n) : "s"(a.sqnorms), "s"(off) : "memory");
+        return dp_clip_factor(n, a.C);
+    };
+
+    bf16x8_t fa0[MI], fg0[NI], fa1[MI], fg1[NI];
+    float c_cur = nsteps > 0 ? clip_of_stage(0) : 1.f;
+    int ex_cur = (int)((uint32_t)k_lo / (uint32_t)a.T);
+
+    // prologue: DMA_NS - 1 stages in flight; publish stage 0
+#pragma unroll
+    for (int st = 0; st < DMA_NS - 1; ++st) issue(st, st);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DMA_NS - 2) * LPS) : "memory");  // stage 0 has landed
+    __syncthreads();
+    load_frags(0, 0, fa0, fg0);
+
+    int buf = 0;
+    for (int s = 0; s < nsteps; ++s) {
+        const int buf1 = buf + 1 == DMA_NS ? 0 : buf + 1;            // stage s+1
+        const int bufp = buf == 0 ? DMA_NS - 1 : buf - 1;            // stage s-1 == stage s + DMA_NS - 1
+        // example boundary: rescale the running sums from weights relative to c_prev to weights relative to c_next
+        const int ex = (int)((uint32_t)(k_lo + (long)s * BK) / (uint32_t)a.T);
+        if (ex != ex_cur) {
+            const float c_next = clip_of_stage(s);
+            const float ratio = c_cur / c_next;
+            ex_cur = ex;
+            c_cur = c_next;
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) bacc[j][r] *= ratio;
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] *= ratio;
+            }
+        }
+        const bool bias_now = want_bias && (s % duty_mod) == duty;
+        load_frags(buf, 1, fa1, fg1);
+        mma(fa0, fg0);
+        if (bias_now) mma_bias(fg0);
+        // my loads of stage s+1 have landed (later stages may still be in flight); after the barrier every
+        // wave's have, and every wave has finished reading stage s-1, whose buffer the newest stage now overwrites
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DMA_NS - 3) * LPS) : "memory");
+        __syncthreads();
+        issue(s + DMA_NS - 1, bufp);
+        load_frags(buf1, 0, fa0, fg0);
+        mma(fa1, fg1);
+        if (bias_now) mma_bias(fg1);
+        buf = buf1;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing may still be writing LDS when the workgroup ends
+
+    // MFMA tile (i, j): accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+    float* base = a.out + (EPI == EPI_STORE ? (size_t)split * a.d_in * a.d_out : (size_t)0);
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int p = p0 + wr * WM + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            if (p < a.d_in) {
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    const int q = q0 + wc * WN + 32 * j + (lane & 31);
+                    if (q < a.d_out) {
+                        float* dst = base + (size_t)p * a.d_out + q;
+                        if (EPI == EPI_ADD) *dst += acc[i][j][r] * c_cur;
+                        else *dst = acc[i][j][r] * c_cur;
+                    }
+                }
+            }
+        }
+    if (want_bias && lane < 32) {
+        // every row of the ones-product equals the column sums; row 0 sits in register 0 of lanes 0..31
+        float* bp = a.bias_part + ((size_t)(split * a.tiles_m + pm) * 2 + wr) * a.d_out;
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int q = q0 + wc * WN + 32 * j + lane;
+            if (q < a.d_out) bp[q] = bacc[j][0] * c_cur;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // fp32 path (small shapes, fp32 inputs): 64 x 64 output tile per workgroup, 16 x 16 threads, 4 x 4 each.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void wgemm_f32_kernel(const float* __restrict__ A, const float* __restrict__ G,
@@ -446,6 +680,15 @@ void wgemm_dispatch(dp_ctx* ctx, const WgemmArgs& a, unsigned grid, int cfg, boo
 
 // Tile shape: 256 x 256 when both dimensions are at least that large, otherwise 128 x 128.
 static inline bool big_tile(int d_in, int d_out) { return d_in >= 256 && d_out >= 256; }
+// The direct-to-LDS kernel serves the 256 x 256 tile when all rows of a stage share one example.
+static inline bool use_dma_path(int cfg, bool uniform) {
+    static int on = -1;
+    if (on < 0) {  // DPCLIP_GEMM_DMA=0 falls back to the register-staged kernel (tuning aid)
+        const char* e = getenv("DPCLIP_GEMM_DMA");
+        on = (e && e[0] == '0') ? 0 : 1;
+    }
+    return on && cfg != 0 && uniform;
+}
 static inline int tile_cfg(int d_in, int d_out) {
     static int big_cfg = -1;
     if (big_cfg < 0) {  // DPCLIP_GEMM_WAVES=4 selects the one-wave-per-SIMD variant (tuning aid)
@@ -563,6 +806,29 @@ dp_status dpk_weighted_gemm(dp_ctx* ctx, const void* A, const void* G, dp_dtype 
     const bool uniform = T % BK == 0;
     const double flops = 2.0 * (double)K * d_in * d_out;
     const int cfg = tile_cfg(d_in, d_out);
+    if (use_dma_path(cfg, uniform)) {
+        // bias partials of this path: one row per (split, tile row, wave row)
+        const int nb = (int)nsplit * a.tiles_m * 2;
+        if (sum_b) {
+            a.bias_part = ws.get<float>((size_t)nb * d_out);
+            if (!a.bias_part) {
+                DP_SET_ERR(ctx, "workspace too small for the bias partials");
+                return DP_ERR_WORKSPACE;
+            }
+        }
+        a.out = nsplit == 1 ? sum_W : part;
+        {
+            dp_prof_scope prof(ctx, DP_PROF_WGEMM, flops);
+            if (nsplit == 1) hipLaunchKernelGGL((wgemm_dma_kernel<EPI_ADD>), dim3((unsigned)nwg), dim3(512), 0, ctx->stream, a);
+            else hipLaunchKernelGGL((wgemm_dma_kernel<EPI_STORE>), dim3((unsigned)nwg), dim3(512), 0, ctx->stream, a);
+        }
+        DP_LAUNCH_CHECK(ctx, "wgemm_dma");
+        dp_status st = DP_OK;
+        if (nsplit > 1)
+            st = dpk_reduce_partials(ctx, part, (int)nsplit, (size_t)d_in * d_out, (size_t)d_in * d_out, sum_W);
+        if (st == DP_OK && sum_b) st = dpk_reduce_partials(ctx, a.bias_part, nb, (size_t)d_out, (size_t)d_out, sum_b);
+        return st;
+    }
     if (nsplit == 1) {
         a.out = sum_W;
         dp_prof_scope prof(ctx, DP_PROF_WGEMM, flops);
