@@ -114,6 +114,15 @@ dp_status dp_sqnorms_embedding(dp_ctx* ctx, const int32_t* ids, const void* G, d
 dp_status dp_clip_accumulate_dense(dp_ctx* ctx, const void* A, const void* G, dp_dtype dtype, int B, int T, int d_in,
                                    int d_out, float C, const float* sqnorms, float* sum_W, float* sum_b);
 
+/* dp_clip_accumulate_dense for n_layers independent layers of ONE shape (same dtype, B, T, d_in, d_out, C and
+ * sqnorms) in as few launches as possible: the layers' tiles fill the chip together, so the token rows need not
+ * be split and no partial sums pass through memory.  A, G, sum_W, sum_b are HOST arrays of n_layers device
+ * pointers (sum_b may be NULL, and so may any of its entries); they are read during the call only.
+ * The result of each layer is what dp_clip_accumulate_dense gives, up to fp32 summation order. */
+dp_status dp_clip_accumulate_dense_batched(dp_ctx* ctx, int n_layers, const void* const* A, const void* const* G,
+                                           dp_dtype dtype, int B, int T, int d_in, int d_out, float C,
+                                           const float* sqnorms, float* const* sum_W, float* const* sum_b);
+
 /* sum_gamma[j] += sum_i c_i sum_t G[i,t,j] Xhat[i,t,j];  sum_beta[j] += sum_i c_i sum_t G[i,t,j]. */
 dp_status dp_clip_accumulate_layernorm(dp_ctx* ctx, const void* Xhat, const void* G, dp_dtype dtype, int B, int T,
                                        int d, float C, const float* sqnorms, float* sum_gamma, float* sum_beta);

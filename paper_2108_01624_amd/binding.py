@@ -30,6 +30,9 @@ SIGNATURES = {
     "dp_clip_factors": [c_void_p, c_void_p, c_int, c_float, c_void_p],
     "dp_clip_accumulate_dense": [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_float, c_void_p,
                                  c_void_p, c_void_p],
+    "dp_clip_accumulate_dense_batched": [c_void_p, c_int, ctypes.POINTER(c_void_p), ctypes.POINTER(c_void_p), c_int, c_int,
+                                         c_int, c_int, c_int, c_float, c_void_p, ctypes.POINTER(c_void_p),
+                                         ctypes.POINTER(c_void_p)],
     "dp_clip_accumulate_layernorm": [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_float, c_void_p,
                                      c_void_p, c_void_p],
     "dp_clip_accumulate_embedding": [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_float, c_void_p,
@@ -174,6 +177,22 @@ def dp_clip_accumulate_dense(ctx, A, G, C, sqnorms, sum_W, sum_b=None):
     st = load_library().dp_clip_accumulate_dense(ctx, _ptr(A), _ptr(G), _dtype_of(A), B, T, d_in, G.shape[-1], float(C),
                                                  _f32(sqnorms), _f32(sum_W), _f32(sum_b))
     _check(ctx, st, "dp_clip_accumulate_dense")
+
+
+def dp_clip_accumulate_dense_batched(ctx, As, Gs, C, sqnorms, sum_Ws, sum_bs=None):
+    """As, Gs, sum_Ws (and sum_bs, entries may be None): equally long lists of same-shaped tensors."""
+    n = len(As)
+    B, T, d_in = As[0].shape
+    d_out = Gs[0].shape[-1]
+    for a, g in zip(As, Gs):
+        if tuple(a.shape) != (B, T, d_in) or tuple(g.shape) != (B, T, d_out) or a.dtype != As[0].dtype:
+            raise ValueError("all layers of a batch must share one shape and dtype")
+    arr = lambda ptrs: (c_void_p * n)(*ptrs)
+    pb = arr([_f32(t) for t in sum_bs]) if sum_bs is not None else None
+    st = load_library().dp_clip_accumulate_dense_batched(ctx, n, arr([_ptr(t) for t in As]), arr([_ptr(t) for t in Gs]),
+                                                         _dtype_of(As[0]), B, T, d_in, d_out, float(C), _f32(sqnorms),
+                                                         arr([_f32(t) for t in sum_Ws]), pb)
+    _check(ctx, st, "dp_clip_accumulate_dense_batched")
 
 
 def dp_clip_accumulate_layernorm(ctx, Xhat, G, C, sqnorms, sum_gamma, sum_beta):

@@ -264,6 +264,28 @@ dp_status dp_clip_accumulate_dense(dp_ctx* ctx, const void* A, const void* G, dp
     return dpk_weighted_gemm(ctx, A, G, dtype, B, T, d_in, d_out, sqnorms, C, sum_W, sum_b);
 }
 
+dp_status dp_clip_accumulate_dense_batched(dp_ctx* ctx, int n_layers, const void* const* A, const void* const* G,
+                                           dp_dtype dtype, int B, int T, int d_in, int d_out, float C,
+                                           const float* sqnorms, float* const* sum_W, float* const* sum_b) {
+    REQUIRE_CTX(ctx);
+    TRY(check_dtype(ctx, dtype));
+    TRY(check_bt(ctx, B, T));
+    if (n_layers < 0 || d_in < 0 || d_out < 0) FAIL(ctx, DP_ERR_SHAPE, "negative layer count or width");
+    if (n_layers == 0) return DP_OK;
+    if (!A || !G || !sum_W) FAIL(ctx, DP_ERR_NULL, "a pointer table is NULL");
+    for (int l = 0; l < n_layers; ++l) {
+        TRY(check_tensor(ctx, "A[l]", A[l], dtype, d_in));
+        TRY(check_tensor(ctx, "G[l]", G[l], dtype, d_out));
+        TRY(check_f32(ctx, "sum_W[l]", sum_W[l]));
+        if (dtype == DP_BF16 && ((uintptr_t)sum_W[l] & 15)) FAIL(ctx, DP_ERR_ALIGN, "sum_W[%d] is not 16-byte aligned", l);
+        if (sum_b && sum_b[l]) TRY(check_f32(ctx, "sum_b[l]", sum_b[l]));
+    }
+    TRY(check_f32(ctx, "sqnorms", sqnorms));
+    TRY(check_clip(ctx, C, B));
+    if (B == 0 || T == 0 || d_out == 0) return DP_OK;
+    return dpk_weighted_gemm_batched(ctx, n_layers, A, G, dtype, B, T, d_in, d_out, sqnorms, C, sum_W, sum_b);
+}
+
 dp_status dp_clip_accumulate_layernorm(dp_ctx* ctx, const void* Xhat, const void* G, dp_dtype dtype, int B, int T,
                                        int d, float C, const float* sqnorms, float* sum_gamma, float* sum_beta) {
     REQUIRE_CTX(ctx);

@@ -166,6 +166,10 @@ dp_status dpk_materialise_sqnorms(dp_ctx*, const void* A, const void* G, dp_dtyp
 dp_status dpk_weighted_gemm(dp_ctx*, const void* A, const void* G, dp_dtype, int B, int T, int d_in, int d_out,
                             const float* sqnorms, float C, float* sum_W, float* sum_b);
 
+dp_status dpk_weighted_gemm_batched(dp_ctx*, int n, const void* const* A, const void* const* G, dp_dtype, int B, int T,
+                                    int d_in, int d_out, const float* sqnorms, float C, float* const* sum_W,
+                                    float* const* sum_b);
+
 // column statistics shared by LayerNorm and dense-bias terms:
 //   sqnorms:  n[i] += [use_x] sum_j (sum_t g x)^2 + [use_1] sum_j (sum_t g)^2
 //   sums:     out_x[j] += sum_i c_i sum_t g x ; out_1[j] += sum_i c_i sum_t g   (either may be NULL)

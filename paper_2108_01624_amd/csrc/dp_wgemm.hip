@@ -53,6 +53,21 @@ struct WgemmArgs {
     int rect_m, rect_n;  // mode 2: the tile grid is cut into rect_m x rect_n rectangles, 8 / nsplit per split
 };
 
+// Several layers of one shape in one launch (direct-to-LDS kernel): the unit of work distribution is the pair
+// (layer, row split); `base` describes the common shape, and base.A / base.G / base.out are not used.
+constexpr int MAX_BATCH = 16;
+struct LayerPtrs {
+    const uint16_t* A;
+    const uint16_t* G;
+    float* out;      // EPI_ADD: the layer's sum_W; EPI_STORE: the layer's first partial [nsplit][d_in][d_out]
+    float* sum_b;    // the layer's bias sum buffer or nullptr (device code only tests it; the finish kernel adds)
+};
+struct WgemmBatchArgs {
+    WgemmArgs base;
+    int n_layers;
+    LayerPtrs L[MAX_BATCH];
+};
+
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef short s16x8_t __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
@@ -412,33 +427,40 @@ __device__ __forceinline__ i32x4_t make_rsrc(const void* base, uint32_t bytes) {
 }
 
 template <int EPI>
-__global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmArgs a) {
+__global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmBatchArgs b) {
     constexpr int MI = 4, NI = 2, WVN = 4, NT = 512;
     constexpr int WM = 128, WN = 64, BM = 256, BN = 256;
     constexpr int LPS = 4;  // LDS-filling loads per wave per stage (2 for A, 2 for G)
     __shared__ __attribute__((aligned(16))) uint16_t As[DMA_NS][BK * BM];
     __shared__ __attribute__((aligned(16))) uint16_t Gs[DMA_NS][BK * BN];
+    const WgemmArgs& a = b.base;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wr = wave / WVN, wc = wave % WVN;
     const int ntiles = a.tiles_m * a.tiles_n;
-    int tile, split;
+    const int nunits = b.n_layers * a.nsplit;  // unit = layer * nsplit + split
+    // Workgroup ids are dealt to the 8 XCDs round-robin: an XCD gets whole units (mode 1) or one rectangle of
+    // one unit's tile grid (mode 2), so that its L2 sees each operand row and column about once.
+    int tile, unit;
     if (a.xcd_map == 1) {
         const int g = blockIdx.x, slot = g >> 3;
-        split = (slot / ntiles) * 8 + (g & 7);
+        unit = (slot / ntiles) * 8 + (g & 7);
         tile = slot % ntiles;
-        if (split >= a.nsplit) return;
+        if (unit >= nunits) return;
     } else if (a.xcd_map == 2) {
         const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
         const int nrect = a.rect_m * a.rect_n;
         const int rect = xcd % nrect;
         const int tm = a.tiles_m / a.rect_m, tn = a.tiles_n / a.rect_n;
-        split = xcd / nrect;
+        unit = xcd / nrect;
         tile = ((rect / a.rect_n) * tm + slot / tn) * a.tiles_n + (rect % a.rect_n) * tn + slot % tn;
     } else {
         tile = blockIdx.x % ntiles;
-        split = blockIdx.x / ntiles;
+        unit = blockIdx.x / ntiles;
     }
+    const int layer = unit / a.nsplit, split = unit % a.nsplit;
+    const uint16_t* Aptr = b.L[layer].A;
+    const uint16_t* Gptr = b.L[layer].G;
     const int pm = tile / a.tiles_n, qn = tile % a.tiles_n;
     const int p0 = pm * BM, q0 = qn * BN;
     const long k_lo = (long)split * a.rows_per_split;
@@ -446,8 +468,8 @@ __global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmArgs a) {
     const int nrows = k_hi > k_lo ? (int)(k_hi - k_lo) : 0;
     const int nsteps = (nrows + BK - 1) / BK;
 
-    const i32x4_t rA = make_rsrc(a.A + (size_t)k_lo * a.d_in, (uint32_t)((size_t)nrows * a.d_in * 2));
-    const i32x4_t rG = make_rsrc(a.G + (size_t)k_lo * a.d_out, (uint32_t)((size_t)nrows * a.d_out * 2));
+    const i32x4_t rA = make_rsrc(Aptr + (size_t)k_lo * a.d_in, (uint32_t)((size_t)nrows * a.d_in * 2));
+    const i32x4_t rG = make_rsrc(Gptr + (size_t)k_lo * a.d_out, (uint32_t)((size_t)nrows * a.d_out * 2));
 
     // Load j (0, 1) of this wave fills tile rows 4*wave + 2*j and + 1: lane l -> row + l/32, LDS chunk l%32,
     // which holds global chunk (l%32) ^ 4*(row%4) (bank swizzle, see the file header).
@@ -509,7 +531,7 @@ __global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmArgs a) {
             for (int j = 0; j < NI; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fg[j], acc[i][j], 0, 0, 0);
     };
-    const bool want_bias = a.bias_part != nullptr;
+    const bool want_bias = b.L[layer].sum_b != nullptr;
     const int duty_mod = 2 * a.tiles_m, duty = 2 * pm + wr;
     const uint32_t one2 = 0x3F803F80u;  // two bf16 ones
     const bf16x8_t ones = __builtin_bit_cast(bf16x8_t, u32x4_t{one2, one2, one2, one2});
@@ -577,7 +599,7 @@ __global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmArgs a) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing may still be writing LDS when the workgroup ends
 
     // MFMA tile (i, j): accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
-    float* base = a.out + (EPI == EPI_STORE ? (size_t)split * a.d_in * a.d_out : (size_t)0);
+    float* base = b.L[layer].out + (EPI == EPI_STORE ? (size_t)split * a.d_in * a.d_out : (size_t)0);
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -597,13 +619,25 @@ __global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmArgs a) {
         }
     if (want_bias && lane < 32) {
         // every row of the ones-product equals the column sums; row 0 sits in register 0 of lanes 0..31
-        float* bp = a.bias_part + ((size_t)(split * a.tiles_m + pm) * 2 + wr) * a.d_out;
+        float* bp = a.bias_part + ((size_t)(unit * a.tiles_m + pm) * 2 + wr) * a.d_out;
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
             const int q = q0 + wc * WN + 32 * j + lane;
             if (q < a.d_out) bp[q] = bacc[j][0] * c_cur;
         }
     }
+}
+
+// sum_b[layer][q] += sum over the layer's nb partial rows, in row order (fixed order).  grid (n_layers, d_out/256).
+__global__ __launch_bounds__(256) void bias_finish_kernel(WgemmBatchArgs b, int nb) {
+    const int layer = blockIdx.x;
+    float* dst = b.L[layer].sum_b;
+    const int q = blockIdx.y * 256 + threadIdx.x;
+    if (!dst || q >= b.base.d_out) return;
+    const float* src = b.base.bias_part + (size_t)layer * nb * b.base.d_out + q;
+    float t = 0.f;
+    for (int r = 0; r < nb; ++r) t += src[(size_t)r * b.base.d_out];
+    dst[q] += t;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -704,6 +738,138 @@ static inline bool range_ok(long rows, int d_in, int d_out) {
     return (rows + 4 * BK) * w * 2 < (1l << 31);
 }
 
+// Row-split count for `total_tiles` tiles: about 256 workgroups (one per CU); counts below 8 are powers of two
+// and larger ones multiples of 8 so that units map onto the 8 XCDs; each split keeps at least 256 rows.
+static long choose_nsplit(long total_tiles, long ksteps) {
+    long nsplit = 1;
+    if (total_tiles < 256) {
+        nsplit = (256 + total_tiles - 1) / total_tiles;
+        const long max_split = (ksteps + 7) / 8;
+        if (nsplit >= 8) nsplit = (nsplit / 8) * 8;
+        else if (nsplit > 4) nsplit = max_split >= 8 ? 8 : 4;
+        else if (nsplit == 3) nsplit = 4;
+        if (nsplit > max_split) nsplit = max_split < 1 ? 1 : max_split;
+        if (nsplit < 1) nsplit = 1;
+    }
+    return nsplit;
+}
+
+// Clip-weighted sums of n same-shaped dense layers.  Layers that the direct-to-LDS kernel can take (bf16, both
+// widths >= 256, T a multiple of the stage height) go out in launches of up to MAX_BATCH layers; anything else
+// falls back to one call per layer.
+dp_status dpk_weighted_gemm_batched(dp_ctx* ctx, int n, const void* const* A, const void* const* G, dp_dtype dt, int B,
+                                    int T, int d_in, int d_out, const float* sqnorms, float C, float* const* sum_W,
+                                    float* const* sum_b) {
+    const bool dma = dt == DP_BF16 && d_in > 0 && use_dma_path(tile_cfg(d_in, d_out), T % BK == 0);
+    if (!dma) {
+        for (int l = 0; l < n; ++l) {
+            dp_status st = dpk_weighted_gemm(ctx, A[l], G[l], dt, B, T, d_in, d_out, sqnorms, C, sum_W[l], sum_b ? sum_b[l] : nullptr);
+            if (st != DP_OK) return st;
+        }
+        return DP_OK;
+    }
+    const long K = (long)B * T;
+    const long ksteps = (K + BK - 1) / BK;
+    for (int l0 = 0; l0 < n; l0 += MAX_BATCH) {
+        const int nl = n - l0 < MAX_BATCH ? n - l0 : MAX_BATCH;
+        WgemmBatchArgs b;
+        WgemmArgs& a = b.base;
+        a.A = nullptr;
+        a.G = nullptr;
+        a.out = nullptr;
+        a.sqnorms = sqnorms;
+        a.C = C;
+        a.T = T;
+        a.d_in = d_in;
+        a.d_out = d_out;
+        a.K = K;
+        a.tiles_m = (d_in + 255) / 256;
+        a.tiles_n = (d_out + 255) / 256;
+        const int ntiles = a.tiles_m * a.tiles_n;
+        long nsplit = choose_nsplit((long)nl * ntiles, ksteps);
+        while (!range_ok((ksteps + nsplit - 1) / nsplit * BK, d_in, d_out)) nsplit *= 2;
+        dp_ws_alloc ws(ctx);
+        float* part = nullptr;
+        while (nsplit > 1) {
+            ws.off = 0;
+            part = ws.get<float>((size_t)nl * nsplit * d_in * d_out);
+            if (part) break;
+            nsplit = nsplit > 8 ? nsplit - 8 : nsplit / 2;  // shrink to what the workspace holds
+        }
+        const long steps_per = (ksteps + nsplit - 1) / nsplit;
+        a.rows_per_split = steps_per * BK;
+        if (!range_ok(a.rows_per_split, d_in, d_out)) {
+            DP_SET_ERR(ctx, "dp_clip_accumulate_dense: workspace too small to split %ld rows", K);
+            return DP_ERR_WORKSPACE;
+        }
+        nsplit = (ksteps + steps_per - 1) / steps_per;
+        a.nsplit = (int)nsplit;
+        const long nunits = (long)nl * nsplit;
+        a.xcd_map = nunits >= 8 ? 1 : 0;
+        a.rect_m = a.rect_n = 1;
+        if (nunits < 8 && 8 % nunits == 0) {
+            // 8 / nunits rectangles per unit: the cut with the smallest half-perimeter (operand bytes per XCD)
+            const int nrect = 8 / (int)nunits;
+            int best = -1;
+            for (int rm = 1; rm <= nrect; ++rm) {
+                if (nrect % rm) continue;
+                const int rn = nrect / rm;
+                if (a.tiles_m % rm || a.tiles_n % rn) continue;
+                const int cost = a.tiles_m / rm + a.tiles_n / rn;
+                if (best < 0 || cost < best) {
+                    best = cost;
+                    a.rect_m = rm;
+                    a.rect_n = rn;
+                }
+            }
+            if (best >= 0) a.xcd_map = 2;
+        }
+        const long nwg = a.xcd_map == 1 ? ((nunits + 7) / 8) * 8 * ntiles : nunits * ntiles;
+        if (nwg > 0x7FFFFFFFl) {
+            DP_SET_ERR(ctx, "dp_clip_accumulate_dense: too many tiles");
+            return DP_ERR_SHAPE;
+        }
+        b.n_layers = nl;
+        bool any_bias = false;
+        for (int l = 0; l < MAX_BATCH; ++l) {
+            const int src = l0 + (l < nl ? l : 0);
+            b.L[l].A = (const uint16_t*)A[src];
+            b.L[l].G = (const uint16_t*)G[src];
+            b.L[l].out = nsplit == 1 ? sum_W[src] : part + (size_t)l * nsplit * d_in * d_out;
+            b.L[l].sum_b = sum_b ? sum_b[src] : nullptr;
+            if (l < nl && b.L[l].sum_b) any_bias = true;
+        }
+        // bias partials: one row per (unit, tile row, wave row)
+        const int nb = (int)nsplit * a.tiles_m * 2;
+        a.bias_part = nullptr;
+        if (any_bias) {
+            a.bias_part = ws.get<float>((size_t)nl * nb * d_out);
+            if (!a.bias_part) {
+                DP_SET_ERR(ctx, "workspace too small for the bias partials");
+                return DP_ERR_WORKSPACE;
+            }
+        }
+        {
+            dp_prof_scope prof(ctx, DP_PROF_WGEMM, 2.0 * (double)K * d_in * d_out * nl);
+            if (nsplit == 1) hipLaunchKernelGGL((wgemm_dma_kernel<EPI_ADD>), dim3((unsigned)nwg), dim3(512), 0, ctx->stream, b);
+            else hipLaunchKernelGGL((wgemm_dma_kernel<EPI_STORE>), dim3((unsigned)nwg), dim3(512), 0, ctx->stream, b);
+        }
+        DP_LAUNCH_CHECK(ctx, "wgemm_dma");
+        if (nsplit > 1) {
+            for (int l = 0; l < nl; ++l) {
+                dp_status st = dpk_reduce_partials(ctx, b.L[l].out, (int)nsplit, (size_t)d_in * d_out,
+                                                   (size_t)d_in * d_out, sum_W[l0 + l]);
+                if (st != DP_OK) return st;
+            }
+        }
+        if (any_bias) {
+            hipLaunchKernelGGL(bias_finish_kernel, dim3(nl, (d_out + 255) / 256), dim3(256), 0, ctx->stream, b, nb);
+            DP_LAUNCH_CHECK(ctx, "bias_finish");
+        }
+    }
+    return DP_OK;
+}
+
 dp_status dpk_weighted_gemm(dp_ctx* ctx, const void* A, const void* G, dp_dtype dt, int B, int T, int d_in, int d_out,
                             const float* sqnorms, float C, float* sum_W, float* sum_b) {
     const long K = (long)B * T;
@@ -725,6 +891,8 @@ dp_status dpk_weighted_gemm(dp_ctx* ctx, const void* A, const void* G, dp_dtype 
         if (st != DP_OK) return st;
         return dpk_colstat_sums(ctx, nullptr, G, dt, B, T, d_out, ctx->cbuf, nullptr, sum_b);
     }
+    if (use_dma_path(tile_cfg(d_in, d_out), T % BK == 0))
+        return dpk_weighted_gemm_batched(ctx, 1, &A, &G, dt, B, T, d_in, d_out, sqnorms, C, &sum_W, &sum_b);
     const bool big = big_tile(d_in, d_out);
     const int BM = big ? 256 : 128, BN = BM;
     WgemmArgs a;
@@ -806,29 +974,6 @@ dp_status dpk_weighted_gemm(dp_ctx* ctx, const void* A, const void* G, dp_dtype 
     const bool uniform = T % BK == 0;
     const double flops = 2.0 * (double)K * d_in * d_out;
     const int cfg = tile_cfg(d_in, d_out);
-    if (use_dma_path(cfg, uniform)) {
-        // bias partials of this path: one row per (split, tile row, wave row)
-        const int nb = (int)nsplit * a.tiles_m * 2;
-        if (sum_b) {
-            a.bias_part = ws.get<float>((size_t)nb * d_out);
-            if (!a.bias_part) {
-                DP_SET_ERR(ctx, "workspace too small for the bias partials");
-                return DP_ERR_WORKSPACE;
-            }
-        }
-        a.out = nsplit == 1 ? sum_W : part;
-        {
-            dp_prof_scope prof(ctx, DP_PROF_WGEMM, flops);
-            if (nsplit == 1) hipLaunchKernelGGL((wgemm_dma_kernel<EPI_ADD>), dim3((unsigned)nwg), dim3(512), 0, ctx->stream, a);
-            else hipLaunchKernelGGL((wgemm_dma_kernel<EPI_STORE>), dim3((unsigned)nwg), dim3(512), 0, ctx->stream, a);
-        }
-        DP_LAUNCH_CHECK(ctx, "wgemm_dma");
-        dp_status st = DP_OK;
-        if (nsplit > 1)
-            st = dpk_reduce_partials(ctx, part, (int)nsplit, (size_t)d_in * d_out, (size_t)d_in * d_out, sum_W);
-        if (st == DP_OK && sum_b) st = dpk_reduce_partials(ctx, a.bias_part, nb, (size_t)d_out, (size_t)d_out, sum_b);
-        return st;
-    }
     if (nsplit == 1) {
         a.out = sum_W;
         dp_prof_scope prof(ctx, DP_PROF_WGEMM, flops);

@@ -56,19 +56,31 @@ class StepRunner:
                 ctx.sqnorms_embedding(l["ids"], l["G"], l["V"], l["distinct"], n)
         return n
 
-    def pass2(self, layers, C):
-        """S += sum_i clip(grad_i, C) for one micro-batch, using the norms left by pass1."""
+    def pass2(self, layers, C, batch_dense=True):
+        """S += sum_i clip(grad_i, C) for one micro-batch, using the norms left by pass1.  The sums of different
+        layers are independent, so dense layers of one shape are handed over together (16 at a time)."""
         ctx = self.ctx
         nB = layers[0]["G"].shape[0]
         n = self.sqnorms[:nB]
+        groups = {}
         for k, l in enumerate(layers):
             if l["kind"] == "dense":
-                sb = self.view(self.S, k, 1) if l["has_bias"] else None
-                ctx.clip_accumulate_dense(l["A"], l["G"], C, n, self.view(self.S, k, 0), sb)
+                if batch_dense:
+                    groups.setdefault((tuple(l["A"].shape), tuple(l["G"].shape), l["A"].dtype), []).append(k)
+                else:
+                    sb = self.view(self.S, k, 1) if l["has_bias"] else None
+                    ctx.clip_accumulate_dense(l["A"], l["G"], C, n, self.view(self.S, k, 0), sb)
             elif l["kind"] == "layernorm":
                 ctx.clip_accumulate_layernorm(l["X"], l["G"], C, n, self.view(self.S, k, 0), self.view(self.S, k, 1))
             else:
                 ctx.clip_accumulate_embedding(l["ids"], l["G"], l["V"], C, n, self.view(self.S, k, 0))
+        for ks in groups.values():
+            for i in range(0, len(ks), 16):
+                sel = ks[i:i + 16]
+                ctx.clip_accumulate_dense_batched(
+                    [layers[k]["A"] for k in sel], [layers[k]["G"] for k in sel], C, n,
+                    [self.view(self.S, k, 0) for k in sel],
+                    [self.view(self.S, k, 1) if layers[k]["has_bias"] else None for k in sel])
 
     def update(self, *, sigma, C, seed, step, batch_size, lr, beta1, beta2, eps=1e-11, weight_decay, zero_sum=True):
         self.ctx.noise_adamw(self.theta, self.m, self.v, self.S, sigma=sigma, C=C, seed=seed, step=step,

@@ -477,3 +477,42 @@ def test_zero_and_empty_calls(dp):
     assert lib.dp_clip_accumulate_layernorm(dp.handle, n.data_ptr(), n.data_ptr(), 1, 4, 0, 8, 1.0, n.data_ptr(), n.data_ptr(), n.data_ptr()) == 0
     dp.sync()
     assert host(n).tolist() == [1, 1, 1, 1]
+
+
+# ------------------------------------------------------------------------------------------------
+# several same-shaped dense layers in one call
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n,B,T,d_in,d_out", [(3, 8, 128, 256, 384), (18, 2, 32, 256, 256), (5, 16, 128, 512, 256),
+                                              (2, 3, 50, 512, 264), (3, 4, 64, 72, 136)])
+def test_clip_accumulate_dense_batched(dp, n, B, T, d_in, d_out):
+    C = 1.0
+    sq = syn.synthetic_sqnorms(B, C, 300)
+    c = orc.clip_factors(sq.astype(np.float64), C)
+    As = [gen((B, T, d_in), 1.0, 310 + l, "bf16") for l in range(n)]
+    Gs = [gen((B, T, d_out), 0.1, 340 + l, "bf16") for l in range(n)]
+    SW = [torch.full((d_in, d_out), 0.25, dtype=torch.float32, device=DEV) for _ in range(n)]
+    Sb = [torch.full((d_out,), -0.5, dtype=torch.float32, device=DEV) if l != 1 else None for l in range(n)]
+    dp.clip_accumulate_dense_batched([to_dev(a) for a in As], [to_dev(g) for g in Gs], C, f32_dev(sq), SW, Sb)
+    dp.sync()
+    for l in range(n):
+        W_ref, b_ref = orc.clip_accumulate_dense(As[l], Gs[l], c, True)
+        rel = assert_sums_close(host(SW[l]).astype(np.float64) - 0.25, W_ref, TOL_BF16, f"layer {l} sum_W")
+        assert rel < 5e-3
+        if Sb[l] is not None:
+            assert_sums_close(host(Sb[l]).astype(np.float64) + 0.5, b_ref, 1e-3, f"layer {l} sum_b")
+
+
+def test_batched_equals_single_layer_calls(dp):
+    """The direct-to-LDS path keeps exact bf16 products: one layer alone and inside a batch agree closely."""
+    n, B, T, d_in, d_out, C = 4, 32, 128, 256, 256, 1.0
+    sq = f32_dev(syn.synthetic_sqnorms(B, C, 301))
+    As = [to_dev(gen((B, T, d_in), 1.0, 400 + l, "bf16")) for l in range(n)]
+    Gs = [to_dev(gen((B, T, d_out), 0.1, 420 + l, "bf16")) for l in range(n)]
+    one = [torch.zeros(d_in, d_out, dtype=torch.float32, device=DEV) for _ in range(n)]
+    bat = [torch.zeros(d_in, d_out, dtype=torch.float32, device=DEV) for _ in range(n)]
+    for l in range(n):
+        dp.clip_accumulate_dense(As[l], Gs[l], C, sq, one[l], None)
+    dp.clip_accumulate_dense_batched(As, Gs, C, sq, bat, None)
+    dp.sync()
+    for l in range(n):
+        assert_sums_close(host(bat[l]), host(one[l]).astype(np.float64), 1e-5, f"layer {l}")
