@@ -12,6 +12,8 @@
 //
 // Roofline: HBM at T = 128 (2*T*(d_in+d_out) bytes per example against 2*T^2*(d_in+d_out) flops, i.e.
 // T flop/B, below the machine balance of ~310 flop/B); each row panel is read once per block it is in.
+#include <stdlib.h>
+
 #include "dp_common.h"
 
 namespace {
@@ -174,6 +176,149 @@ __global__ __launch_bounds__(256, 2) void gram_bf16_kernel(const uint16_t* __res
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// T <= 128 (one block per example), both widths multiples of 64: the same computation with the row panels
+// streamed straight into a four-stage LDS ring by LDS-filling buffer loads, three 16 KiB chunks in flight per
+// workgroup (the register-staged kernel above keeps one: at two workgroups per CU that is too few bytes in
+// flight to cover the HBM latency at full bandwidth).  The loads go through inline assembly so that the wave
+// waits (vmcnt) for the chunk it is about to publish only, not for every load in flight.
+// LDS layout: [128 rows][8 chunks of 16 B], chunk position c of row r holds global chunk c ^ ((r >> 1) & 7):
+// the 16-byte reads of 16 consecutive rows then fall into 64 distinct banks.
+// ------------------------------------------------------------------------------------------------
+typedef int gram_i32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void gram_dma16(gram_i32x4 rsrc, uint32_t lds_byte_addr, int voff, int soff) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_byte_addr), "v"(voff), "s"(rsrc), "s"(soff)
+                 : "memory");
+}
+
+__device__ __forceinline__ gram_i32x4 gram_rsrc(const void* base, uint32_t bytes) {
+    const uint64_t p = (uint64_t)base;
+    gram_i32x4 r;
+    r[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)p);
+    r[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)(p >> 32));
+    r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+    r[3] = 0x00020000;
+    return r;
+}
+
+// GDK: contraction chunk per stage (a row segment of 2*GDK bytes per load); NS: ring stages.
+template <int GDK, int NS, int WGS_PER_CU>
+__global__ __launch_bounds__(256, WGS_PER_CU) void gram_dma_kernel(const uint16_t* __restrict__ A,
+                                                                   const uint16_t* __restrict__ G, int T, int d_in,
+                                                                   int d_out, int has_bias, float* __restrict__ out) {
+    constexpr int STAGE = GB * GDK;        // bf16 elements per stage
+    constexpr int CPR = GDK / 8;           // 16-byte chunks per row (8 or 16)
+    constexpr int RPI = 64 / CPR;          // rows filled by one wave-wide load
+    constexpr int LPS = GB / RPI / 4;      // loads per wave per stage
+    __shared__ __attribute__((aligned(16))) uint16_t ring[NS][STAGE];
+    __shared__ float wred[4];
+    const int i = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wr = wave >> 1, wc = wave & 1;
+    const bool active = wr <= wc;  // the lower-left quadrant mirrors the upper-right one
+    const int nchA = d_in / GDK, nch = nchA + d_out / GDK;
+    // chunk position c of row r holds global chunk c ^ swz(r): 16 consecutive rows -> 64 distinct banks
+    auto swz = [](int r) { return CPR == 8 ? (r >> 1) & 7 : r & 15; };
+
+    // rows >= T of the panel lie outside the example's byte range and read as zero
+    const gram_i32x4 rA = gram_rsrc(A + (size_t)i * T * d_in, (uint32_t)((size_t)T * d_in * 2));
+    const gram_i32x4 rG = gram_rsrc(G + (size_t)i * T * d_out, (uint32_t)((size_t)T * d_out * 2));
+    // load j of this wave fills rows (LPS*wave + j)*RPI .. : lane l -> row + l/CPR, chunk position l%CPR
+    int voffA[LPS], voffG[LPS];
+    uint32_t ldsoff[LPS];
+#pragma unroll
+    for (int j = 0; j < LPS; ++j) {
+        const int row0 = (LPS * wave + j) * RPI, row = row0 + lane / CPR;
+        const int cg = (lane % CPR) ^ swz(row);
+        voffA[j] = (row * d_in + cg * 8) * 2;
+        voffG[j] = (row * d_out + cg * 8) * 2;
+        ldsoff[j] = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)&ring[0][row0 * GDK];
+    }
+    int ibuf = 0;  // buffer of the next stage to issue
+    auto issue = [&](int st) {
+        const bool isA = st < nchA;
+        const int soff = __builtin_amdgcn_readfirstlane((isA ? st : st - nchA) * GDK * 2);
+#pragma unroll
+        for (int j = 0; j < LPS; ++j) {
+            const uint32_t dst = __builtin_amdgcn_readfirstlane(ldsoff[j] + ibuf * (STAGE * 2));
+            if (isA) gram_dma16(rA, dst, voffA[j], soff);
+            else if (st < nch) gram_dma16(rG, dst, voffG[j], soff);
+            else gram_dma16(rG, dst, voffG[j], 0x7FFFFFF0);  // past the end: reads zeros, keeps the load count uniform
+        }
+        ibuf = ibuf + 1 == NS ? 0 : ibuf + 1;
+    };
+    // fragment addresses (elements) inside a stage for k step 0
+    int fr[2], fc[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int r = wr * 64 + u * 32 + (lane & 31), c = wc * 64 + u * 32 + (lane & 31);
+        fr[u] = r * GDK + (((lane >> 5) ^ swz(r)) << 3);
+        fc[u] = c * GDK + (((lane >> 5) ^ swz(c)) << 3);
+    }
+    f32x16_t accA[2][2], accG[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) accA[a][b][r] = accG[a][b][r] = 0.f;
+
+#pragma unroll
+    for (int st = 0; st < NS - 1; ++st) issue(st);
+    int cbuf = 0;
+    for (int s = 0; s < nch; ++s) {
+        // my loads of chunk s have landed (later chunks may be in flight); after the barrier everyone's have,
+        // and everyone is done reading chunk s-1, whose buffer the newest chunk overwrites
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * LPS) : "memory");
+        __syncthreads();
+        issue(s + NS - 1);
+        if (active) {
+            const uint16_t* st = ring[cbuf];
+            const bool isA = s < nchA;
+#pragma unroll
+            for (int kk = 0; kk < GDK / 16; ++kk) {
+                bf16x8_t a0[2], b0[2];
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    // k chunk 2*kk + lane/32: its swizzled position differs from the kk = 0 one by XOR 2*kk
+                    const int xr = fr[u] ^ ((2 * kk) << 3), xc = fc[u] ^ ((2 * kk) << 3);
+                    a0[u] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(st + xr));
+                    b0[u] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(st + xc));
+                }
+                if (isA) {
+#pragma unroll
+                    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                        for (int nt = 0; nt < 2; ++nt)
+                            accA[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mt], b0[nt], accA[mt][nt], 0, 0, 0);
+                } else {
+#pragma unroll
+                    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                        for (int nt = 0; nt < 2; ++nt)
+                            accG[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mt], b0[nt], accG[mt][nt], 0, 0, 0);
+                }
+            }
+        }
+        cbuf = cbuf + 1 == NS ? 0 : cbuf + 1;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing may still be writing LDS when the workgroup ends
+    const float bias_term = has_bias ? 1.f : 0.f;
+    float sum = 0.f;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sum += (accA[a][b][r] + bias_term) * accG[a][b][r];
+    sum *= wr == wc ? 1.f : (wr < wc ? 2.f : 0.f);
+    const float tot = dp_block_sum<256>(sum, wred);
+    if (threadIdx.x == 0) out[i] += tot;
+}
+
 // fp32 reference-precision paths (small shapes; parity configuration with fp32 inputs).
 // One workgroup per example; thread-strided loop over the pairs t <= s.
 __global__ __launch_bounds__(256) void gram_f32_kernel(const float* __restrict__ A, const float* __restrict__ G, int T,
@@ -243,6 +388,26 @@ dp_status dpk_gram_sqnorms(dp_ctx* ctx, const void* A, const void* G, dp_dtype d
         lds_attr_set = true;
     }
     const double bytes = 2.0 * (double)B * T * ((double)d_in + d_out);
+    if (npairs == 1 && d_in % GK == 0 && d_out % GK == 0 && (size_t)T * (d_in > d_out ? d_in : d_out) * 2 < (1u << 31)) {
+        dp_prof_scope prof(ctx, DP_PROF_GRAM, bytes);
+        static int variant = -1;
+        if (variant < 0) {  // DPCLIP_GRAM_VARIANT: tuning aid
+            const char* e = getenv("DPCLIP_GRAM_VARIANT");
+            variant = e ? atoi(e) : 1;
+        }
+        const bool wide = d_in % 128 == 0 && d_out % 128 == 0;
+        if (variant == 1 && wide)
+            hipLaunchKernelGGL((gram_dma_kernel<128, 2, 2>), dim3(B), dim3(256), 0, ctx->stream, (const uint16_t*)A,
+                               (const uint16_t*)G, T, d_in, d_out, has_bias, sqnorms);
+        else if (variant == 2 && wide)
+            hipLaunchKernelGGL((gram_dma_kernel<128, 3, 1>), dim3(B), dim3(256), 0, ctx->stream, (const uint16_t*)A,
+                               (const uint16_t*)G, T, d_in, d_out, has_bias, sqnorms);
+        else
+            hipLaunchKernelGGL((gram_dma_kernel<64, 4, 2>), dim3(B), dim3(256), 0, ctx->stream, (const uint16_t*)A,
+                               (const uint16_t*)G, T, d_in, d_out, has_bias, sqnorms);
+        DP_LAUNCH_CHECK(ctx, "gram_dma");
+        return DP_OK;
+    }
     if (npairs == 1) {
         dp_prof_scope prof(ctx, DP_PROF_GRAM, bytes);
         hipLaunchKernelGGL(gram_bf16_kernel, dim3(B), dim3(256), lds, ctx->stream, (const uint16_t*)A,
