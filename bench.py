@@ -134,6 +134,16 @@ def main():
     ctx.profile_enable(False)
 
     achieved = g_flops / (g_ms * 1e-3) / 1e12 if g_ms > 0 else 0.0
+    # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary of this same
+    # command (FETCH_SIZE and WRITE_SIZE runs, scaled as described there); null if no summary is present
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"bench_{args.workload.lower()}_hbm_traffic.json")
+    if not args.batch and os.path.exists(tpath):
+        try:
+            k = json.load(open(tpath))["kernels"]["wgemm_dma_kernel"]
+            traffic = k["hbm_read_bytes_per_launch"] + k["hbm_write_bytes_per_launch"]
+        except Exception:
+            traffic = None
     out = {
         "metric": "clipped per-example grads/sec (examples/s), BERT-Large seq128; MFMA util %",
         "value": B / (ms_per_step * 1e-3),
@@ -154,8 +164,9 @@ def main():
                                if args.workload != "C2" else f"C2: BERT-Base-shaped stack, B={B}, T={T}",
                    "params": int(run.P), "micro_batch": B, "seq_len": T, "input_bytes": int(in_bytes)},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
-                     "kernel": "wgemm_bf16_kernel (clip-weighted A^T diag(c) G)",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
+                     "traffic_unit": "HBM bytes per launch (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, profiles/)",
+                     "kernel": "wgemm_dma_kernel (clip-weighted A^T diag(c) G, up to 16 same-shaped layers per launch)",
                      "avg_launch_ms": g_ms / max(1, g_n), "launches": int(g_n)},
         "kernels": {
             "gram_sqnorms": {"bound": "hbm", "achieved_GBps": n_bytes / (n_ms * 1e-3) / 1e9 if n_ms else 0.0,

@@ -445,8 +445,12 @@ __global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmBatchArgs b) {
     if (a.xcd_map == 1) {
         const int g = blockIdx.x, slot = g >> 3;
         unit = (slot / ntiles) * 8 + (g & 7);
-        tile = slot % ntiles;
         if (unit >= nunits) return;
+        // An XCD runs about 32 workgroups at a time: walk the unit's tile grid in rect_m x rect_n rectangles so
+        // that those 32 share as many operand columns as possible (rect 1 x 1 = plain row-major order).
+        const int t = slot % ntiles, per = a.rect_m * a.rect_n, rect = t / per, w = t % per;
+        const int rpr = a.tiles_n / a.rect_n;
+        tile = ((rect / rpr) * a.rect_m + w / a.rect_n) * a.tiles_n + (rect % rpr) * a.rect_n + w % a.rect_n;
     } else if (a.xcd_map == 2) {
         const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
         const int nrect = a.rect_m * a.rect_n;
@@ -823,6 +827,22 @@ dp_status dpk_weighted_gemm_batched(dp_ctx* ctx, int n, const void* const* A, co
                 }
             }
             if (best >= 0) a.xcd_map = 2;
+        }
+        if (a.xcd_map == 1 && ntiles > 32) {
+            // rectangle of about 32 tiles (one XCD's worth of workgroups) with the smallest half-perimeter
+            int best = -1;
+            for (int tm = 1; tm <= a.tiles_m && tm <= 32; ++tm) {
+                if (a.tiles_m % tm) continue;
+                int tn = 32 / tm;
+                if (tn > a.tiles_n) tn = a.tiles_n;
+                while (tn > 1 && a.tiles_n % tn) --tn;
+                const int cost = (tm + tn) * 1024 / (tm * tn);  // operand columns fetched per tile
+                if (best < 0 || cost < best) {
+                    best = cost;
+                    a.rect_m = tm;
+                    a.rect_n = tn;
+                }
+            }
         }
         const long nwg = a.xcd_map == 1 ? ((nunits + 7) / 8) * 8 * ntiles : nunits * ntiles;
         if (nwg > 0x7FFFFFFFl) {
