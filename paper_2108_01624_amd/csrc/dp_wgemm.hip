@@ -774,8 +774,14 @@ dp_status dpk_weighted_gemm_batched(dp_ctx* ctx, int n, const void* const* A, co
     }
     const long K = (long)B * T;
     const long ksteps = (K + BK - 1) / BK;
-    for (int l0 = 0; l0 < n; l0 += MAX_BATCH) {
-        const int nl = n - l0 < MAX_BATCH ? n - l0 : MAX_BATCH;
+    // layers per launch: enough to give every CU one workgroup, but no more than one round of workgroups when a
+    // layer has many tiles (workgroups that run at the same time share operands through L2; later rounds do not)
+    const int tiles_per_layer = ((d_in + 255) / 256) * ((d_out + 255) / 256);
+    int per_launch = 256 / tiles_per_layer;
+    if (per_launch < 1) per_launch = 1;
+    if (per_launch > MAX_BATCH) per_launch = MAX_BATCH;
+    for (int l0 = 0; l0 < n; l0 += per_launch) {
+        const int nl = n - l0 < per_launch ? n - l0 : per_launch;
         WgemmBatchArgs b;
         WgemmArgs& a = b.base;
         a.A = nullptr;
