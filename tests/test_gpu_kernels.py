@@ -516,3 +516,35 @@ def test_batched_equals_single_layer_calls(dp):
     dp.sync()
     for l in range(n):
         assert_sums_close(host(bat[l]), host(one[l]).astype(np.float64), 1e-5, f"layer {l}")
+
+
+# ------------------------------------------------------------------------------------------------
+# Philox against an independent library (needs the HIP runtime, hence a GPU-box test)
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("seed,offset,n", [(0, 0, 64), (0x0123456789ABCDEF, 0, 4096), (2 ** 64 - 1, 4096, 1000),
+                                           (42, 7, 33), (1234, 4 * (2 ** 32) - 8, 64)])
+def test_philox_matches_rocrand_host_generator(dp, seed, offset, n):
+    """rocRAND's host-side Philox4x32-10 generator (seed -> key, stream offset -> counter, four words per
+    counter) is an implementation of the same published rounds by other hands: the oracle and the HIP kernel
+    must give its words bit for bit (step = 0 leaves the upper counter words zero, as rocRAND has them)."""
+    import ctypes
+
+    try:
+        lib = ctypes.CDLL("/opt/rocm/lib/librocrand.so")
+    except OSError:
+        pytest.skip("librocrand.so not available")
+    gen = ctypes.c_void_p()
+    if lib.rocrand_create_generator_host_blocking(ctypes.byref(gen), 404) != 0:  # ROCRAND_RNG_PSEUDO_PHILOX4_32_10
+        pytest.skip("rocRAND host generator cannot be created here")
+    try:
+        assert lib.rocrand_set_seed(gen, ctypes.c_ulonglong(seed)) == 0
+        assert lib.rocrand_set_offset(gen, ctypes.c_ulonglong(offset)) == 0
+        ref = np.zeros(n, dtype=np.uint32)
+        assert lib.rocrand_generate(gen, ref.ctypes.data_as(ctypes.c_void_p), ctypes.c_size_t(n)) == 0
+    finally:
+        lib.rocrand_destroy_generator(gen)
+    np.testing.assert_array_equal(orc.philox_u32(n, offset, seed, 0), ref)
+    out = torch.zeros(n, dtype=torch.int32, device=DEV)
+    dp.philox_u32(out, offset, seed, 0)
+    dp.sync()
+    np.testing.assert_array_equal(host(out).view(np.uint32), ref)

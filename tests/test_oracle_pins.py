@@ -312,7 +312,21 @@ def test_bf16_widening_matches_torch():
 # ----------------------------------------------------------------------------------------------
 # Adam with decoupled weight decay
 # ----------------------------------------------------------------------------------------------
-HP = dict(lr=6.0902e-4, beta1=0.75, beta2=0.9, eps=1e-11, weight_decay=1.0)  # Table 1, best trial
+def _table1():
+    """Best-trial hyper-parameters as the paper prints them (Table 1; xi from Algorithm 1)."""
+    import os
+
+    vals = {}
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "table1_best_trial.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                k, v = line.split()
+                vals[k] = float(v)
+    return dict(lr=vals["learning_rate"], beta1=1 - vals["one_minus_beta1"], beta2=1 - vals["one_minus_beta2"],
+                eps=vals["xi"], weight_decay=vals["weight_decay"])
+
+
+HP = _table1()
 
 
 def test_adamw_matches_torch_optim_five_steps():
@@ -488,3 +502,25 @@ def test_noise_depends_on_global_element_index():
     part = orc.noise_adamw(np.zeros(10), np.zeros(10), np.zeros(10), S[13:23], elem_offset=13, **kw)
     for a, b in zip(full, part):
         np.testing.assert_array_equal(a[13:23], b)
+
+
+# ----------------------------------------------------------------------------------------------
+# stored reference (written by tests/golden/make_oracle_reference.py from the oracle alone): drift guard
+# ----------------------------------------------------------------------------------------------
+def test_oracle_matches_its_stored_reference():
+    import importlib.util
+    import json
+    import os
+
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_oracle_reference", os.path.join(here, "make_oracle_reference.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    now = mod.build()
+    ref = json.load(open(os.path.join(here, "oracle_c1_reference.json")))
+    assert set(now) == set(ref)
+    for k in ref:
+        if k.startswith("philox") or k == "sum_idx":
+            assert now[k] == ref[k], k
+        else:
+            np.testing.assert_allclose(now[k], ref[k], rtol=1e-12, atol=1e-300, err_msg=k)
