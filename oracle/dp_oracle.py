@@ -28,8 +28,9 @@ invariant and clip no-op against a flat GEMM / bincount / index_add; torch.optim
 hand-worked element for the update; statistical moments and exact-uniform checks for the
 normals.  Philox known-answer vectors are NOT in this repository: its raw stream is
 "parity unpinned" on the CPU beyond an independent big-integer implementation, the
-inverse-round bijection check and avalanche statistics (a GPU-box test compares it with the
-rocRAND host generator where that library can run).
+inverse-round bijection check and avalanche statistics.  The gpu-marked test
+test_philox_matches_rocrand_host_generator pins the words bit for bit against rocRAND's host
+Philox4x32-10 generator, an independent implementation that only runs where a GPU is present.
 """
 from __future__ import annotations
 
