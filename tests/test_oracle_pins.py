@@ -177,6 +177,14 @@ def test_dense_orientation():
     S_W, _ = orc.clip_accumulate_dense(A, G, np.ones(1), False)
     assert S_W.shape == (3, 4)
     assert S_W[2, 1] == 6.0 and np.count_nonzero(S_W) == 1
+    # square layer (the attention projections): the shape cannot reveal a transposed product, the entry does
+    A = np.zeros((1, 2, 4))
+    A[0, 1, 3] = 5.0
+    G[0, 1, 0] = 7.0
+    S_W, _ = orc.clip_accumulate_dense(A, G, np.ones(1), False)
+    assert S_W[3, 0] == 35.0 and np.count_nonzero(S_W) == 1
+    gW, _ = orc.dense_example_grads(A[0], G[0])
+    assert gW[3, 0] == 35.0 and gW[0, 3] == 0.0
 
 
 # ----------------------------------------------------------------------------------------------
