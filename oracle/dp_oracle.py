@@ -368,3 +368,29 @@ def noise_adamw(theta, m, v, S, *, elem_offset: int, sigma: float, C: float, see
     v_hat = v_new / (1.0 - beta2 ** step)
     theta_new = theta - lr * (m_hat / (np.sqrt(v_hat) + eps) + wd * theta)
     return theta_new, m_new, v_new, g
+
+
+# --------------------------------------------------------------------------------------
+# gradient signal-to-noise ratio (the batch-size study of the experiments section)
+# --------------------------------------------------------------------------------------
+
+
+def gradient_snr_terms(S, *, elem_offset: int, sigma: float, C: float, seed: int, step: int):
+    """Squared L2 norms of the two vectors whose ratio the paper tracks over training: the aggregated
+    (clipped, summed) gradient S and the noise vector sigma*C*z that the update adds to it, over the
+    flat elements [elem_offset, elem_offset + len(S)).  Both are taken before the division by |B_t|
+    (which cancels in the ratio).  The noise vector is the one noise_adamw draws for the same
+    (seed, step, element)."""
+    S = to_f64(S)
+    f = lambda x: float(np.float32(x))
+    sigma, C = f(sigma), f(C)
+    signal_sq = float(np.sum(S * S))
+    if sigma == 0.0:
+        return signal_sq, 0.0
+    noise = sigma * C * normals(S.shape[0], elem_offset, seed, step)
+    return signal_sq, float(np.sum(noise * noise))
+
+
+def gradient_snr(signal_sq: float, noise_sq: float) -> float:
+    """||S||_2 / ||sigma C z||_2 from the two squared norms (summed over slices by the caller)."""
+    return float(np.sqrt(signal_sq / noise_sq)) if noise_sq > 0 else float("inf")

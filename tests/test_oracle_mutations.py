@@ -89,6 +89,17 @@ MUTANTS = [
     ("decay_coupled_into_gradient", [("    m_new = beta1 * m", "    g = g + wd * theta\n    m_new = beta1 * m", None),
                                      ("+ eps) + wd * theta)", "+ eps))", None)], "test_adamw_matches_torch_optim_five_steps"),
     ("decay_sign_flipped", [("+ eps) + wd * theta)", "+ eps) - wd * theta)", None)], "test_adamw_zero_gradient_is_pure_decay"),
+    ("snr_signal_not_squared", [("signal_sq = float(np.sum(S * S))", "signal_sq = float(np.sum(np.abs(S)))", None)], "test_gradient_snr_closed_forms"),
+    ("snr_noise_without_clip_norm", [("noise = sigma * C * normals(S.shape[0], elem_offset, seed, step)", "noise = sigma * normals(S.shape[0], elem_offset, seed, step)", None)],
+     "test_gradient_snr_closed_forms"),
+    ("snr_noise_ignores_offset", [("noise = sigma * C * normals(S.shape[0], elem_offset, seed, step)", "noise = sigma * C * normals(S.shape[0], 0, seed, step)", None)],
+     "test_gradient_snr_noise_is_what_the_update_adds"),
+    ("snr_noise_from_another_step", [("noise = sigma * C * normals(S.shape[0], elem_offset, seed, step)", "noise = sigma * C * normals(S.shape[0], elem_offset, seed, 1)", None)],
+     "test_gradient_snr_noise_is_what_the_update_adds"),
+    ("snr_ratio_of_squares", [("return float(np.sqrt(signal_sq / noise_sq)) if noise_sq > 0", "return float(signal_sq / noise_sq) if noise_sq > 0", None)],
+     "test_gradient_snr_closed_forms"),
+    ("snr_inverted", [("return float(np.sqrt(signal_sq / noise_sq)) if noise_sq > 0", "return float(np.sqrt(noise_sq / signal_sq)) if noise_sq > 0", None)],
+     "test_gradient_snr_closed_forms"),
     ("bf16_widening_shift", [("<< np.uint32(16)", "<< np.uint32(15)", None)], "test_bf16_widening_matches_torch"),
 ]
 

@@ -513,6 +513,60 @@ def test_noise_depends_on_global_element_index():
 
 
 # ----------------------------------------------------------------------------------------------
+# gradient signal-to-noise ratio (Section 5.2, effect of batch size on DP gradients)
+# ----------------------------------------------------------------------------------------------
+def test_gradient_snr_closed_forms():
+    n, sigma, C = 1 << 16, 0.6, 0.5
+    f = lambda x: float(np.float32(x))
+    S = np.full(n, 0.25)
+    sig, noi = orc.gradient_snr_terms(S, elem_offset=8, sigma=sigma, C=C, seed=7, step=3)
+    assert sig == n * 0.0625                                    # constant vector: n a^2, exact in binary
+    # chi-square with n degrees of freedom: mean n, standard deviation sqrt(2n)
+    assert abs(noi / (f(sigma) * f(C)) ** 2 - n) < 5 * math.sqrt(2 * n)
+    # sigma scales the noise norm linearly, C likewise; the signal does not move
+    sig2, noi2 = orc.gradient_snr_terms(S, elem_offset=8, sigma=2 * sigma, C=C, seed=7, step=3)
+    assert sig2 == sig and math.isclose(noi2, 4 * noi, rel_tol=1e-12)
+    _, noi3 = orc.gradient_snr_terms(S, elem_offset=8, sigma=sigma, C=2 * C, seed=7, step=3)
+    assert math.isclose(noi3, 4 * noi, rel_tol=1e-12)
+    assert orc.gradient_snr_terms(S, elem_offset=8, sigma=0.0, C=C, seed=7, step=3) == (sig, 0.0)
+    # expected ratio for a constant signal: a sqrt(n) / (sigma C sqrt(n)) = a / (sigma C), within the chi-square spread
+    assert math.isclose(orc.gradient_snr(sig, noi), 0.25 / (f(sigma) * f(C)), rel_tol=5 / math.sqrt(2 * n))
+    assert orc.gradient_snr(9.0, 4.0) == 1.5 and orc.gradient_snr(1.0, 0.0) == float("inf")
+
+
+def test_gradient_snr_noise_is_what_the_update_adds():
+    """The noise norm is the norm of the vector the update actually adds to the sum: recover it from the
+    update's own gradient, g*|B| - S, for a slice that starts inside a Philox block."""
+    n, off, Bsz = 1001, 13, 64
+    S = syn.normal_f32((n,), 3.0, 21)
+    kw = dict(elem_offset=off, sigma=0.8, C=0.7, seed=99, step=5)
+    _, _, _, g = orc.noise_adamw(np.zeros(n), np.zeros(n), np.zeros(n), S, batch_size=Bsz, lr=1e-3, beta1=0.9, beta2=0.999,
+                                 eps=1e-11, weight_decay=0.0, **kw)
+    added = g * Bsz - S.astype(np.float64)
+    sig, noi = orc.gradient_snr_terms(S, **kw)
+    assert math.isclose(noi, float(np.dot(added, added)), rel_tol=1e-9)
+    assert math.isclose(sig, float(np.linalg.norm(S.astype(np.float64)) ** 2), rel_tol=1e-12)
+    # slices add up (squared norms are additive over a partition of the element range)
+    a = orc.gradient_snr_terms(S[:333], **kw)
+    b = orc.gradient_snr_terms(S[333:], **dict(kw, elem_offset=off + 333))
+    assert math.isclose(a[0] + b[0], sig, rel_tol=1e-12) and math.isclose(a[1] + b[1], noi, rel_tol=1e-12)
+
+
+def test_gradient_snr_grows_with_batch_size():
+    """Section 5.2's observation in its simplest form: with per-example clipped gradients pointing the same
+    way, the signal norm grows like |B| while the noise norm does not depend on |B|."""
+    n = 4096
+    unit = syn.normal_f32((n,), 1.0, 31).astype(np.float64)
+    unit /= np.linalg.norm(unit)
+    snr = []
+    for Bsz in (64, 256, 1024):
+        sig, noi = orc.gradient_snr_terms(Bsz * unit, elem_offset=0, sigma=1.0, C=1.0, seed=1, step=1)
+        snr.append(orc.gradient_snr(sig, noi))
+    assert math.isclose(snr[1] / snr[0], 4.0, rel_tol=1e-9) and math.isclose(snr[2] / snr[1], 4.0, rel_tol=1e-9)
+    assert math.isclose(snr[0], 64 / math.sqrt(n), rel_tol=0.1)
+
+
+# ----------------------------------------------------------------------------------------------
 # stored reference (written by tests/golden/make_oracle_reference.py from the oracle alone): drift guard
 # ----------------------------------------------------------------------------------------------
 def test_oracle_matches_its_stored_reference():
