@@ -151,6 +151,22 @@ dp_status dp_noise_adamw(dp_ctx* ctx, float* params, float* m, float* v, float* 
                          uint64_t batch_size, float lr, float beta1, float beta2, float eps, float weight_decay,
                          int zero_sum);
 
+/* The same update, which also measures the two vectors whose ratio is the gradient signal-to-noise ratio
+ * of Section 5.2 (effect of batch size on DP gradients) while they pass through registers, at no extra
+ * memory traffic:
+ *     snr_sq[0] += sum_e sum[e]^2               (the aggregated clipped gradient, before the division by |B_t|)
+ *     snr_sq[1] += sum_e (sigma*C*z_e)^2        (the noise vector added to it; 0 if sigma == 0)
+ * over the slice's elements.  snr_sq is a DEVICE array of 2 floats that the caller clears (dp_zero_f32)
+ * before the first slice of a step; squared norms add over slices, and the ratio is
+ * sqrt(snr_sq[0] / snr_sq[1]).  Each workgroup reduces its elements in fp32 in a fixed order, the
+ * per-workgroup pairs (library workspace: 8 bytes per 1024 elements; DP_ERR_WORKSPACE if that does not
+ * fit) are added in fp64 in index order: results are reproducible run to run.  Everything else, argument
+ * checks included, is dp_noise_adamw. */
+dp_status dp_noise_adamw_snr(dp_ctx* ctx, float* params, float* m, float* v, float* sum, uint64_t n,
+                             uint64_t elem_offset, float sigma, float C, uint64_t seed, uint64_t step,
+                             uint64_t batch_size, float lr, float beta1, float beta2, float eps, float weight_decay,
+                             int zero_sum, float* snr_sq);
+
 /* ---------------------------------------------------------------------------------------------------
  * Aids
  * ------------------------------------------------------------------------------------------------- */

@@ -319,11 +319,10 @@ dp_status dp_clip_accumulate_embedding(dp_ctx* ctx, const int32_t* ids, const vo
     return dpk_embedding_sums(ctx, ids, G, dtype, B, T, d, V, ctx->cbuf, sum_E);
 }
 
-dp_status dp_noise_adamw(dp_ctx* ctx, float* params, float* m, float* v, float* sum, uint64_t n,
-                         uint64_t elem_offset, float sigma, float C, uint64_t seed, uint64_t step,
-                         uint64_t batch_size, float lr, float beta1, float beta2, float eps, float weight_decay,
-                         int zero_sum) {
-    REQUIRE_CTX(ctx);
+static dp_status noise_adamw_checked(dp_ctx* ctx, float* params, float* m, float* v, float* sum, uint64_t n,
+                                     uint64_t elem_offset, float sigma, float C, uint64_t seed, uint64_t step,
+                                     uint64_t batch_size, float lr, float beta1, float beta2, float eps,
+                                     float weight_decay, int zero_sum, float* sq_out) {
     TRY(check_f32(ctx, "params", params));
     TRY(check_f32(ctx, "m", m));
     TRY(check_f32(ctx, "v", v));
@@ -337,7 +336,27 @@ dp_status dp_noise_adamw(dp_ctx* ctx, float* params, float* m, float* v, float* 
     if (!isfinite(lr) || !isfinite(weight_decay)) FAIL(ctx, DP_ERR_VALUE, "lr and weight_decay must be finite");
     if (elem_offset + n < elem_offset) FAIL(ctx, DP_ERR_SHAPE, "elem_offset + n overflows");
     return dpk_noise_adamw(ctx, params, m, v, sum, n, elem_offset, sigma, C, seed, step, batch_size, lr, beta1, beta2,
-                           eps, weight_decay, zero_sum);
+                           eps, weight_decay, zero_sum, sq_out);
+}
+
+dp_status dp_noise_adamw(dp_ctx* ctx, float* params, float* m, float* v, float* sum, uint64_t n,
+                         uint64_t elem_offset, float sigma, float C, uint64_t seed, uint64_t step,
+                         uint64_t batch_size, float lr, float beta1, float beta2, float eps, float weight_decay,
+                         int zero_sum) {
+    REQUIRE_CTX(ctx);
+    return noise_adamw_checked(ctx, params, m, v, sum, n, elem_offset, sigma, C, seed, step, batch_size, lr, beta1,
+                               beta2, eps, weight_decay, zero_sum, nullptr);
+}
+
+dp_status dp_noise_adamw_snr(dp_ctx* ctx, float* params, float* m, float* v, float* sum, uint64_t n,
+                             uint64_t elem_offset, float sigma, float C, uint64_t seed, uint64_t step,
+                             uint64_t batch_size, float lr, float beta1, float beta2, float eps, float weight_decay,
+                             int zero_sum, float* snr_sq) {
+    REQUIRE_CTX(ctx);
+    if (!snr_sq) FAIL(ctx, DP_ERR_NULL, "snr_sq is NULL");
+    if ((uintptr_t)snr_sq & 3) FAIL(ctx, DP_ERR_ALIGN, "snr_sq must be 4-byte aligned");
+    return noise_adamw_checked(ctx, params, m, v, sum, n, elem_offset, sigma, C, seed, step, batch_size, lr, beta1,
+                               beta2, eps, weight_decay, zero_sum, snr_sq);
 }
 
 dp_status dp_zero_f32(dp_ctx* ctx, float* p, uint64_t n) {

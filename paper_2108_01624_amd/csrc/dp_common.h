@@ -156,7 +156,7 @@ dp_status dpk_philox_u32(dp_ctx*, uint32_t* out, uint64_t n, uint64_t off, uint6
 dp_status dpk_normal_f32(dp_ctx*, float* out, uint64_t n, uint64_t off, uint64_t seed, uint64_t step);
 dp_status dpk_noise_adamw(dp_ctx*, float* params, float* m, float* v, float* sum, uint64_t n, uint64_t off,
                           float sigma, float C, uint64_t seed, uint64_t step, uint64_t batch, float lr, float b1,
-                          float b2, float eps, float wd, int zero_sum);
+                          float b2, float eps, float wd, int zero_sum, float* snr_sq /* device [2], += ; or NULL */);
 
 dp_status dpk_gram_sqnorms(dp_ctx*, const void* A, const void* G, dp_dtype, int B, int T, int d_in, int d_out,
                            int has_bias, float* sqnorms);

@@ -78,56 +78,122 @@ __device__ __forceinline__ void adam_elem(float& th, float& m, float& v, float s
     th = th - a.lr * (mh / (sqrtf(vh) + a.eps) + a.wd * th);
 }
 
+// Gradient signal-to-noise terms (Section 5.2): with SNR the kernels also form the squares of the sum and of
+// the noise sigma*C*z they read / draw anyway, reduce them over the workgroup in a fixed order and store one
+// pair per workgroup at snr_part[2 * (part0 + blockIdx.x)]; snr_finish_kernel adds the pairs in index order.
+template <bool SNR>
+__device__ __forceinline__ void snr_store(float sig, float noi, float* __restrict__ snr_part, uint64_t slot) {
+    if (!SNR) return;
+    __shared__ float red[2][4];
+    sig = dp_wave_sum(sig);
+    noi = dp_wave_sum(noi);
+    if ((threadIdx.x & 63) == 0) {
+        red[0][threadIdx.x >> 6] = sig;
+        red[1][threadIdx.x >> 6] = noi;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        snr_part[2 * slot] = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+        snr_part[2 * slot + 1] = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+    }
+}
+
 // Fast path: elem_offset % 4 == 0 and 16-byte aligned pointers.  Thread i owns local elements 4i .. 4i+3.
-template <bool NOISE, bool ZERO>
+template <bool NOISE, bool ZERO, bool SNR>
 __global__ __launch_bounds__(256) void noise_adamw_vec4(float* __restrict__ params, float* __restrict__ m,
                                                         float* __restrict__ v, float* __restrict__ sum,
                                                         uint64_t nblocks4, uint64_t block0, uint64_t seed,
-                                                        uint64_t step, AdamArgs a) {
+                                                        uint64_t step, AdamArgs a, float* __restrict__ snr_part) {
     const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= nblocks4) return;
-    float4 th = reinterpret_cast<float4*>(params)[i];
-    float4 mm = reinterpret_cast<float4*>(m)[i];
-    float4 vv = reinterpret_cast<float4*>(v)[i];
-    const float4 ss = reinterpret_cast<const float4*>(sum)[i];
-    float z[4] = {0.f, 0.f, 0.f, 0.f};
-    if (NOISE) block_normals(block0 + i, seed, step, z);
-    adam_elem(th.x, mm.x, vv.x, ss.x, z[0], a);
-    adam_elem(th.y, mm.y, vv.y, ss.y, z[1], a);
-    adam_elem(th.z, mm.z, vv.z, ss.z, z[2], a);
-    adam_elem(th.w, mm.w, vv.w, ss.w, z[3], a);
-    reinterpret_cast<float4*>(params)[i] = th;
-    reinterpret_cast<float4*>(m)[i] = mm;
-    reinterpret_cast<float4*>(v)[i] = vv;
-    if (ZERO) reinterpret_cast<float4*>(sum)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    float sig = 0.f, noi = 0.f;
+    if (i < nblocks4) {
+        float4 th = reinterpret_cast<float4*>(params)[i];
+        float4 mm = reinterpret_cast<float4*>(m)[i];
+        float4 vv = reinterpret_cast<float4*>(v)[i];
+        const float4 ss = reinterpret_cast<const float4*>(sum)[i];
+        float z[4] = {0.f, 0.f, 0.f, 0.f};
+        if (NOISE) block_normals(block0 + i, seed, step, z);
+        adam_elem(th.x, mm.x, vv.x, ss.x, z[0], a);
+        adam_elem(th.y, mm.y, vv.y, ss.y, z[1], a);
+        adam_elem(th.z, mm.z, vv.z, ss.z, z[2], a);
+        adam_elem(th.w, mm.w, vv.w, ss.w, z[3], a);
+        reinterpret_cast<float4*>(params)[i] = th;
+        reinterpret_cast<float4*>(m)[i] = mm;
+        reinterpret_cast<float4*>(v)[i] = vv;
+        if (ZERO) reinterpret_cast<float4*>(sum)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (SNR) {
+            sig = (ss.x * ss.x + ss.y * ss.y) + (ss.z * ss.z + ss.w * ss.w);
+            const float n0 = a.noise_scale * z[0], n1 = a.noise_scale * z[1], n2 = a.noise_scale * z[2],
+                        n3 = a.noise_scale * z[3];
+            noi = (n0 * n0 + n1 * n1) + (n2 * n2 + n3 * n3);
+        }
+    }
+    snr_store<SNR>(sig, noi, snr_part, blockIdx.x);
 }
 
 // General path: any offset / alignment, and the ragged tail of the fast path.  Thread i owns the Philox
 // block first_block + i and touches only those of its four elements that fall inside [e_lo, e_hi).
 // `base_elem` is the global index of params[0].
-template <bool NOISE, bool ZERO>
+template <bool NOISE, bool ZERO, bool SNR>
 __global__ __launch_bounds__(256) void noise_adamw_scalar(float* __restrict__ params, float* __restrict__ m,
                                                           float* __restrict__ v, float* __restrict__ sum,
                                                           uint64_t base_elem, uint64_t e_lo, uint64_t e_hi,
                                                           uint64_t first_block, uint64_t nblocks, uint64_t seed,
-                                                          uint64_t step, AdamArgs a) {
+                                                          uint64_t step, AdamArgs a, float* __restrict__ snr_part,
+                                                          uint64_t part0) {
     const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= nblocks) return;
-    const uint64_t blk = first_block + i;
-    float z[4] = {0.f, 0.f, 0.f, 0.f};
-    if (NOISE) block_normals(blk, seed, step, z);
+    float sig = 0.f, noi = 0.f;
+    if (i < nblocks) {
+        const uint64_t blk = first_block + i;
+        float z[4] = {0.f, 0.f, 0.f, 0.f};
+        if (NOISE) block_normals(blk, seed, step, z);
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const uint64_t e = blk * 4 + k;
-        if (e >= e_lo && e < e_hi) {
-            const uint64_t j = e - base_elem;
-            float th = params[j], mm = m[j], vv = v[j];
-            adam_elem(th, mm, vv, sum[j], z[k], a);
-            params[j] = th;
-            m[j] = mm;
-            v[j] = vv;
-            if (ZERO) sum[j] = 0.f;
+        for (int k = 0; k < 4; ++k) {
+            const uint64_t e = blk * 4 + k;
+            if (e >= e_lo && e < e_hi) {
+                const uint64_t j = e - base_elem;
+                float th = params[j], mm = m[j], vv = v[j];
+                const float sj = sum[j];
+                adam_elem(th, mm, vv, sj, z[k], a);
+                params[j] = th;
+                m[j] = mm;
+                v[j] = vv;
+                if (ZERO) sum[j] = 0.f;
+                if (SNR) {
+                    const float nz = a.noise_scale * z[k];
+                    sig += sj * sj;
+                    noi += nz * nz;
+                }
+            }
         }
+    }
+    snr_store<SNR>(sig, noi, snr_part, part0 + blockIdx.x);
+}
+
+// sq_out[0] += sum of the signal partials, sq_out[1] += sum of the noise partials, each added in fp64 in a fixed
+// order (thread t takes pairs t, t + 1024, ...; then a fixed tree over the 1024 threads).  One workgroup.
+__global__ __launch_bounds__(1024) void snr_finish_kernel(const float* __restrict__ snr_part, uint64_t npairs,
+                                                          float* __restrict__ sq_out) {
+    __shared__ double red[2][1024];
+    double sig = 0.0, noi = 0.0;
+    for (uint64_t k = threadIdx.x; k < npairs; k += 1024) {
+        const float2 pr = reinterpret_cast<const float2*>(snr_part)[k];
+        sig += (double)pr.x;
+        noi += (double)pr.y;
+    }
+    red[0][threadIdx.x] = sig;
+    red[1][threadIdx.x] = noi;
+    __syncthreads();
+    for (int w = 512; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) {
+            red[0][threadIdx.x] += red[0][threadIdx.x + w];
+            red[1][threadIdx.x] += red[1][threadIdx.x + w];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        sq_out[0] = (float)((double)sq_out[0] + red[0][0]);
+        sq_out[1] = (float)((double)sq_out[1] + red[1][0]);
     }
 }
 
@@ -182,44 +248,63 @@ __global__ __launch_bounds__(256) void clip_factors_kernel(const float* __restri
     if (i < B) c[i] = dp_clip_factor(sqnorms[i], C);
 }
 
-template <bool NOISE, bool ZERO>
+template <bool NOISE, bool ZERO, bool SNR>
 dp_status launch_adamw(dp_ctx* ctx, float* params, float* m, float* v, float* sum, uint64_t n, uint64_t off,
-                       uint64_t seed, uint64_t step, const AdamArgs& a) {
+                       uint64_t seed, uint64_t step, const AdamArgs& a, float* sq_out) {
     const bool aligned = (off % 4 == 0) && (((uintptr_t)params | (uintptr_t)m | (uintptr_t)v | (uintptr_t)sum) & 15) == 0;
-    uint64_t done = 0;
-    if (aligned && n >= 4) {
-        const uint64_t nb4 = n / 4;
-        const uint64_t grid = (nb4 + 255) / 256;
-        if (grid > 0x7FFFFFFFull) {
-            DP_SET_ERR(ctx, "dp_noise_adamw: slice too large for one launch");
-            return DP_ERR_SHAPE;
-        }
-        hipLaunchKernelGGL((noise_adamw_vec4<NOISE, ZERO>), dim3((unsigned)grid), dim3(256), 0, ctx->stream, params, m,
-                           v, sum, nb4, off / 4, seed, step, a);
-        DP_LAUNCH_CHECK(ctx, "noise_adamw_vec4");
-        done = nb4 * 4;
-    }
+    const uint64_t nb4 = (aligned && n >= 4) ? n / 4 : 0;
+    const uint64_t grid4 = (nb4 + 255) / 256;
+    const uint64_t done = nb4 * 4;
+    uint64_t first = 0, nblocks = 0, grid1 = 0;
     if (done < n) {
-        const uint64_t e_lo = off + done, e_hi = off + n;
-        const uint64_t first = e_lo / 4, last = (e_hi - 1) / 4;
-        const uint64_t nblocks = last - first + 1;
-        const uint64_t grid = (nblocks + 255) / 256;
-        if (grid > 0x7FFFFFFFull) {
-            DP_SET_ERR(ctx, "dp_noise_adamw: slice too large for one launch");
-            return DP_ERR_SHAPE;
+        first = (off + done) / 4;
+        nblocks = (off + n - 1) / 4 - first + 1;
+        grid1 = (nblocks + 255) / 256;
+    }
+    if (grid4 > 0x7FFFFFFFull || grid1 > 0x7FFFFFFFull) {
+        DP_SET_ERR(ctx, "dp_noise_adamw: slice too large for one launch");
+        return DP_ERR_SHAPE;
+    }
+    float* part = nullptr;
+    if (SNR) {
+        dp_ws_alloc ws(ctx);
+        part = ws.get<float>(2 * (grid4 + grid1));
+        if (!part) {
+            DP_SET_ERR(ctx, "dp_noise_adamw_snr: workspace too small for the per-workgroup partial norms");
+            return DP_ERR_WORKSPACE;
         }
-        hipLaunchKernelGGL((noise_adamw_scalar<NOISE, ZERO>), dim3((unsigned)grid), dim3(256), 0, ctx->stream, params,
-                           m, v, sum, off, e_lo, e_hi, first, nblocks, seed, step, a);
+    }
+    if (grid4) {
+        hipLaunchKernelGGL((noise_adamw_vec4<NOISE, ZERO, SNR>), dim3((unsigned)grid4), dim3(256), 0, ctx->stream,
+                           params, m, v, sum, nb4, off / 4, seed, step, a, part);
+        DP_LAUNCH_CHECK(ctx, "noise_adamw_vec4");
+    }
+    if (grid1) {
+        hipLaunchKernelGGL((noise_adamw_scalar<NOISE, ZERO, SNR>), dim3((unsigned)grid1), dim3(256), 0, ctx->stream,
+                           params, m, v, sum, off, off + done, off + n, first, nblocks, seed, step, a, part, grid4);
         DP_LAUNCH_CHECK(ctx, "noise_adamw_scalar");
     }
+    if (SNR) {
+        hipLaunchKernelGGL(snr_finish_kernel, dim3(1), dim3(1024), 0, ctx->stream, part, grid4 + grid1, sq_out);
+        DP_LAUNCH_CHECK(ctx, "snr_finish_kernel");
+    }
     return DP_OK;
+}
+
+template <bool SNR>
+dp_status dispatch_adamw(dp_ctx* ctx, float* params, float* m, float* v, float* sum, uint64_t n, uint64_t off,
+                         uint64_t seed, uint64_t step, const AdamArgs& a, bool noise, int zero_sum, float* sq_out) {
+    if (noise && zero_sum) return launch_adamw<true, true, SNR>(ctx, params, m, v, sum, n, off, seed, step, a, sq_out);
+    if (noise) return launch_adamw<true, false, SNR>(ctx, params, m, v, sum, n, off, seed, step, a, sq_out);
+    if (zero_sum) return launch_adamw<false, true, SNR>(ctx, params, m, v, sum, n, off, seed, step, a, sq_out);
+    return launch_adamw<false, false, SNR>(ctx, params, m, v, sum, n, off, seed, step, a, sq_out);
 }
 
 }  // namespace
 
 dp_status dpk_noise_adamw(dp_ctx* ctx, float* params, float* m, float* v, float* sum, uint64_t n, uint64_t off,
                           float sigma, float C, uint64_t seed, uint64_t step, uint64_t batch, float lr, float b1,
-                          float b2, float eps, float wd, int zero_sum) {
+                          float b2, float eps, float wd, int zero_sum, float* sq_out) {
     if (n == 0) return DP_OK;
     AdamArgs a;
     a.noise_scale = sigma * C;
@@ -233,10 +318,8 @@ dp_status dpk_noise_adamw(dp_ctx* ctx, float* params, float* m, float* v, float*
     a.wd = wd;
     const bool noise = sigma != 0.f;
     dp_prof_scope prof(ctx, DP_PROF_ADAMW, (zero_sum ? 32.0 : 28.0) * (double)n);
-    if (noise && zero_sum) return launch_adamw<true, true>(ctx, params, m, v, sum, n, off, seed, step, a);
-    if (noise) return launch_adamw<true, false>(ctx, params, m, v, sum, n, off, seed, step, a);
-    if (zero_sum) return launch_adamw<false, true>(ctx, params, m, v, sum, n, off, seed, step, a);
-    return launch_adamw<false, false>(ctx, params, m, v, sum, n, off, seed, step, a);
+    if (sq_out) return dispatch_adamw<true>(ctx, params, m, v, sum, n, off, seed, step, a, noise, zero_sum, sq_out);
+    return dispatch_adamw<false>(ctx, params, m, v, sum, n, off, seed, step, a, noise, zero_sum, nullptr);
 }
 
 template <int MODE>

@@ -82,7 +82,14 @@ class StepRunner:
                     [self.view(self.S, k, 0) for k in sel],
                     [self.view(self.S, k, 1) if layers[k]["has_bias"] else None for k in sel])
 
-    def update(self, *, sigma, C, seed, step, batch_size, lr, beta1, beta2, eps=1e-11, weight_decay, zero_sum=True):
-        self.ctx.noise_adamw(self.theta, self.m, self.v, self.S, sigma=sigma, C=C, seed=seed, step=step,
-                             batch_size=batch_size, lr=lr, beta1=beta1, beta2=beta2, eps=eps,
-                             weight_decay=weight_decay, zero_sum=zero_sum)
+    def update(self, *, sigma, C, seed, step, batch_size, lr, beta1, beta2, eps=1e-11, weight_decay, zero_sum=True,
+               snr_sq=None):
+        """Noise + Adam over the whole flat parameter space.  With `snr_sq` (a device tensor of two floats) the
+        squared norms of the aggregated gradient and of the noise vector are written there (gradient-SNR terms)."""
+        kw = dict(sigma=sigma, C=C, seed=seed, step=step, batch_size=batch_size, lr=lr, beta1=beta1, beta2=beta2, eps=eps,
+                  weight_decay=weight_decay, zero_sum=zero_sum)
+        if snr_sq is None:
+            self.ctx.noise_adamw(self.theta, self.m, self.v, self.S, **kw)
+        else:
+            self.ctx.zero_f32(snr_sq, 2)
+            self.ctx.noise_adamw_snr(self.theta, self.m, self.v, self.S, snr_sq, **kw)

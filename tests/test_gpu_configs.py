@@ -8,7 +8,8 @@ Coverage contract (what the oracle computed is what is claimed):
       stand-in norms fed to both sides, (c) every tensor for a leading subset of B' examples (GPU re-run at B');
       embedding rows written are checked exactly at full size.
   C4  update over all ~334M parameters against the oracle on sampled slices (Philox words bit-exact on the same
-      slices); accumulation over micro-batches on a one-block manifest against the oracle; a B = 1024 dense layer
+      slices), gradient-SNR terms of all parameters against a chi-square bound / a library sum and, on the one-block
+      manifest, against the oracle over every parameter; accumulation over micro-batches on a one-block manifest against the oracle; a B = 1024 dense layer
       with sampled entries; linearity of the accumulation on the GPU (an invariant, not oracle parity).
 """
 import numpy as np
@@ -282,7 +283,15 @@ def test_c4_update_all_parameters_sampled_slices():
     kw = dict(sigma=cfg["sigma"], C=cfg["C"], seed=cfg["noise_seed"], step=1, batch_size=Bsz, lr=cfg["lr"], beta1=cfg["beta1"],
               beta2=cfg["beta2"], eps=1e-11, weight_decay=cfg["weight_decay"])
     with pkg.Context() as ctx:
-        ctx.noise_adamw(th, m, v, S, zero_sum=True, **kw)
+        # the variant that also returns the gradient-SNR terms (same update, bit for bit: see the kernel tests)
+        S_sq = float((S.double() ** 2).sum().item())
+        snr = torch.zeros(2, dtype=torch.float32, device=DEV)
+        ctx.noise_adamw_snr(th, m, v, S, snr, zero_sum=True, **kw)
+        ctx.sync()
+        sig, noi = [float(x) for x in host(snr)]
+        assert abs(sig - S_sq) <= 1e-5 * S_sq                      # a library reduction, not the oracle (size)
+        sc2 = (float(np.float32(cfg["sigma"])) * float(np.float32(cfg["C"]))) ** 2
+        assert abs(noi / sc2 - P) < 6 * np.sqrt(2.0 * P) + 1e-5 * P  # chi-square with P degrees of freedom
         w = torch.zeros(L, dtype=torch.int32, device=DEV)
         for o, (th0, S0) in zip(offs, before):
             ctx.philox_u32(w, o, cfg["noise_seed"], 1)
@@ -323,8 +332,16 @@ def test_c4_accumulation_over_micro_batches_one_block():
         S_host = host(run.S).copy()
         kw = dict(sigma=cfg["sigma"], C=cfg["C"], seed=cfg["noise_seed"], step=1, batch_size=Bm * K, lr=cfg["lr"],
                   beta1=cfg["beta1"], beta2=cfg["beta2"], eps=1e-11, weight_decay=cfg["weight_decay"])
-        run.update(**kw)
+        snr = torch.zeros(2, dtype=torch.float32, device=DEV)
+        run.update(snr_sq=snr, **kw)
         ctx.sync()
+        # gradient-SNR terms over every parameter of the manifest, oracle in chunks
+        sig = noi = 0.0
+        for o in range(0, run.P, 1 << 22):
+            a, b = orc.gradient_snr_terms(S_host[o:o + (1 << 22)], elem_offset=o, sigma=cfg["sigma"], C=cfg["C"],
+                                          seed=cfg["noise_seed"], step=1)
+            sig, noi = sig + a, noi + b
+        np.testing.assert_allclose(host(snr), [sig, noi], rtol=1e-5)
         L = 1 << 16
         for o in (0, run.P - L, 31_000_000):
             th_ref, m_ref, _, _ = orc.noise_adamw(th0[o:o + L], np.zeros(L), np.zeros(L), S_host[o:o + L], elem_offset=o, **kw)

@@ -157,6 +157,55 @@ def test_adamw_untouched_row_is_pure_decay(dp):
 
 
 # ------------------------------------------------------------------------------------------------
+# gradient signal-to-noise terms fused into the update (Section 5.2)
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n,off,sigma,zero_sum", [(64 * 64, 0, 1.0, False), (1, 0, 0.6, False), (4099, 0, 0.6, True),
+                                                   (1000, 5, 0.6, False), (7, 2, 0.0, False), (300007, 8, 0.6, True),
+                                                   (1 << 20, 0, 0.6, False)])
+def test_noise_adamw_snr_matches_oracle_and_plain_update(dp, n, off, sigma, zero_sum):
+    th0 = syn.normal_f32((n,), 0.02, 80)
+    S = syn.normal_f32((n,), 3.0, 81)
+    kw = dict(elem_offset=off, sigma=sigma, C=0.7, seed=1234, step=2, batch_size=64, lr=1e-3, beta1=0.9, beta2=0.999,
+              eps=1e-11, weight_decay=0.5)
+    z = lambda: torch.zeros(n, dtype=torch.float32, device=DEV)
+    th_a, m_a, v_a, S_a = f32_dev(th0), z(), z(), f32_dev(S)
+    th_b, m_b, v_b, S_b = f32_dev(th0), z(), z(), f32_dev(S)
+    snr = torch.full((2,), 7.0, dtype=torch.float32, device=DEV)     # "+=": a stale value must survive as an offset
+    dp.noise_adamw(th_a, m_a, v_a, S_a, zero_sum=zero_sum, **kw)
+    dp.noise_adamw_snr(th_b, m_b, v_b, S_b, snr, zero_sum=zero_sum, **kw)
+    dp.sync()
+    for a, b in ((th_a, th_b), (m_a, m_b), (v_a, v_b), (S_a, S_b)):   # the update itself is bit-identical
+        np.testing.assert_array_equal(host(a), host(b))
+    sig, noi = orc.gradient_snr_terms(S, elem_offset=off, sigma=sigma, C=0.7, seed=1234, step=2)
+    got = host(snr).astype(np.float64) - 7.0
+    assert abs(got[0] - sig) <= 1e-5 * sig + 1e-5, (got[0], sig)
+    assert abs(got[1] - noi) <= 1e-5 * noi + 1e-5, (got[1], noi)
+    if sigma == 0.0:
+        assert got[1] == 0.0
+
+
+def test_noise_adamw_snr_slices_add_and_repeat_exactly(dp):
+    n, off, cut = 50021, 12, 20001
+    S = syn.normal_f32((n,), 2.0, 82)
+    kw = dict(sigma=0.6, C=1.0, seed=5, step=1, batch_size=32, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-11, weight_decay=0.0)
+    z = lambda k: torch.zeros(k, dtype=torch.float32, device=DEV)
+    out = []
+    for rep in range(2):
+        whole, parts = z(2), z(2)
+        dp.noise_adamw_snr(z(n), z(n), z(n), f32_dev(S), whole, elem_offset=off, **kw)
+        S_d = f32_dev(S)
+        dp.noise_adamw_snr(z(cut), z(cut), z(cut), S_d[:cut], parts, n=cut, elem_offset=off, **kw)
+        dp.noise_adamw_snr(z(n - cut), z(n - cut), z(n - cut), S_d[cut:], parts, n=n - cut, elem_offset=off + cut, **kw)
+        dp.sync()
+        out.append((host(whole), host(parts)))
+    np.testing.assert_allclose(out[0][0], out[0][1], rtol=1e-5)
+    np.testing.assert_array_equal(out[0][0], out[1][0])   # fixed summation order: reproducible bit for bit
+    np.testing.assert_array_equal(out[0][1], out[1][1])
+    sig, noi = orc.gradient_snr_terms(S, elem_offset=off, sigma=0.6, C=1.0, seed=5, step=1)
+    np.testing.assert_allclose(out[0][0], [sig, noi], rtol=1e-5)
+
+
+# ------------------------------------------------------------------------------------------------
 # dense layers: norms
 # ------------------------------------------------------------------------------------------------
 DENSE_SHAPES = [
