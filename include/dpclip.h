@@ -180,6 +180,24 @@ dp_status dp_choose_path(int T, int d_in, int d_out, dp_dtype dtype, dp_path* ou
 
 
 /* ---------------------------------------------------------------------------------------------------
+ * Schedules: the per-step scalars q_t (batch size) and eta_t (learning rate) of Algorithm 1's input list.
+ * Host-only, pure; `out` is a HOST pointer; `step` counts from 1; DP_ERR_VALUE on inconsistent arguments.
+ *
+ * dp_batch_size_schedule: the increasing batch-size schedule of the batch-size study (Section 5.2.1): the
+ * batch grows from b_start to b_end over ramp_steps steps in n_increments equal jumps of
+ * floor((b_end - b_start) / n_increments), the k-th one once k/n_increments of the ramp's steps are complete,
+ * the last one landing exactly on b_end (the paper's run: 262144 -> 1048576 over 7500 steps in 4 jumps of
+ * 196608).  The caller turns q_t into a number of micro-batches and passes q_t as batch_size to the update.
+ *
+ * dp_lr_schedule: linear warm-up to `peak` at step == warmup_steps, then quadratic decay
+ * peak * ((total_steps - step) / (total_steps - warmup_steps))^2, zero from total_steps on (the schedule named in
+ * the hyper-parameter tuning section: 7500 warm-up steps of 20000; the exact form of the decay is not given there).
+ * ------------------------------------------------------------------------------------------------- */
+dp_status dp_batch_size_schedule(uint64_t step, uint64_t b_start, uint64_t b_end, uint64_t ramp_steps,
+                                 uint32_t n_increments, uint64_t* out);
+dp_status dp_lr_schedule(uint64_t step, double peak, uint64_t warmup_steps, uint64_t total_steps, double* out);
+
+/* ---------------------------------------------------------------------------------------------------
  * Kernel timing (for benchmarks): while enabled, the library brackets each launch of its three main
  * kernels with HIP events on the context's stream.  dp_profile_read synchronises the stream and returns,
  * for one kernel kind, the summed launch duration in milliseconds, the launch count and the summed

@@ -394,3 +394,39 @@ def gradient_snr_terms(S, *, elem_offset: int, sigma: float, C: float, seed: int
 def gradient_snr(signal_sq: float, noise_sq: float) -> float:
     """||S||_2 / ||sigma C z||_2 from the two squared norms (summed over slices by the caller)."""
     return float(np.sqrt(signal_sq / noise_sq)) if noise_sq > 0 else float("inf")
+
+
+# --------------------------------------------------------------------------------------
+# schedules (host-side scalars of Algorithm 1: the batch sizes q_t and the learning rates eta_t)
+# --------------------------------------------------------------------------------------
+
+
+def batch_size_schedule(step: int, b_start: int, b_end: int, ramp_steps: int, n_increments: int) -> int:
+    """Increasing batch-size schedule of the batch-size study: the batch grows from b_start to b_end over
+    ramp_steps steps, in n_increments equal jumps, one after every ramp_steps/n_increments completed steps
+    (the paper: 262,144 -> 1,048,576 over 7,500 steps, a jump of 196,608 after each quarter, 1,048,576 from
+    the end of the ramp on).  `step` counts from 1 as in Algorithm 1; step t has t - 1 completed steps
+    before it.  Reading of what the text leaves open: jumps are equal, (b_end - b_start) / n_increments
+    rounded down, with the last jump landing exactly on b_end."""
+    if step < 1 or n_increments < 1 or ramp_steps < n_increments or b_end < b_start:
+        raise ValueError("bad schedule arguments")
+    done = step - 1
+    k = min(n_increments, (done * n_increments) // ramp_steps)
+    if k == n_increments:
+        return b_end
+    return b_start + k * ((b_end - b_start) // n_increments)
+
+
+def lr_schedule(step: int, peak: float, warmup_steps: int, total_steps: int) -> float:
+    """Linear warm-up to `peak` over warmup_steps steps, then quadratic decay to zero at total_steps
+    (hyper-parameter tuning section: 7,500 warm-up steps of 20,000).  Reading of the unspecified form of the
+    decay: eta_t = peak * ((total - t) / (total - warmup))^2 for t > warmup; eta_t = peak * t / warmup up to
+    and including t = warmup; 0 beyond total_steps."""
+    if step < 1 or warmup_steps < 0 or total_steps < max(1, warmup_steps):
+        raise ValueError("bad schedule arguments")
+    if step <= warmup_steps:
+        return peak * step / warmup_steps
+    if step >= total_steps:
+        return 0.0
+    frac = (total_steps - step) / (total_steps - warmup_steps)
+    return peak * frac * frac

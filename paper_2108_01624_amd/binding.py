@@ -45,6 +45,8 @@ SIGNATURES = {
     "dp_philox_u32": [c_void_p, c_void_p, c_uint64, c_uint64, c_uint64, c_uint64],
     "dp_normal_f32": [c_void_p, c_void_p, c_uint64, c_uint64, c_uint64, c_uint64],
     "dp_choose_path": [c_int, c_int, c_int, c_int, ctypes.POINTER(c_int)],
+    "dp_batch_size_schedule": [c_uint64, c_uint64, c_uint64, c_uint64, ctypes.c_uint32, ctypes.POINTER(c_uint64)],
+    "dp_lr_schedule": [c_uint64, ctypes.c_double, c_uint64, c_uint64, ctypes.POINTER(ctypes.c_double)],
     "dp_profile_enable": [c_void_p, c_int],
     "dp_profile_read": [c_void_p, c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_uint64),
                         ctypes.POINTER(ctypes.c_double)],
@@ -242,6 +244,22 @@ def dp_philox_u32(ctx, out, elem_offset, seed, step, n=None):
 def dp_normal_f32(ctx, out, elem_offset, seed, step, n=None):
     _check(ctx, load_library().dp_normal_f32(ctx, _f32(out), out.numel() if n is None else n, elem_offset, seed, step),
            "dp_normal_f32")
+
+
+def dp_batch_size_schedule(step, b_start, b_end, ramp_steps, n_increments) -> int:
+    out = c_uint64()
+    st = load_library().dp_batch_size_schedule(step, b_start, b_end, ramp_steps, n_increments, ctypes.byref(out))
+    if st != DP_OK:
+        raise DpError(st, "dp_batch_size_schedule")
+    return out.value
+
+
+def dp_lr_schedule(step, peak, warmup_steps, total_steps) -> float:
+    out = ctypes.c_double()
+    st = load_library().dp_lr_schedule(step, peak, warmup_steps, total_steps, ctypes.byref(out))
+    if st != DP_OK:
+        raise DpError(st, "dp_lr_schedule")
+    return out.value
 
 
 def dp_choose_path(T, d_in, d_out, dtype=DP_BF16) -> int:

@@ -192,6 +192,31 @@ dp_status dp_choose_path(int T, int d_in, int d_out, dp_dtype dtype, dp_path* ou
     return DP_OK;
 }
 
+dp_status dp_batch_size_schedule(uint64_t step, uint64_t b_start, uint64_t b_end, uint64_t ramp_steps,
+                                 uint32_t n_increments, uint64_t* out) {
+    if (!out) return DP_ERR_NULL;
+    if (step == 0 || n_increments == 0 || ramp_steps < n_increments || b_end < b_start) return DP_ERR_VALUE;
+    // k jumps have happened once k/n_increments of the ramp's steps are complete (step t has t - 1 behind it)
+    const unsigned __int128 done = (unsigned __int128)(step - 1) * n_increments;
+    const uint64_t k = (uint64_t)(done / ramp_steps);
+    *out = k >= n_increments ? b_end : b_start + k * ((b_end - b_start) / n_increments);
+    return DP_OK;
+}
+
+dp_status dp_lr_schedule(uint64_t step, double peak, uint64_t warmup_steps, uint64_t total_steps, double* out) {
+    if (!out) return DP_ERR_NULL;
+    if (step == 0 || total_steps == 0 || total_steps < warmup_steps || !isfinite(peak)) return DP_ERR_VALUE;
+    if (step <= warmup_steps) {
+        *out = peak * (double)step / (double)warmup_steps;
+    } else if (step >= total_steps) {
+        *out = 0.0;
+    } else {
+        const double frac = (double)(total_steps - step) / (double)(total_steps - warmup_steps);
+        *out = peak * frac * frac;
+    }
+    return DP_OK;
+}
+
 dp_status dp_sqnorms_dense(dp_ctx* ctx, const void* A, const void* G, dp_dtype dtype, int B, int T, int d_in,
                            int d_out, int has_bias, dp_path path, float* sqnorms) {
     REQUIRE_CTX(ctx);

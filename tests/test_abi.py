@@ -79,3 +79,25 @@ def test_manifest_counts():
     assert syn.manifest_param_count(syn.CONFIGS["C1"]["manifest"]()) == 4096
     assert syn.manifest_param_count(syn.CONFIGS["C2"]["manifest"]()) == 85_054_464
     assert syn.manifest_param_count(syn.CONFIGS["C3"]["manifest"]()) == 334_088_192
+
+
+def test_schedules_match_the_oracle(lib):
+    """Host-only entry points (no GPU work): every step of the paper's run, and ragged small cases."""
+    import paper_2108_01624_amd as pkg
+    from oracle import dp_oracle as orc
+
+    for t in list(range(1, 7600)) + [9999, 19999, 20000, 20001, 1 << 40]:
+        assert pkg.dp_batch_size_schedule(t, 262144, 1048576, 7500, 4) == orc.batch_size_schedule(t, 262144, 1048576, 7500, 4)
+    for t in list(range(1, 20003, 7)) + [7499, 7500, 7501, 19999, 20000]:
+        got, ref = pkg.dp_lr_schedule(t, 6.0902e-4, 7500, 20000), orc.lr_schedule(t, 6.0902e-4, 7500, 20000)
+        assert abs(got - ref) <= 1e-15 * abs(ref)
+    for args in ((10, 20, 7, 3), (64, 64, 4, 2), (1, 1000, 13, 13), (5, 6, 100, 7)):
+        for t in range(1, 2 * args[2] + 3):
+            assert pkg.dp_batch_size_schedule(t, *args) == orc.batch_size_schedule(t, *args)
+    for bad in ((0, 1, 2, 4, 2), (1, 1, 2, 4, 0), (1, 3, 2, 4, 2), (1, 1, 2, 1, 2)):
+        with pytest.raises(pkg.DpError):
+            pkg.dp_batch_size_schedule(*bad)
+    with pytest.raises(pkg.DpError):
+        pkg.dp_lr_schedule(0, 1e-3, 10, 20)
+    with pytest.raises(pkg.DpError):
+        pkg.dp_lr_schedule(1, 1e-3, 30, 20)

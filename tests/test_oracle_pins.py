@@ -1,6 +1,7 @@
 """Pins of the CPU oracle to things other than itself: brute-force autograd, closed forms,
 invariants, library routines (flat GEMM, bincount, torch.optim.AdamW), statistics of the noise."""
 import math
+import os
 
 import numpy as np
 import pytest
@@ -564,6 +565,63 @@ def test_gradient_snr_grows_with_batch_size():
         snr.append(orc.gradient_snr(sig, noi))
     assert math.isclose(snr[1] / snr[0], 4.0, rel_tol=1e-9) and math.isclose(snr[2] / snr[1], 4.0, rel_tol=1e-9)
     assert math.isclose(snr[0], 64 / math.sqrt(n), rel_tol=0.1)
+
+
+# ----------------------------------------------------------------------------------------------
+# schedules (batch sizes q_t of the batch-size study; learning rates eta_t of the tuning section)
+# ----------------------------------------------------------------------------------------------
+def _schedule_numbers():
+    out = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "batch_size_schedule.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                k, val = line.split()
+                out[k] = int(val)
+    return out
+
+
+def test_batch_size_schedule_reproduces_the_papers_numbers():
+    n = _schedule_numbers()
+    q = lambda t: orc.batch_size_schedule(t, n["b_start"], n["b_end"], n["ramp_steps"], n["parts"])
+    assert q(1) == 262144 and q(n["ramp_steps"] + 1) == 1048576 and q(20000) == 1048576
+    quarter = n["ramp_steps"] // n["parts"]
+    sizes = [q(k * quarter + 1) for k in range(n["parts"] + 1)]
+    jumps = np.diff(sizes)
+    assert (jumps == jumps[0]).all() and abs(int(jumps[0]) - n["jump_approx"]) < 1000      # "~196k" each quarter
+    assert sizes == [262144, 458752, 655360, 851968, 1048576]                                # 2^18 + k * 3 * 2^16
+    # constant within a quarter; the jump comes after the quarter's last step, never earlier
+    assert q(quarter) == sizes[0] and q(quarter + 1) == sizes[1] and q(n["ramp_steps"]) == sizes[3]
+    all_q = np.array([q(t) for t in range(1, n["ramp_steps"] + 2)])
+    assert (np.diff(all_q) >= 0).all() and len(set(all_q.tolist())) == 5
+    # examples visited over the ramp against a fixed 1M batch: the mean of the four plateaus
+    assert all_q[:-1].sum() == quarter * sum(sizes[:4])
+
+
+def test_batch_size_schedule_general_and_errors():
+    # ragged: 10 -> 20 in 3 jumps over 7 steps; jumps of 3 after floor-boundaries 7/3, 14/3; ends exactly at 20
+    got = [orc.batch_size_schedule(t, 10, 20, 7, 3) for t in range(1, 10)]
+    assert got == [10, 10, 10, 13, 13, 16, 16, 20, 20]
+    assert orc.batch_size_schedule(5, 64, 64, 4, 2) == 64
+    for bad in ((0, 1, 2, 4, 2), (1, 1, 2, 4, 0), (1, 3, 2, 4, 2), (1, 1, 2, 1, 2)):
+        with pytest.raises(ValueError):
+            orc.batch_size_schedule(*bad)
+
+
+def test_lr_schedule_shape():
+    n = _schedule_numbers()
+    W, Ttot, peak = n["warmup_steps"], n["total_steps"], HP["lr"]
+    lr = np.array([orc.lr_schedule(t, peak, W, Ttot) for t in range(1, Ttot + 2)])
+    assert lr[W - 1] == peak and lr.argmax() == W - 1            # the peak is reached exactly at the end of warm-up
+    np.testing.assert_allclose(np.diff(lr[:W]), peak / W, rtol=1e-9)             # linear: constant first difference
+    d2 = np.diff(lr[W - 1:Ttot], 2)
+    np.testing.assert_allclose(d2, 2 * peak / (Ttot - W) ** 2, rtol=1e-6)        # quadratic: constant second difference
+    assert lr[Ttot - 1] == 0.0 and lr[Ttot] == 0.0 and (lr >= 0).all()
+    assert math.isclose(lr[(W + Ttot) // 2 - 1], peak / 4, rel_tol=1e-12)        # half-way down the decay: a quarter
+    assert orc.lr_schedule(1, peak, 0, 10) == peak * (9 / 10) ** 2               # no warm-up: decay from step 0
+    with pytest.raises(ValueError):
+        orc.lr_schedule(0, peak, W, Ttot)
+    with pytest.raises(ValueError):
+        orc.lr_schedule(1, peak, 10, 5)
 
 
 # ----------------------------------------------------------------------------------------------
