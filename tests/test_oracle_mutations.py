@@ -100,6 +100,14 @@ MUTANTS = [
      "test_gradient_snr_closed_forms"),
     ("snr_inverted", [("return float(np.sqrt(signal_sq / noise_sq)) if noise_sq > 0", "return float(np.sqrt(noise_sq / signal_sq)) if noise_sq > 0", None)],
      "test_gradient_snr_closed_forms"),
+    ("batch_schedule_jump_one_step_early", [("    done = step - 1\n", "    done = step\n", None)], "test_batch_size_schedule_reproduces_the_papers_numbers"),
+    ("batch_schedule_linear_ramp", [("k = min(n_increments, (done * n_increments) // ramp_steps)", "k = min(n_increments, (done * n_increments) / ramp_steps)", None)],
+     "test_batch_size_schedule_reproduces_the_papers_numbers"),
+    ("batch_schedule_never_reaches_end", [("    if k == n_increments:\n        return b_end\n", "", None)], "test_batch_size_schedule_general_and_errors"),
+    ("lr_decay_linear", [("return peak * frac * frac", "return peak * frac", None)], "test_lr_schedule_shape"),
+    ("lr_warmup_lags_one_step", [("return peak * step / warmup_steps", "return peak * (step - 1) / warmup_steps", None)], "test_lr_schedule_shape"),
+    ("lr_decay_measured_from_step_zero", [("frac = (total_steps - step) / (total_steps - warmup_steps)", "frac = (total_steps - step) / total_steps", None)],
+     "test_lr_schedule_shape"),
     ("bf16_widening_shift", [("<< np.uint32(16)", "<< np.uint32(15)", None)], "test_bf16_widening_matches_torch"),
 ]
 
