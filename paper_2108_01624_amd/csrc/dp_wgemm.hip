@@ -489,15 +489,17 @@ __global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmBatchArgs b) {
         ldsG[j] = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)&Gs[0][row0 * BN];
     }
     auto issue = [&](int st, int buf) {
-        const int soffA = __builtin_amdgcn_readfirstlane(st * BK * a.d_in * 2);
-        const int soffG = __builtin_amdgcn_readfirstlane(st * BK * a.d_out * 2);
+        // stages past the range load the last stage again (never multiplied): the stage offset is not part of the
+        // buffer bounds check, so it must not run past the rows
+        const int stc = st < nsteps ? st : (nsteps > 0 ? nsteps - 1 : 0);
+        const int soffA = __builtin_amdgcn_readfirstlane(stc * BK * a.d_in * 2);
+        const int soffG = __builtin_amdgcn_readfirstlane(stc * BK * a.d_out * 2);
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             dma_load16(rA, __builtin_amdgcn_readfirstlane(ldsA[j] + buf * (BK * BM * 2)), voffA[j], soffA);
             dma_load16(rG, __builtin_amdgcn_readfirstlane(ldsG[j] + buf * (BK * BN * 2)), voffG[j], soffG);
         }
     };
-
     const int frow = 8 * (lane >> 5) + ((lane & 15) >> 2);
     const int fsw = frow & 3;
     int foffA[MI], foffG[NI];
@@ -556,49 +558,99 @@ __global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmBatchArgs b) {
 
     bf16x8_t fa0[MI], fg0[NI], fa1[MI], fg1[NI];
     float c_cur = nsteps > 0 ? clip_of_stage(0) : 1.f;
-    int ex_cur = (int)((uint32_t)k_lo / (uint32_t)a.T);
 
     // prologue: DMA_NS - 1 stages in flight; publish stage 0
+    constexpr int AHEAD = DMA_NS - 1;  // the newest stage in flight is AHEAD stages past the one being multiplied
 #pragma unroll
-    for (int st = 0; st < DMA_NS - 1; ++st) issue(st, st);
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DMA_NS - 2) * LPS) : "memory");  // stage 0 has landed
+    for (int st = 0; st < AHEAD; ++st) issue(st, st);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((AHEAD - 1) * LPS) : "memory");  // stage 0 has landed
     __syncthreads();
-    load_frags(0, 0, fa0, fg0);
+    int buf = 0;      // ring slot of the stage being multiplied
+    int ibuf = AHEAD; // ring slot the next load fills
+    load_frags(buf, 0, fa0, fg0);
 
-    int buf = 0;
-    for (int s = 0; s < nsteps; ++s) {
-        const int buf1 = buf + 1 == DMA_NS ? 0 : buf + 1;            // stage s+1
-        const int bufp = buf == 0 ? DMA_NS - 1 : buf - 1;            // stage s-1 == stage s + DMA_NS - 1
-        // example boundary: rescale the running sums from weights relative to c_prev to weights relative to c_next
-        const int ex = (int)((uint32_t)(k_lo + (long)s * BK) / (uint32_t)a.T);
-        if (ex != ex_cur) {
-            const float c_next = clip_of_stage(s);
-            const float ratio = c_cur / c_next;
-            ex_cur = ex;
-            c_cur = c_next;
+    // One loop iteration = one stage = one barrier.  Iterations that start an example (RESCALE) multiply the
+    // accumulators by c_prev / c_next tile by tile, each tile's 16 multiplies directly before its MFMA, so that the
+    // matrix pipe works on tile t while the VALU rescales tile t+1; all other iterations are plain.  The two kinds
+    // are separate straight-line bodies in nested loops (a two-armed branch around the MFMAs costs the register
+    // allocator > 100 spilled VGPRs). 
+    int my = 0;      // the stage being multiplied; stages >= nsteps hold zeros
+    const int spe = a.T / BK;                                  // stages per example
+    // plain stages up to the first example start, and the example that starts there
+    const int head = (spe - (int)((uint32_t)(k_lo / BK) % (uint32_t)spe)) % spe;
+    int ex_run = (int)((uint32_t)(k_lo / BK + head) / (uint32_t)spe);
+    const int nex = (int)(a.K / a.T);
+    // lane l: clip factor c_e of example e = (ex & ~63) + l and the rescaling ratio c_{e-1} / c_e that applies when
+    // example e starts.  Two plain loads per 64 examples; the compiler's wait for them also waits for the
+    // LDS-filling loads in flight, a bubble once per 256 or more stages.
+    float cvec = 1.f, rvec = 1.f;
+    auto load_factors = [&](int ex) {
+        const int e = (ex & ~63) + lane;
+        const float n_e = e < nex ? a.sqnorms[e] : 1.f;
+        const float n_p = (e >= 1 && e - 1 < nex) ? a.sqnorms[e - 1] : n_e;
+        cvec = dp_clip_factor(n_e, a.C);
+        rvec = dp_clip_factor(n_p, a.C) / cvec;
+    };
+    if (nsteps > 0) load_factors(ex_run);
+    int s_issue = AHEAD;
+    auto body = [&](auto rescale_tag) {
+        constexpr bool RESCALE = decltype(rescale_tag)::value;
+        const int buf1 = buf + 1 == DMA_NS ? 0 : buf + 1;
+        const bool bias_now = want_bias && (my % duty_mod) == duty;
+        load_frags(buf, 1, fa1, fg1);
+        if (RESCALE) {
+            // factors of 64 examples sit in registers (lane = example mod 64), refilled every 64 examples
+            if ((ex_run & 63) == 0) load_factors(ex_run);
+            const int el = __builtin_amdgcn_readfirstlane(ex_run & 63);
+            const float ratio = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, rvec), el));
+            c_cur = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cvec), el));
+            ++ex_run;
 #pragma unroll
-            for (int j = 0; j < NI; ++j) {
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] *= ratio;
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[i], fg0[j], acc[i][j], 0, 0, 0);
+                }
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) bacc[j][r] *= ratio;
 #pragma unroll
-                for (int i = 0; i < MI; ++i)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[i][j][r] *= ratio;
+            for (int t = 0; t < MI * NI; ++t) {
+                __builtin_amdgcn_sched_group_barrier(0x002, 16, 0);  // 16 VALU
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
             }
+        } else {
+            mma(fa0, fg0);
         }
-        const bool bias_now = want_bias && (s % duty_mod) == duty;
-        load_frags(buf, 1, fa1, fg1);
-        mma(fa0, fg0);
         if (bias_now) mma_bias(fg0);
-        // my loads of stage s+1 have landed (later stages may still be in flight); after the barrier every
-        // wave's have, and every wave has finished reading stage s-1, whose buffer the newest stage now overwrites
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((DMA_NS - 3) * LPS) : "memory");
+        // my loads of the next stage have landed (later stages may still be in flight); after the barrier every
+        // wave's have, and every wave has finished reading the stage whose ring slot the newest stage now overwrites
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((AHEAD - 2) * LPS) : "memory");
         __syncthreads();
-        issue(s + DMA_NS - 1, bufp);
+        issue(s_issue, ibuf);
+        ++s_issue;
+        ibuf = ibuf + 1 == DMA_NS ? 0 : ibuf + 1;
         load_frags(buf1, 0, fa0, fg0);
         mma(fa1, fg1);
         if (bias_now) mma_bias(fg1);
         buf = buf1;
+        ++my;
+    };
+    int left = nsteps;
+    {
+        int n = head < left ? head : left;
+        left -= n;
+        for (int q = 0; q < n; ++q) body(std::false_type{});
+    }
+    while (left > 0) {
+        body(std::true_type{});
+        --left;
+        int n = spe - 1 < left ? spe - 1 : left;
+        left -= n;
+        for (int q = 0; q < n; ++q) body(std::false_type{});
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing may still be writing LDS when the workgroup ends
 
@@ -877,8 +929,9 @@ dp_status dpk_weighted_gemm_batched(dp_ctx* ctx, int n, const void* const* A, co
         }
         {
             dp_prof_scope prof(ctx, DP_PROF_WGEMM, 2.0 * (double)K * d_in * d_out * nl);
-            if (nsplit == 1) hipLaunchKernelGGL((wgemm_dma_kernel<EPI_ADD>), dim3((unsigned)nwg), dim3(512), 0, ctx->stream, b);
-            else hipLaunchKernelGGL((wgemm_dma_kernel<EPI_STORE>), dim3((unsigned)nwg), dim3(512), 0, ctx->stream, b);
+            const dim3 grid((unsigned)nwg), block(512);
+            if (nsplit == 1) hipLaunchKernelGGL((wgemm_dma_kernel<EPI_ADD>), grid, block, 0, ctx->stream, b);
+            else hipLaunchKernelGGL((wgemm_dma_kernel<EPI_STORE>), grid, block, 0, ctx->stream, b);
         }
         DP_LAUNCH_CHECK(ctx, "wgemm_dma");
         if (nsplit > 1) {
