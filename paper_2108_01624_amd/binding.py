@@ -25,6 +25,7 @@ SIGNATURES = {
     "dp_status_str": [c_int],
     "dp_last_error": [c_void_p],
     "dp_sqnorms_dense": [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p],
+    "dp_sqnorms_dense_batched": [c_void_p, c_int, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p],
     "dp_sqnorms_layernorm": [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_void_p],
     "dp_sqnorms_embedding": [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p],
     "dp_clip_factors": [c_void_p, c_void_p, c_int, c_float, c_void_p],
@@ -157,6 +158,20 @@ def dp_sqnorms_dense(ctx, A, G, has_bias, path, sqnorms, *, B=None, T=None):
     st = load_library().dp_sqnorms_dense(ctx, _ptr(A), _ptr(G), _dtype_of(A), B, T, A.shape[-1], G.shape[-1],
                                          int(has_bias), int(path), _f32(sqnorms))
     _check(ctx, st, "dp_sqnorms_dense")
+
+
+def dp_sqnorms_dense_batched(ctx, As, Gs, has_bias, path, sqnorms):
+    """As, Gs: equally long lists of same-shaped tensors (one pair per layer)."""
+    n = len(As)
+    B, T, d_in = As[0].shape
+    d_out = Gs[0].shape[-1]
+    for a, g in zip(As, Gs):
+        if tuple(a.shape) != (B, T, d_in) or tuple(g.shape) != (B, T, d_out) or a.dtype != As[0].dtype:
+            raise ValueError("all layers of a batch must share one shape and dtype")
+    arr = lambda ptrs: (c_void_p * n)(*ptrs)
+    st = load_library().dp_sqnorms_dense_batched(ctx, n, arr([_ptr(t) for t in As]), arr([_ptr(t) for t in Gs]),
+                                                 _dtype_of(As[0]), B, T, d_in, d_out, int(has_bias), int(path), _f32(sqnorms))
+    _check(ctx, st, "dp_sqnorms_dense_batched")
 
 
 def dp_sqnorms_layernorm(ctx, Xhat, G, sqnorms):

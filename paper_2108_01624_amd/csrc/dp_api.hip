@@ -238,6 +238,30 @@ dp_status dp_sqnorms_dense(dp_ctx* ctx, const void* A, const void* G, dp_dtype d
     return dpk_materialise_sqnorms(ctx, A, G, dtype, B, T, d_in, d_out, has_bias, sqnorms);
 }
 
+dp_status dp_sqnorms_dense_batched(dp_ctx* ctx, int n_layers, const void* const* A, const void* const* G, dp_dtype dtype,
+                                   int B, int T, int d_in, int d_out, int has_bias, dp_path path, float* sqnorms) {
+    REQUIRE_CTX(ctx);
+    TRY(check_dtype(ctx, dtype));
+    if (path != DP_PATH_AUTO && path != DP_PATH_GRAM && path != DP_PATH_MATERIALISE)
+        FAIL(ctx, DP_ERR_DTYPE, "unknown path %d", (int)path);
+    TRY(check_bt(ctx, B, T));
+    if (n_layers < 0 || d_in < 0 || d_out < 0) FAIL(ctx, DP_ERR_SHAPE, "negative layer count or width");
+    if (n_layers == 0) return DP_OK;
+    if (!A || !G) FAIL(ctx, DP_ERR_NULL, "a pointer table is NULL");
+    for (int l = 0; l < n_layers; ++l) {
+        TRY(check_tensor(ctx, "A[l]", A[l], dtype, d_in));
+        TRY(check_tensor(ctx, "G[l]", G[l], dtype, d_out));
+    }
+    TRY(check_f32(ctx, "sqnorms", sqnorms));
+    if (B == 0 || T == 0 || d_out == 0) return DP_OK;
+    if (path == DP_PATH_AUTO && d_in > 0) dp_choose_path(T, d_in, d_out, dtype, &path);
+    if (path == DP_PATH_GRAM && d_in > 0)
+        return dpk_gram_sqnorms_batched(ctx, n_layers, A, G, dtype, B, T, d_in, d_out, has_bias, sqnorms);
+    for (int l = 0; l < n_layers; ++l)
+        TRY(dp_sqnorms_dense(ctx, A[l], G[l], dtype, B, T, d_in, d_out, has_bias, path, sqnorms));
+    return DP_OK;
+}
+
 dp_status dp_sqnorms_layernorm(dp_ctx* ctx, const void* Xhat, const void* G, dp_dtype dtype, int B, int T, int d,
                                float* sqnorms) {
     REQUIRE_CTX(ctx);

@@ -205,17 +205,30 @@ __device__ __forceinline__ gram_i32x4 gram_rsrc(const void* base, uint32_t bytes
 }
 
 // GDK: contraction chunk per stage (a row segment of 2*GDK bytes per load); NS: ring stages.
+// Up to GRAM_MAX_BATCH same-shaped layers per launch: workgroup g works on example g % B of layer g / B.  More
+// workgroups than the chip holds at once keep the memory pipeline full across examples (one round of 512
+// workgroups spends a fifth of its time filling and draining it).
+constexpr int GRAM_MAX_BATCH = 16;
+struct GramBatch {
+    const uint16_t* A[GRAM_MAX_BATCH];
+    const uint16_t* G[GRAM_MAX_BATCH];
+    int n_layers;
+    int B;
+};
+
+// out: n_layers == 1: sqnorms, "+="; otherwise partials [B][n_layers], stored.
 template <int GDK, int NS, int WGS_PER_CU>
-__global__ __launch_bounds__(256, WGS_PER_CU) void gram_dma_kernel(const uint16_t* __restrict__ A,
-                                                                   const uint16_t* __restrict__ G, int T, int d_in,
-                                                                   int d_out, int has_bias, float* __restrict__ out) {
+__global__ __launch_bounds__(256, WGS_PER_CU) void gram_dma_kernel(GramBatch gb, int T, int d_in, int d_out,
+                                                                   int has_bias, float* __restrict__ out) {
     constexpr int STAGE = GB * GDK;        // bf16 elements per stage
     constexpr int CPR = GDK / 8;           // 16-byte chunks per row (8 or 16)
     constexpr int RPI = 64 / CPR;          // rows filled by one wave-wide load
     constexpr int LPS = GB / RPI / 4;      // loads per wave per stage
     __shared__ __attribute__((aligned(16))) uint16_t ring[NS][STAGE];
     __shared__ float wred[4];
-    const int i = blockIdx.x;
+    const int layer = blockIdx.x / gb.B, i = blockIdx.x - layer * gb.B;
+    const uint16_t* __restrict__ A = gb.A[layer];
+    const uint16_t* __restrict__ G = gb.G[layer];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wr = wave >> 1, wc = wave & 1;
     const bool active = wr <= wc;  // the lower-left quadrant mirrors the upper-right one
@@ -316,7 +329,10 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gram_dma_kernel(const uint16_
             for (int r = 0; r < 16; ++r) sum += (accA[a][b][r] + bias_term) * accG[a][b][r];
     sum *= wr == wc ? 1.f : (wr < wc ? 2.f : 0.f);
     const float tot = dp_block_sum<256>(sum, wred);
-    if (threadIdx.x == 0) out[i] += tot;
+    if (threadIdx.x == 0) {
+        if (gb.n_layers == 1) out[i] += tot;
+        else out[(size_t)i * gb.n_layers + layer] = tot;
+    }
 }
 
 // fp32 reference-precision paths (small shapes; parity configuration with fp32 inputs).
@@ -369,6 +385,70 @@ __global__ __launch_bounds__(256) void materialise_f32_kernel(const float* __res
 
 }  // namespace
 
+// The LDS-ring kernel serves one 128 x 128 block per example and widths that are multiples of its row segment.
+static bool gram_dma_ok(int T, int d_in, int d_out) {
+    return T <= GB && d_in % GK == 0 && d_out % GK == 0 && d_in > 0 && d_out > 0 &&
+           (size_t)T * (d_in > d_out ? d_in : d_out) * 2 < (1u << 31);
+}
+
+static dp_status gram_dma_launch(dp_ctx* ctx, const GramBatch& gb, int T, int d_in, int d_out, int has_bias, float* out,
+                                 double bytes) {
+    dp_prof_scope prof(ctx, DP_PROF_GRAM, bytes);
+    static int variant = -1;
+    if (variant < 0) {  // DPCLIP_GRAM_VARIANT: tuning aid
+        const char* e = getenv("DPCLIP_GRAM_VARIANT");
+        variant = e ? atoi(e) : 1;
+    }
+    const dim3 grid((unsigned)((long)gb.n_layers * gb.B)), block(256);
+    const bool wide = d_in % 128 == 0 && d_out % 128 == 0;
+    if (variant == 1 && wide)
+        hipLaunchKernelGGL((gram_dma_kernel<128, 2, 2>), grid, block, 0, ctx->stream, gb, T, d_in, d_out, has_bias, out);
+    else if (variant == 2 && wide)
+        hipLaunchKernelGGL((gram_dma_kernel<128, 3, 1>), grid, block, 0, ctx->stream, gb, T, d_in, d_out, has_bias, out);
+    else
+        hipLaunchKernelGGL((gram_dma_kernel<64, 4, 2>), grid, block, 0, ctx->stream, gb, T, d_in, d_out, has_bias, out);
+    DP_LAUNCH_CHECK(ctx, "gram_dma");
+    return DP_OK;
+}
+
+dp_status dpk_gram_sqnorms_batched(dp_ctx* ctx, int n_layers, const void* const* A, const void* const* G, dp_dtype dt,
+                                   int B, int T, int d_in, int d_out, int has_bias, float* sqnorms) {
+    if (dt != DP_BF16 || !gram_dma_ok(T, d_in, d_out) || (long)B * GRAM_MAX_BATCH > 0x7FFFFFFFl) {
+        for (int l = 0; l < n_layers; ++l) {
+            dp_status st = dpk_gram_sqnorms(ctx, A[l], G[l], dt, B, T, d_in, d_out, has_bias, sqnorms);
+            if (st != DP_OK) return st;
+        }
+        return DP_OK;
+    }
+    for (int l0 = 0; l0 < n_layers; l0 += GRAM_MAX_BATCH) {
+        const int nl = n_layers - l0 < GRAM_MAX_BATCH ? n_layers - l0 : GRAM_MAX_BATCH;
+        GramBatch gb;
+        for (int l = 0; l < GRAM_MAX_BATCH; ++l) {
+            gb.A[l] = (const uint16_t*)A[l0 + (l < nl ? l : 0)];
+            gb.G[l] = (const uint16_t*)G[l0 + (l < nl ? l : 0)];
+        }
+        gb.n_layers = nl;
+        gb.B = B;
+        const double bytes = 2.0 * (double)B * T * ((double)d_in + d_out) * nl;
+        if (nl == 1) {
+            dp_status st = gram_dma_launch(ctx, gb, T, d_in, d_out, has_bias, sqnorms, bytes);
+            if (st != DP_OK) return st;
+            continue;
+        }
+        dp_ws_alloc ws(ctx);
+        float* part = ws.get<float>((size_t)B * nl);
+        if (!part) {
+            DP_SET_ERR(ctx, "workspace too small for %d x %d norm partials", B, nl);
+            return DP_ERR_WORKSPACE;
+        }
+        dp_status st = gram_dma_launch(ctx, gb, T, d_in, d_out, has_bias, part, bytes);
+        if (st != DP_OK) return st;
+        st = dpk_finish_partials(ctx, part, B, nl, sqnorms);   // layers added in index order
+        if (st != DP_OK) return st;
+    }
+    return DP_OK;
+}
+
 dp_status dpk_gram_sqnorms(dp_ctx* ctx, const void* A, const void* G, dp_dtype dt, int B, int T, int d_in, int d_out,
                            int has_bias, float* sqnorms) {
     if (dt == DP_F32) {
@@ -388,25 +468,15 @@ dp_status dpk_gram_sqnorms(dp_ctx* ctx, const void* A, const void* G, dp_dtype d
         lds_attr_set = true;
     }
     const double bytes = 2.0 * (double)B * T * ((double)d_in + d_out);
-    if (npairs == 1 && d_in % GK == 0 && d_out % GK == 0 && (size_t)T * (d_in > d_out ? d_in : d_out) * 2 < (1u << 31)) {
-        dp_prof_scope prof(ctx, DP_PROF_GRAM, bytes);
-        static int variant = -1;
-        if (variant < 0) {  // DPCLIP_GRAM_VARIANT: tuning aid
-            const char* e = getenv("DPCLIP_GRAM_VARIANT");
-            variant = e ? atoi(e) : 1;
+    if (gram_dma_ok(T, d_in, d_out)) {
+        GramBatch gb;
+        for (int l = 0; l < GRAM_MAX_BATCH; ++l) {
+            gb.A[l] = (const uint16_t*)A;
+            gb.G[l] = (const uint16_t*)G;
         }
-        const bool wide = d_in % 128 == 0 && d_out % 128 == 0;
-        if (variant == 1 && wide)
-            hipLaunchKernelGGL((gram_dma_kernel<128, 2, 2>), dim3(B), dim3(256), 0, ctx->stream, (const uint16_t*)A,
-                               (const uint16_t*)G, T, d_in, d_out, has_bias, sqnorms);
-        else if (variant == 2 && wide)
-            hipLaunchKernelGGL((gram_dma_kernel<128, 3, 1>), dim3(B), dim3(256), 0, ctx->stream, (const uint16_t*)A,
-                               (const uint16_t*)G, T, d_in, d_out, has_bias, sqnorms);
-        else
-            hipLaunchKernelGGL((gram_dma_kernel<64, 4, 2>), dim3(B), dim3(256), 0, ctx->stream, (const uint16_t*)A,
-                               (const uint16_t*)G, T, d_in, d_out, has_bias, sqnorms);
-        DP_LAUNCH_CHECK(ctx, "gram_dma");
-        return DP_OK;
+        gb.n_layers = 1;
+        gb.B = B;
+        return gram_dma_launch(ctx, gb, T, d_in, d_out, has_bias, sqnorms, bytes);
     }
     if (npairs == 1) {
         dp_prof_scope prof(ctx, DP_PROF_GRAM, bytes);

@@ -41,19 +41,26 @@ class StepRunner:
             n *= s
         return buf[off:off + n].view(*shp)
 
-    def pass1(self, layers, path=B_.DP_PATH_AUTO):
-        """Per-example squared global norms of one micro-batch: sqnorms[:B] = sum over all layers."""
+    def pass1(self, layers, path=B_.DP_PATH_AUTO, batch_dense=True):
+        """Per-example squared global norms of one micro-batch: sqnorms[:B] = sum over all layers.  The norm is a sum
+        over layers, so dense layers of one shape are handed over together."""
         ctx = self.ctx
         nB = layers[0]["G"].shape[0]
         n = self.sqnorms[:nB]
         ctx.zero_f32(n)
+        groups = {}
         for l in layers:
             if l["kind"] == "dense":
-                ctx.sqnorms_dense(l["A"], l["G"], l["has_bias"], path, n)
+                if batch_dense:
+                    groups.setdefault((tuple(l["A"].shape), tuple(l["G"].shape), l["A"].dtype, bool(l["has_bias"])), []).append(l)
+                else:
+                    ctx.sqnorms_dense(l["A"], l["G"], l["has_bias"], path, n)
             elif l["kind"] == "layernorm":
                 ctx.sqnorms_layernorm(l["X"], l["G"], n)
             else:
                 ctx.sqnorms_embedding(l["ids"], l["G"], l["V"], l["distinct"], n)
+        for key, ls in groups.items():
+            ctx.sqnorms_dense_batched([l["A"] for l in ls], [l["G"] for l in ls], key[3], path, n)
         return n
 
     def pass2(self, layers, C, batch_dense=True):

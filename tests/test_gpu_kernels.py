@@ -567,6 +567,36 @@ def test_batched_equals_single_layer_calls(dp):
         assert_sums_close(host(bat[l]), host(one[l]).astype(np.float64), 1e-5, f"layer {l}")
 
 
+@pytest.mark.parametrize("n,B,T,d_in,d_out,has_bias", [(3, 5, 128, 256, 384, True), (18, 3, 96, 64, 128, False),
+                                                        (2, 4, 100, 72, 136, True), (2, 2, 300, 128, 128, True),
+                                                        (1, 6, 128, 128, 64, True)])
+def test_sqnorms_dense_batched(dp, n, B, T, d_in, d_out, has_bias):
+    """n same-shaped layers in one call: fast-path shapes (shared launches, more than 16 layers), ragged shapes and
+    several Gram blocks (per-layer fallback); the norms of all layers add up, on top of what sqnorms held."""
+    import paper_2108_01624_amd as pkg
+
+    As = [gen((B, T, d_in), 1.0, 500 + l, "bf16") for l in range(n)]
+    Gs = [gen((B, T, d_out), 0.1, 540 + l, "bf16") for l in range(n)]
+    ref = sum(orc.sqnorms_dense(a, g, has_bias) for a, g in zip(As, Gs))
+    A_d, G_d = [to_dev(a) for a in As], [to_dev(g) for g in Gs]
+    for path in (pkg.DP_PATH_AUTO, pkg.DP_PATH_GRAM, pkg.DP_PATH_MATERIALISE):
+        out = torch.full((B,), 3.0, dtype=torch.float32, device=DEV)
+        dp.sqnorms_dense_batched(A_d, G_d, has_bias, path, out)
+        dp.sync()
+        assert_norms_close(host(out).astype(np.float64) - 3.0, ref, 1e-4, f"path {path}")
+    # bit-reproducible, and equal to layer-by-layer calls up to the order of the fp32 additions
+    one = torch.zeros(B, dtype=torch.float32, device=DEV)
+    two = torch.zeros(B, dtype=torch.float32, device=DEV)
+    seq = torch.zeros(B, dtype=torch.float32, device=DEV)
+    dp.sqnorms_dense_batched(A_d, G_d, has_bias, pkg.DP_PATH_GRAM, one)
+    dp.sqnorms_dense_batched(A_d, G_d, has_bias, pkg.DP_PATH_GRAM, two)
+    for a, g in zip(A_d, G_d):
+        dp.sqnorms_dense(a, g, has_bias, pkg.DP_PATH_GRAM, seq)
+    dp.sync()
+    np.testing.assert_array_equal(host(one), host(two))
+    np.testing.assert_allclose(host(one), host(seq), rtol=1e-6)
+
+
 # ------------------------------------------------------------------------------------------------
 # Philox against an independent library (needs the HIP runtime, hence a GPU-box test)
 # ------------------------------------------------------------------------------------------------
