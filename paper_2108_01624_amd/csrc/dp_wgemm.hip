@@ -55,7 +55,7 @@ struct WgemmArgs {
 
 // Several layers of one shape in one launch (direct-to-LDS kernel): the unit of work distribution is the pair
 // (layer, row split); `base` describes the common shape, and base.A / base.G / base.out are not used.
-constexpr int MAX_BATCH = 16;
+constexpr int MAX_BATCH = 32;
 struct LayerPtrs {
     const uint16_t* A;
     const uint16_t* G;

@@ -65,7 +65,7 @@ class StepRunner:
 
     def pass2(self, layers, C, batch_dense=True):
         """S += sum_i clip(grad_i, C) for one micro-batch, using the norms left by pass1.  The sums of different
-        layers are independent, so dense layers of one shape are handed over together (16 at a time)."""
+        layers are independent, so dense layers of one shape are handed over together (the library cuts them into launches that fill the chip)."""
         ctx = self.ctx
         nB = layers[0]["G"].shape[0]
         n = self.sqnorms[:nB]
@@ -81,13 +81,11 @@ class StepRunner:
                 ctx.clip_accumulate_layernorm(l["X"], l["G"], C, n, self.view(self.S, k, 0), self.view(self.S, k, 1))
             else:
                 ctx.clip_accumulate_embedding(l["ids"], l["G"], l["V"], C, n, self.view(self.S, k, 0))
-        for ks in groups.values():
-            for i in range(0, len(ks), 16):
-                sel = ks[i:i + 16]
-                ctx.clip_accumulate_dense_batched(
-                    [layers[k]["A"] for k in sel], [layers[k]["G"] for k in sel], C, n,
-                    [self.view(self.S, k, 0) for k in sel],
-                    [self.view(self.S, k, 1) if layers[k]["has_bias"] else None for k in sel])
+        for sel in groups.values():
+            ctx.clip_accumulate_dense_batched(
+                [layers[k]["A"] for k in sel], [layers[k]["G"] for k in sel], C, n,
+                [self.view(self.S, k, 0) for k in sel],
+                [self.view(self.S, k, 1) if layers[k]["has_bias"] else None for k in sel])
 
     def update(self, *, sigma, C, seed, step, batch_size, lr, beta1, beta2, eps=1e-11, weight_decay, zero_sum=True,
                snr_sq=None):
