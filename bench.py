@@ -30,6 +30,8 @@ def parse():
     ap.add_argument("--workload", default="C3", choices=["C2", "C3", "C4", "C5"],
                     help="C3 is the workload the metric is quoted on; C4 = mega-batch step (64 micro-batches of 1024 "
                          "examples accumulated, one update; the micro-batch buffers are reused), others for comparison")
+    ap.add_argument("--path", default="auto", choices=["auto", "gram", "materialise"],
+                    help="force the dense-layer norm path of pass 1 (comparison runs; auto is what the metric uses)")
     ap.add_argument("--batch", type=int, default=0, help="override the micro-batch size (parity/debug only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-examples", type=int, default=0, help="examples in the oracle sample (0 = auto)")
@@ -96,10 +98,11 @@ def main():
     run.theta.copy_(torch.randn(run.P, generator=gen, device=dev) * 0.02)
 
     n_micro = cfg.get("micro_batches", 1) if not args.batch else 1
+    path = {"auto": pkg.DP_PATH_AUTO, "gram": pkg.DP_PATH_GRAM, "materialise": pkg.DP_PATH_MATERIALISE}[args.path]
 
     def step(t):
         for _ in range(n_micro):
-            run.pass1(layers)
+            run.pass1(layers, path)
             run.pass2(layers, cfg["C"])
         run.update(sigma=upd["sigma"], C=cfg["C"], seed=upd["noise_seed"], step=t, batch_size=B * n_micro, lr=upd["lr"],
                    beta1=upd["beta1"], beta2=upd["beta2"], weight_decay=upd["weight_decay"], zero_sum=True)
@@ -122,7 +125,7 @@ def main():
         ev = evs[k]
         if n_micro == 1:
             ev[0].record()
-            run.pass1(layers)
+            run.pass1(layers, path)
             ev[1].record()
             run.pass2(layers, cfg["C"])
             ev[2].record()
@@ -174,7 +177,7 @@ def main():
                                f"micro-batch B={B}, seq T={T}, bf16 inputs / fp32 accumulation, C={cfg['C']}; "
                                f"one step = norms + clip-accumulate over all layers + noise/AdamW over all params"
                                if args.workload != "C2" else f"C2: BERT-Base-shaped stack, B={B}, T={T}",
-                   "params": int(run.P), "micro_batch": B, "micro_batches_per_step": n_micro, "seq_len": T,
+                   "params": int(run.P), "micro_batch": B, "micro_batches_per_step": n_micro, "seq_len": T, "norm_path": args.path,
                    "input_bytes": int(in_bytes)},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
