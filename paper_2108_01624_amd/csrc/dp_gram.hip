@@ -335,6 +335,149 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gram_dma_kernel(GramBatch gb,
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// T > 128, widths multiples of 64: one workgroup per 128 x 128 block pair (tb <= sb) of one example's T x T plane,
+// fed like the kernel above: the two row panels of a 64-wide contraction chunk (32 KiB; 16 KiB on the diagonal,
+// where they coincide) go straight into an LDS ring, no staging registers and no LDS store instructions.  At this
+// size the contraction, not HBM, is the bound (T flop per byte against ~310 at the machine balance), and within the
+// contraction the LDS reads: with 64 x 64 wave tiles every 32x32x16 MFMA needs one 16-byte-per-lane fragment read,
+// which by itself keeps the CU's LDS port busy.  Two stages and two workgroups per CU measured best (22.9 ms for
+// pass 1 of the T = 512 workload against 27.7 ms for the register-staged kernel); a deeper ring with one workgroup
+// per CU (one wave per SIMD) was slower (31 ms).  The block pairs of an example share an XCD (workgroup id % 8), so
+// each panel comes from HBM once and from L2 for its other uses.
+// ------------------------------------------------------------------------------------------------
+constexpr int GP_K = 64;
+
+template <bool OFFDIAG, int GP_NS>
+__device__ __forceinline__ float gram_pair_ring(const uint16_t* __restrict__ A, const uint16_t* __restrict__ G, int T,
+                                                int d_in, int d_out, int tb, int sb, float bias_term,
+                                                uint16_t (*ring)[2 * GB * GP_K]) {
+    constexpr int PANEL = GB * GP_K;        // bf16 elements of one panel of a stage
+    constexpr int LPP = 4;                  // loads per wave per panel: 8 rows of 8 chunks each
+    constexpr int LPS = OFFDIAG ? 2 * LPP : LPP;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wr = wave >> 1, wc = wave & 1;
+    const bool active = OFFDIAG || wr <= wc;
+    const int nchA = d_in / GP_K, nch = nchA + d_out / GP_K;
+    auto swz = [](int r) { return (r >> 1) & 7; };
+    // rows >= T lie outside the example's byte range and read as zero
+    const gram_i32x4 rA = gram_rsrc(A, (uint32_t)((size_t)T * d_in * 2));
+    const gram_i32x4 rG = gram_rsrc(G, (uint32_t)((size_t)T * d_out * 2));
+    int voffA[2][LPP], voffG[2][LPP];
+    uint32_t ldsoff[LPP];
+#pragma unroll
+    for (int j = 0; j < LPP; ++j) {
+        const int row0 = (LPP * wave + j) * 8, row = row0 + (lane >> 3);
+        const int cg = (lane & 7) ^ swz(row);
+        voffA[0][j] = ((tb * GB + row) * d_in + cg * 8) * 2;
+        voffG[0][j] = ((tb * GB + row) * d_out + cg * 8) * 2;
+        voffA[1][j] = ((sb * GB + row) * d_in + cg * 8) * 2;
+        voffG[1][j] = ((sb * GB + row) * d_out + cg * 8) * 2;
+        ldsoff[j] = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)&ring[0][row0 * GP_K];
+    }
+    int ibuf = 0;
+    auto issue = [&](int st) {
+        const bool isA = st < nchA;
+        // past the last chunk the loads still go out (the wait counts stay uniform) but read zeros
+        const int soff = __builtin_amdgcn_readfirstlane(st < nch ? (isA ? st : st - nchA) * GP_K * 2 : 0x7FFFFFF0);
+#pragma unroll
+        for (int pn = 0; pn < (OFFDIAG ? 2 : 1); ++pn)
+#pragma unroll
+            for (int j = 0; j < LPP; ++j) {
+                const uint32_t dst = __builtin_amdgcn_readfirstlane(ldsoff[j] + (ibuf * 2 * PANEL + pn * PANEL) * 2);
+                if (isA) gram_dma16(rA, dst, voffA[pn][j], soff);
+                else gram_dma16(rG, dst, voffG[pn][j], soff);
+            }
+        ibuf = ibuf + 1 == GP_NS ? 0 : ibuf + 1;
+    };
+    int fr[2], fc[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int r = wr * 64 + u * 32 + (lane & 31), c = wc * 64 + u * 32 + (lane & 31);
+        fr[u] = r * GP_K + (((lane >> 5) ^ swz(r)) << 3);
+        fc[u] = c * GP_K + (((lane >> 5) ^ swz(c)) << 3) + (OFFDIAG ? PANEL : 0);
+    }
+    f32x16_t accA[2][2], accG[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) accA[a][b][r] = accG[a][b][r] = 0.f;
+
+#pragma unroll
+    for (int st = 0; st < GP_NS - 1; ++st) issue(st);
+    int cbuf = 0, s_next = GP_NS - 1;
+    auto stage = [&](f32x16_t (&acc)[2][2]) {
+        // my loads of this chunk have landed (up to three later chunks may be in flight); after the barrier everyone's
+        // have, and everyone is done reading the previous chunk, whose slot the newest chunk overwrites
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((GP_NS - 2) * LPS) : "memory");
+        __syncthreads();
+        issue(s_next++);
+        if (active) {
+            const uint16_t* st = ring[cbuf];
+#pragma unroll
+            for (int kk = 0; kk < GP_K / 16; ++kk) {
+                bf16x8_t a0[2], b0[2];
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int xr = fr[u] ^ ((2 * kk) << 3), xc = fc[u] ^ ((2 * kk) << 3);
+                    a0[u] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(st + xr));
+                    b0[u] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(st + xc));
+                }
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < 2; ++nt)
+                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mt], b0[nt], acc[mt][nt], 0, 0, 0);
+            }
+        }
+        cbuf = cbuf + 1 == GP_NS ? 0 : cbuf + 1;
+    };
+    for (int s = 0; s < nchA; ++s) stage(accA);
+    for (int s = nchA; s < nch; ++s) stage(accG);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing may still be writing LDS past this point
+    float sum = 0.f;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sum += (accA[a][b][r] + bias_term) * accG[a][b][r];
+    return sum * (OFFDIAG ? 2.f : (wr == wc ? 1.f : (wr < wc ? 2.f : 0.f)));
+}
+
+// out: partials [B][n_layers * npairs], stored.  Workgroup id g -> XCD g % 8; unit (layer, example) u =
+// (g / 8 / npairs) * 8 + g % 8, pair = (g / 8) % npairs.
+template <int GP_NS, int WPC>
+__global__ __launch_bounds__(256, WPC) void gram_pairs_dma_kernel(GramBatch gb, int T, int d_in, int d_out, int has_bias,
+                                                                  int nblk, int npairs, float* __restrict__ out) {
+    __shared__ __attribute__((aligned(16))) uint16_t ring[GP_NS][2 * GB * GP_K];
+    const int slot = blockIdx.x >> 3;
+    const int u = (slot / npairs) * 8 + (blockIdx.x & 7);
+    const int pair = slot % npairs;
+    if (u >= gb.n_layers * gb.B) return;
+    const int layer = u / gb.B, i = u - layer * gb.B;
+    int tb = 0, sb = 0;
+    {
+        int p = pair;
+        while (p >= nblk - tb) {  // row tb of the upper triangle holds nblk - tb pairs
+            p -= nblk - tb;
+            ++tb;
+        }
+        sb = tb + p;
+    }
+    const uint16_t* A = gb.A[layer] + (size_t)i * T * d_in;
+    const uint16_t* G = gb.G[layer] + (size_t)i * T * d_out;
+    const float bias_term = has_bias ? 1.f : 0.f;
+    float s;
+    if (tb == sb) s = gram_pair_ring<false, GP_NS>(A, G, T, d_in, d_out, tb, sb, bias_term, ring);
+    else s = gram_pair_ring<true, GP_NS>(A, G, T, d_in, d_out, tb, sb, bias_term, ring);
+    __syncthreads();  // the ring is free: its first floats serve the reduction
+    const float tot = dp_block_sum<256>(s, reinterpret_cast<float*>(&ring[0][0]));
+    if (threadIdx.x == 0) out[((size_t)i * gb.n_layers + layer) * npairs + pair] = tot;
+}
+
 // fp32 reference-precision paths (small shapes; parity configuration with fp32 inputs).
 // One workgroup per example; thread-strided loop over the pairs t <= s.
 __global__ __launch_bounds__(256) void gram_f32_kernel(const float* __restrict__ A, const float* __restrict__ G, int T,
@@ -411,8 +554,71 @@ static dp_status gram_dma_launch(dp_ctx* ctx, const GramBatch& gb, int T, int d_
     return DP_OK;
 }
 
+// The block-pair ring kernel: several 128 x 128 blocks per example, widths multiples of its 64-wide chunk.
+static bool gram_pairs_ok(int T, int d_in, int d_out) {
+    return T > GB && d_in % GP_K == 0 && d_out % GP_K == 0 && d_in > 0 && d_out > 0 &&
+           (size_t)T * (d_in > d_out ? d_in : d_out) * 2 < (1u << 31);
+}
+
+// nl <= GRAM_MAX_BATCH same-shaped layers: partials [B][nl * npairs] through the workspace, added in index order.
+static dp_status gram_pairs_launch(dp_ctx* ctx, const GramBatch& gb, int T, int d_in, int d_out, int has_bias,
+                                   float* sqnorms) {
+    const int nblk = (T + GB - 1) / GB;
+    const long npairs = (long)nblk * (nblk + 1) / 2;
+    const long units = (long)gb.n_layers * gb.B;
+    const long nwg = (units + 7) / 8 * 8 * npairs;
+    if (nwg > 0x7FFFFFFFl || npairs * gb.n_layers > 0x7FFFFFFFl) {
+        DP_SET_ERR(ctx, "dp_sqnorms_dense: B * T^2 too large for one launch");
+        return DP_ERR_SHAPE;
+    }
+    dp_ws_alloc ws(ctx);
+    float* part = ws.get<float>((size_t)units * npairs);
+    if (!part) {
+        DP_SET_ERR(ctx, "workspace too small for %ld x %ld Gram partials", units, npairs);
+        return DP_ERR_WORKSPACE;
+    }
+    {
+        dp_prof_scope prof(ctx, DP_PROF_GRAM, 2.0 * (double)gb.B * T * ((double)d_in + d_out) * gb.n_layers);
+        hipLaunchKernelGGL((gram_pairs_dma_kernel<2, 2>), dim3((unsigned)nwg), dim3(256), 0, ctx->stream, gb, T, d_in,
+                           d_out, has_bias, nblk, (int)npairs, part);
+    }
+    DP_LAUNCH_CHECK(ctx, "gram_pairs_dma");
+    return dpk_finish_partials(ctx, part, gb.B, (int)(npairs * gb.n_layers), sqnorms);
+}
+
+static bool gram_pairs_enabled() {
+    static int on = -1;
+    if (on < 0) {  // DPCLIP_GRAM_PAIRS=0: the register-staged kernel for T > 128 (tuning aid)
+        const char* e = getenv("DPCLIP_GRAM_PAIRS");
+        on = (e && e[0] == '0') ? 0 : 1;
+    }
+    return on != 0;
+}
+
 dp_status dpk_gram_sqnorms_batched(dp_ctx* ctx, int n_layers, const void* const* A, const void* const* G, dp_dtype dt,
                                    int B, int T, int d_in, int d_out, int has_bias, float* sqnorms) {
+    if (dt == DP_BF16 && gram_pairs_ok(T, d_in, d_out) && gram_pairs_enabled()) {
+        // enough layers per launch for a few rounds of workgroups, and partials that fit the workspace
+        const int nblk = (T + GB - 1) / GB;
+        const long npairs = (long)nblk * (nblk + 1) / 2;
+        int per = GRAM_MAX_BATCH;
+        while (per > 1 && ((size_t)per * B * npairs * sizeof(float) > ctx->ws_bytes / 2 ||
+                           (long)per * B * npairs > (1l << 22)))
+            per /= 2;
+        for (int l0 = 0; l0 < n_layers; l0 += per) {
+            const int nl = n_layers - l0 < per ? n_layers - l0 : per;
+            GramBatch gb;
+            for (int l = 0; l < GRAM_MAX_BATCH; ++l) {
+                gb.A[l] = (const uint16_t*)A[l0 + (l < nl ? l : 0)];
+                gb.G[l] = (const uint16_t*)G[l0 + (l < nl ? l : 0)];
+            }
+            gb.n_layers = nl;
+            gb.B = B;
+            dp_status st = gram_pairs_launch(ctx, gb, T, d_in, d_out, has_bias, sqnorms);
+            if (st != DP_OK) return st;
+        }
+        return DP_OK;
+    }
     if (dt != DP_BF16 || !gram_dma_ok(T, d_in, d_out) || (long)B * GRAM_MAX_BATCH > 0x7FFFFFFFl) {
         for (int l = 0; l < n_layers; ++l) {
             dp_status st = dpk_gram_sqnorms(ctx, A[l], G[l], dt, B, T, d_in, d_out, has_bias, sqnorms);
@@ -468,7 +674,7 @@ dp_status dpk_gram_sqnorms(dp_ctx* ctx, const void* A, const void* G, dp_dtype d
         lds_attr_set = true;
     }
     const double bytes = 2.0 * (double)B * T * ((double)d_in + d_out);
-    if (gram_dma_ok(T, d_in, d_out)) {
+    if (gram_dma_ok(T, d_in, d_out) || (gram_pairs_ok(T, d_in, d_out) && gram_pairs_enabled())) {
         GramBatch gb;
         for (int l = 0; l < GRAM_MAX_BATCH; ++l) {
             gb.A[l] = (const uint16_t*)A;
@@ -476,6 +682,7 @@ dp_status dpk_gram_sqnorms(dp_ctx* ctx, const void* A, const void* G, dp_dtype d
         }
         gb.n_layers = 1;
         gb.B = B;
+        if (T > GB) return gram_pairs_launch(ctx, gb, T, d_in, d_out, has_bias, sqnorms);
         return gram_dma_launch(ctx, gb, T, d_in, d_out, has_bias, sqnorms, bytes);
     }
     if (npairs == 1) {

@@ -219,6 +219,9 @@ DENSE_SHAPES = [
     ("bf16", 9, 300, 264, 128),   # 3 x 3 Gram blocks with a ragged last block, 9 examples over 8 XCD lanes
     ("bf16", 2, 512, 128, 1024),  # 4 x 4 Gram blocks
     ("bf16", 1, 1, 8, 8),         # T = 1
+    ("bf16", 3, 300, 128, 192),   # 3 x 3 blocks, ragged last block, widths the block-pair ring kernel takes
+    ("bf16", 2, 129, 64, 64),     # one row into the second block
+    ("bf16", 11, 256, 320, 64),   # 2 x 2 blocks, 11 examples over the 8 XCD lanes
 ]
 
 
