@@ -209,6 +209,24 @@ dp_status dp_batch_size_schedule(uint64_t step, uint64_t b_start, uint64_t b_end
 dp_status dp_lr_schedule(uint64_t step, double peak, uint64_t warmup_steps, uint64_t total_steps, double* out);
 
 /* ---------------------------------------------------------------------------------------------------
+ * Privacy accounting for a schedule of batch sizes (Section 3: Renyi-DP composition over steps with different
+ * batch sizes, then translation to (eps, delta)).  Host-only, pure, double precision; out pointers are HOST
+ * pointers.  Written from the cited papers (Mironov, "Renyi differential privacy"; Mironov, Talwar, Zhang,
+ * "Renyi differential privacy of the sampled Gaussian mechanism"), integer orders only.
+ *
+ * dp_rdp_sampled_gaussian: eps(alpha) of ONE step that applies the Gaussian mechanism with noise multiplier sigma
+ * to a Poisson sample of rate q = batch size / data-set size, for an integer order alpha >= 2:
+ *     eps(alpha) = ln( sum_{k=0..alpha} C(alpha,k) (1-q)^(alpha-k) q^k exp((k^2-k) / (2 sigma^2)) ) / (alpha - 1).
+ * dp_rdp_epsilon: a run of n_phases phases, phase p = steps[p] steps at rate q[p], is
+ * (alpha, sum_p steps[p] * eps_p(alpha))-RDP; returns the smallest eps = RDP(alpha) + ln(1/delta) / (alpha - 1)
+ * over alpha = 2 .. max_alpha and (if best_alpha is not NULL) the order that gives it.
+ * DP_ERR_VALUE for q outside [0,1], sigma <= 0, alpha < 2, delta outside (0,1).
+ * ------------------------------------------------------------------------------------------------- */
+dp_status dp_rdp_sampled_gaussian(double q, double sigma, int alpha, double* out);
+dp_status dp_rdp_epsilon(const double* q, const uint64_t* steps, int n_phases, double sigma, double delta, int max_alpha,
+                         double* eps, int* best_alpha);
+
+/* ---------------------------------------------------------------------------------------------------
  * Kernel timing (for benchmarks): while enabled, the library brackets each launch of its three main
  * kernels with HIP events on the context's stream.  dp_profile_read synchronises the stream and returns,
  * for one kernel kind, the summed launch duration in milliseconds, the launch count and the summed

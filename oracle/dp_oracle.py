@@ -430,3 +430,47 @@ def lr_schedule(step: int, peak: float, warmup_steps: int, total_steps: int) -> 
         return 0.0
     frac = (total_steps - step) / (total_steps - warmup_steps)
     return peak * frac * frac
+
+
+# --------------------------------------------------------------------------------------
+# privacy accounting over a schedule of batch sizes (Renyi DP composition, Section 3)
+# --------------------------------------------------------------------------------------
+
+
+def rdp_sampled_gaussian(q: float, sigma: float, alpha: int) -> float:
+    """Renyi divergence of integer order alpha >= 2 between one step's output distributions on neighbouring
+    data sets: the Gaussian mechanism with noise multiplier sigma applied to a Poisson sample of rate q
+    (Mironov, Talwar, Zhang, "Renyi differential privacy of the sampled Gaussian mechanism"):
+        eps(alpha) = ln( sum_{k=0..alpha} C(alpha,k) (1-q)^(alpha-k) q^k exp((k^2 - k) / (2 sigma^2)) ) / (alpha - 1),
+    written out term by term in 60-digit decimal arithmetic."""
+    from decimal import Decimal, getcontext
+    from math import comb
+
+    if not (0.0 <= q <= 1.0) or sigma <= 0 or alpha < 2:
+        raise ValueError("bad accounting arguments")
+    getcontext().prec = 60
+    qd, sd = Decimal(q), Decimal(sigma)
+    total = Decimal(0)
+    power = lambda x, n: Decimal(1) if n == 0 else x ** n   # 0^0 = 1 (the decimal module refuses it)
+    for k in range(alpha + 1):
+        total += Decimal(comb(alpha, k)) * power(1 - qd, alpha - k) * power(qd, k) * (Decimal(k * k - k) / (2 * sd * sd)).exp()
+    return float(total.ln() / (alpha - 1))
+
+
+def rdp_epsilon(q, steps, sigma: float, delta: float, max_alpha: int = 256):
+    """(eps, best alpha) of a run made of phases: phase p takes steps[p] steps at sampling rate q[p] (batch size over
+    data-set size), all with noise multiplier sigma.  By composition the run is (alpha, sum_p steps[p] * eps_p(alpha))-RDP
+    for every alpha (the paper's accounting for the increasing batch-size schedule); the (eps, delta) guarantee is the
+    best conversion over integer orders 2..max_alpha, eps = RDP(alpha) + ln(1/delta) / (alpha - 1) (Mironov,
+    "Renyi differential privacy", Proposition 3).  Reading: the paper names the accountant but not the conversion."""
+    import math
+
+    if len(q) != len(steps) or not (0.0 < delta < 1.0) or max_alpha < 2:
+        raise ValueError("bad accounting arguments")
+    best = (float("inf"), 0)
+    for alpha in range(2, max_alpha + 1):
+        rdp = sum(n * rdp_sampled_gaussian(qq, sigma, alpha) for qq, n in zip(q, steps))
+        eps = rdp + math.log(1.0 / delta) / (alpha - 1)
+        if eps < best[0]:
+            best = (eps, alpha)
+    return best

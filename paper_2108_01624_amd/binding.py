@@ -48,6 +48,9 @@ SIGNATURES = {
     "dp_choose_path": [c_int, c_int, c_int, c_int, ctypes.POINTER(c_int)],
     "dp_batch_size_schedule": [c_uint64, c_uint64, c_uint64, c_uint64, ctypes.c_uint32, ctypes.POINTER(c_uint64)],
     "dp_lr_schedule": [c_uint64, ctypes.c_double, c_uint64, c_uint64, ctypes.POINTER(ctypes.c_double)],
+    "dp_rdp_sampled_gaussian": [ctypes.c_double, ctypes.c_double, c_int, ctypes.POINTER(ctypes.c_double)],
+    "dp_rdp_epsilon": [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_uint64), c_int, ctypes.c_double, ctypes.c_double,
+                       c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_int)],
     "dp_profile_enable": [c_void_p, c_int],
     "dp_profile_read": [c_void_p, c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_uint64),
                         ctypes.POINTER(ctypes.c_double)],
@@ -275,6 +278,27 @@ def dp_lr_schedule(step, peak, warmup_steps, total_steps) -> float:
     if st != DP_OK:
         raise DpError(st, "dp_lr_schedule")
     return out.value
+
+
+def dp_rdp_sampled_gaussian(q, sigma, alpha) -> float:
+    out = ctypes.c_double()
+    st = load_library().dp_rdp_sampled_gaussian(q, sigma, alpha, ctypes.byref(out))
+    if st != DP_OK:
+        raise DpError(st, "dp_rdp_sampled_gaussian")
+    return out.value
+
+
+def dp_rdp_epsilon(q, steps, sigma, delta, max_alpha=256):
+    """(eps, best order) of a run of len(q) phases: steps[p] steps at sampling rate q[p]."""
+    n = len(q)
+    if len(steps) != n:
+        raise ValueError("q and steps must be equally long")
+    eps, arg = ctypes.c_double(), c_int()
+    st = load_library().dp_rdp_epsilon((ctypes.c_double * n)(*q), (c_uint64 * n)(*steps), n, sigma, delta, max_alpha,
+                                       ctypes.byref(eps), ctypes.byref(arg))
+    if st != DP_OK:
+        raise DpError(st, "dp_rdp_epsilon")
+    return eps.value, arg.value
 
 
 def dp_choose_path(T, d_in, d_out, dtype=DP_BF16) -> int:

@@ -217,6 +217,52 @@ dp_status dp_lr_schedule(uint64_t step, double peak, uint64_t warmup_steps, uint
     return DP_OK;
 }
 
+// ln of one term of the sampled-Gaussian moment sum; -inf for a vanishing factor
+static double rdp_log_term(double q, double sigma, int alpha, int k) {
+    const double lq = q > 0.0 ? log(q) : -INFINITY, l1q = q < 1.0 ? log1p(-q) : -INFINITY;
+    double t = lgamma(alpha + 1.0) - lgamma(k + 1.0) - lgamma(alpha - k + 1.0);
+    if (k > 0) t += k * lq;
+    if (alpha - k > 0) t += (alpha - k) * l1q;
+    return t + ((double)k * k - k) / (2.0 * sigma * sigma);
+}
+
+dp_status dp_rdp_sampled_gaussian(double q, double sigma, int alpha, double* out) {
+    if (!out) return DP_ERR_NULL;
+    if (!(q >= 0.0 && q <= 1.0) || !(sigma > 0.0) || !isfinite(sigma) || alpha < 2) return DP_ERR_VALUE;
+    // log-sum-exp over the alpha + 1 terms
+    double mx = -INFINITY;
+    for (int k = 0; k <= alpha; ++k) mx = fmax(mx, rdp_log_term(q, sigma, alpha, k));
+    double acc = 0.0;
+    for (int k = 0; k <= alpha; ++k) acc += exp(rdp_log_term(q, sigma, alpha, k) - mx);
+    *out = (mx + log(acc)) / (alpha - 1.0);
+    return DP_OK;
+}
+
+dp_status dp_rdp_epsilon(const double* q, const uint64_t* steps, int n_phases, double sigma, double delta, int max_alpha,
+                         double* eps, int* best_alpha) {
+    if (!q || !steps || !eps) return DP_ERR_NULL;
+    if (n_phases < 0 || !(delta > 0.0 && delta < 1.0) || max_alpha < 2) return DP_ERR_VALUE;
+    double best = INFINITY;
+    int arg = 0;
+    for (int alpha = 2; alpha <= max_alpha; ++alpha) {
+        double rdp = 0.0;
+        for (int p = 0; p < n_phases; ++p) {
+            double e;
+            const dp_status st = dp_rdp_sampled_gaussian(q[p], sigma, alpha, &e);
+            if (st != DP_OK) return st;
+            rdp += (double)steps[p] * e;
+        }
+        const double cand = rdp + log(1.0 / delta) / (alpha - 1.0);
+        if (cand < best) {
+            best = cand;
+            arg = alpha;
+        }
+    }
+    *eps = best;
+    if (best_alpha) *best_alpha = arg;
+    return DP_OK;
+}
+
 dp_status dp_sqnorms_dense(dp_ctx* ctx, const void* A, const void* G, dp_dtype dtype, int B, int T, int d_in,
                            int d_out, int has_bias, dp_path path, float* sqnorms) {
     REQUIRE_CTX(ctx);

@@ -101,3 +101,29 @@ def test_schedules_match_the_oracle(lib):
         pkg.dp_lr_schedule(0, 1e-3, 10, 20)
     with pytest.raises(pkg.DpError):
         pkg.dp_lr_schedule(1, 1e-3, 30, 20)
+
+
+def test_privacy_accounting_matches_the_oracle(lib):
+    """Host-only entry points: log-space double arithmetic against the oracle's 60-digit term-by-term sum."""
+    import math
+
+    import paper_2108_01624_amd as pkg
+    from oracle import dp_oracle as orc
+
+    for q in (0.0, 1e-6, 7.6e-4, 3.03e-3, 0.05, 0.5, 1.0):
+        for sigma in (0.3, 0.6, 1.0, 4.0):
+            for alpha in (2, 3, 7, 32, 128, 256):
+                got, ref = pkg.dp_rdp_sampled_gaussian(q, sigma, alpha), orc.rdp_sampled_gaussian(q, sigma, alpha)
+                assert abs(got - ref) <= 1e-10 * abs(ref) + 1e-16, (q, sigma, alpha, got, ref)
+    N = 346_000_000
+    q = [262144 / N, 458752 / N, 655360 / N, 851968 / N, 1048576 / N]
+    steps = [1875, 1875, 1875, 1875, 12500]
+    for sigma in (0.5, 0.6, 1.0):
+        got, ref = pkg.dp_rdp_epsilon(q, steps, sigma, 2.89e-9, 64), orc.rdp_epsilon(q, steps, sigma, 2.89e-9, 64)
+        assert got[1] == ref[1] and math.isclose(got[0], ref[0], rel_tol=1e-10)
+    assert pkg.dp_rdp_epsilon([], [], 1.0, 1e-5, 8)[0] == math.log(1e5) / 7      # no steps: only the conversion term is left
+    for bad in ((-0.1, 1.0, 2), (1.1, 1.0, 2), (0.1, 0.0, 2), (0.1, 1.0, 1)):
+        with pytest.raises(pkg.DpError):
+            pkg.dp_rdp_sampled_gaussian(*bad)
+    with pytest.raises(pkg.DpError):
+        pkg.dp_rdp_epsilon([0.1], [1], 1.0, 0.0, 8)

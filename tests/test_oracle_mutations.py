@@ -108,6 +108,16 @@ MUTANTS = [
     ("lr_warmup_lags_one_step", [("return peak * step / warmup_steps", "return peak * (step - 1) / warmup_steps", None)], "test_lr_schedule_shape"),
     ("lr_decay_measured_from_step_zero", [("frac = (total_steps - step) / (total_steps - warmup_steps)", "frac = (total_steps - step) / total_steps", None)],
      "test_lr_schedule_shape"),
+    ("rdp_divides_by_alpha", [("return float(total.ln() / (alpha - 1))", "return float(total.ln() / alpha)", None)], "test_rdp_closed_forms"),
+    ("rdp_exponent_k_squared_plus_k", [("Decimal(k * k - k) / (2 * sd * sd)", "Decimal(k * k + k) / (2 * sd * sd)", None)], "test_rdp_closed_forms"),
+    ("rdp_exponent_without_the_half", [("Decimal(k * k - k) / (2 * sd * sd)", "Decimal(k * k - k) / (sd * sd)", None)], "test_rdp_closed_forms"),
+    ("rdp_binomial_weights_dropped", [("Decimal(comb(alpha, k)) * power(1 - qd, alpha - k)", "power(1 - qd, alpha - k)", None)], "test_rdp_closed_forms"),
+    ("rdp_conversion_divides_by_alpha", [("eps = rdp + math.log(1.0 / delta) / (alpha - 1)", "eps = rdp + math.log(1.0 / delta) / alpha", None)],
+     "test_rdp_epsilon_composition_over_a_batch_size_schedule"),
+    ("rdp_composition_ignores_step_counts", [("rdp = sum(n * rdp_sampled_gaussian(qq, sigma, alpha) for qq, n in zip(q, steps))", "rdp = sum(rdp_sampled_gaussian(qq, sigma, alpha) for qq, n in zip(q, steps))", None)],
+     "test_rdp_epsilon_composition_over_a_batch_size_schedule"),
+    ("rdp_takes_the_worst_order", [("        if eps < best[0]:\n            best = (eps, alpha)", "        if eps > best[0] or best[1] == 0:\n            best = (eps, alpha)", None)],
+     "test_rdp_epsilon_composition_over_a_batch_size_schedule"),
     ("bf16_widening_shift", [("<< np.uint32(16)", "<< np.uint32(15)", None)], "test_bf16_widening_matches_torch"),
 ]
 

@@ -625,6 +625,69 @@ def test_lr_schedule_shape():
 
 
 # ----------------------------------------------------------------------------------------------
+# privacy accounting (Renyi DP of the sampled Gaussian mechanism, composed over a batch-size schedule)
+# ----------------------------------------------------------------------------------------------
+def _renyi_by_quadrature(q, sigma, alpha):
+    """The definition itself: D_alpha(P || Q) = ln E_Q[(P/Q)^alpha] / (alpha - 1) with Q = N(0, sigma^2) and
+    P = (1-q) N(0, sigma^2) + q N(1, sigma^2) (one example changes the clipped, C-normalised sum by at most 1),
+    by the trapezoid rule on a fine grid."""
+    x = np.linspace(-40.0 * sigma, 40.0 * sigma + alpha, 2_000_001)
+    logQ = -0.5 * (x / sigma) ** 2
+    ratio = (1.0 - q) + q * np.exp((2.0 * x - 1.0) / (2.0 * sigma * sigma))      # P/Q pointwise
+    integrand = np.exp(logQ + alpha * np.log(ratio)) / (sigma * math.sqrt(2.0 * math.pi))
+    return math.log(np.trapezoid(integrand, x)) / (alpha - 1)
+
+
+def test_rdp_matches_the_definition_by_quadrature():
+    for q, sigma, alpha in [(0.01, 0.6, 2), (0.01, 0.6, 5), (0.3, 1.0, 3), (0.003, 0.8, 16), (1.0, 1.5, 4), (0.5, 2.0, 9)]:
+        assert math.isclose(orc.rdp_sampled_gaussian(q, sigma, alpha), _renyi_by_quadrature(q, sigma, alpha), rel_tol=1e-7)
+
+
+def test_rdp_closed_forms():
+    # no subsampling: the Gaussian mechanism, alpha / (2 sigma^2)
+    for sigma, alpha in [(0.6, 2), (1.0, 7), (2.5, 64)]:
+        assert math.isclose(orc.rdp_sampled_gaussian(1.0, sigma, alpha), alpha / (2 * sigma * sigma), rel_tol=1e-13)
+    # order 2 by hand: ln(1 + q^2 (e^{1/sigma^2} - 1))
+    for q, sigma in [(0.01, 1.0), (0.25, 0.7)]:
+        assert math.isclose(orc.rdp_sampled_gaussian(q, sigma, 2), math.log1p(q * q * math.expm1(1 / sigma ** 2)), rel_tol=1e-12)
+    assert orc.rdp_sampled_gaussian(0.0, 1.0, 8) == 0.0                      # nothing sampled: nothing revealed
+    # monotone in the sampling rate, the order and 1/sigma
+    e = [orc.rdp_sampled_gaussian(q, 0.8, 8) for q in (1e-4, 1e-3, 1e-2, 1e-1, 1.0)]
+    assert all(a < b for a, b in zip(e, e[1:]))
+    e = [orc.rdp_sampled_gaussian(0.01, 0.8, a) for a in (2, 3, 8, 32)]
+    assert all(a < b for a, b in zip(e, e[1:]))
+    assert orc.rdp_sampled_gaussian(0.01, 0.5, 8) > orc.rdp_sampled_gaussian(0.01, 1.0, 8)
+    for bad in ((-0.1, 1.0, 2), (1.1, 1.0, 2), (0.1, 0.0, 2), (0.1, 1.0, 1)):
+        with pytest.raises(ValueError):
+            orc.rdp_sampled_gaussian(*bad)
+
+
+def test_rdp_epsilon_composition_over_a_batch_size_schedule():
+    n = _schedule_numbers()
+    N, sigma, delta = 346_000_000, 0.6, 2.89e-9          # data-set size and delta as the paper states them (delta = 1/N)
+    sizes = [orc.batch_size_schedule(k * 1875 + 1, n["b_start"], n["b_end"], n["ramp_steps"], n["parts"]) for k in range(5)]
+    q = [b / N for b in sizes]
+    steps = [1875, 1875, 1875, 1875, n["total_steps"] - n["ramp_steps"]]
+    eps, alpha = orc.rdp_epsilon(q, steps, sigma, delta, 64)
+    # the definition of the conversion at the reported order, from the per-step values
+    rdp = sum(s * orc.rdp_sampled_gaussian(qq, sigma, alpha) for qq, s in zip(q, steps))
+    assert math.isclose(eps, rdp + math.log(1 / delta) / (alpha - 1), rel_tol=1e-12)
+    # no other order does better; splitting a phase in two changes nothing; the schedule sits between its extremes
+    for a in range(2, 65):
+        r = sum(s * orc.rdp_sampled_gaussian(qq, sigma, a) for qq, s in zip(q, steps))
+        assert eps <= r + math.log(1 / delta) / (a - 1) + 1e-12
+    eps_split, _ = orc.rdp_epsilon(q + [q[-1]], steps[:-1] + [5000, steps[-1] - 5000], sigma, delta, 64)
+    assert math.isclose(eps, eps_split, rel_tol=1e-12)
+    lo, _ = orc.rdp_epsilon([q[0]], [n["total_steps"]], sigma, delta, 64)
+    hi, _ = orc.rdp_epsilon([q[-1]], [n["total_steps"]], sigma, delta, 64)
+    assert lo < eps < hi
+    # a single Gaussian release (q = 1, one step): min over alpha of alpha/(2 sigma^2) + ln(1/delta)/(alpha-1), on integers
+    e1, a1 = orc.rdp_epsilon([1.0], [1], 4.0, 1e-5, 256)
+    ref = min(a / 32.0 + math.log(1e5) / (a - 1) for a in range(2, 257))
+    assert math.isclose(e1, ref, rel_tol=1e-12) and abs(a1 - (1 + math.sqrt(32 * math.log(1e5)))) <= 1
+
+
+# ----------------------------------------------------------------------------------------------
 # stored reference (written by tests/golden/make_oracle_reference.py from the oracle alone): drift guard
 # ----------------------------------------------------------------------------------------------
 def test_oracle_matches_its_stored_reference():
