@@ -197,8 +197,8 @@ def main():
                      {"whole_step": phase_ms[2] / args.steps, "input_gen_s": t_gen}),
     }
     if not args.no_cpu_baseline:
-        # ~155 GFLOP of fp64 work per BERT-Large example at T=128: a handful of examples is 10-30 s
-        n_ex = args.cpu_examples or max(1, min(B, 16 * 128 // T))
+        # ~155 GFLOP of fp64 work per BERT-Large example at T=128: a few dozen examples are 10-30 s of host time
+        n_ex = args.cpu_examples or max(1, min(B, 32 * 128 // T))
         base, _ = cpu_baseline(layers, cfg, n_ex)
         out["cpu_baseline"] = base
     ctx.close()
