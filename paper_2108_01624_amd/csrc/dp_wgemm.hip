@@ -630,11 +630,31 @@ __global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmBatchArgs b) {
         // wave's have, and every wave has finished reading the stage whose ring slot the newest stage now overwrites
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"((AHEAD - 2) * LPS) : "memory");
         __syncthreads();
-        issue(s_issue, ibuf);
+        load_frags(buf1, 0, fa0, fg0);
+        // The four LDS-filling loads of the newest stage go out one after every second MFMA: issued back to back
+        // right after the barrier by all eight waves they queue up in the address unit, and a wave that waits there
+        // issues no MFMA either.
+        {
+            const int stc = s_issue < nsteps ? s_issue : (nsteps > 0 ? nsteps - 1 : 0);
+            const int soffA = __builtin_amdgcn_readfirstlane(stc * BK * a.d_in * 2);
+            const int soffG = __builtin_amdgcn_readfirstlane(stc * BK * a.d_out * 2);
+#pragma unroll
+            for (int t = 0; t < MI * NI; ++t) {
+                const int i = t / NI, j = t % NI;
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[i], fg1[j], acc[i][j], 0, 0, 0);
+                if (t % 2 == 1) {
+                    const int k = t / 2, jj = k >> 1;
+                    __builtin_amdgcn_sched_barrier(0);
+                    if ((k & 1) == 0)
+                        dma_load16(rA, __builtin_amdgcn_readfirstlane(ldsA[jj] + ibuf * (BK * BM * 2)), voffA[jj], soffA);
+                    else
+                        dma_load16(rG, __builtin_amdgcn_readfirstlane(ldsG[jj] + ibuf * (BK * BN * 2)), voffG[jj], soffG);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
         ++s_issue;
         ibuf = ibuf + 1 == DMA_NS ? 0 : ibuf + 1;
-        load_frags(buf1, 0, fa0, fg0);
-        mma(fa1, fg1);
         if (bias_now) mma_bias(fg1);
         buf = buf1;
         ++my;
