@@ -435,7 +435,8 @@ __global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmBatchArgs b) {
     __shared__ __attribute__((aligned(16))) uint16_t Gs[DMA_NS][BK * BN];
     const WgemmArgs& a = b.base;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: everything derived from it stays in SGPRs
     const int wr = wave / WVN, wc = wave % WVN;
     const int ntiles = a.tiles_m * a.tiles_n;
     const int nunits = b.n_layers * a.nsplit;  // unit = layer * nsplit + split
@@ -575,6 +576,7 @@ __global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmBatchArgs b) {
     // are separate straight-line bodies in nested loops (a two-armed branch around the MFMAs costs the register
     // allocator > 100 spilled VGPRs). 
     int my = 0;      // the stage being multiplied; stages >= nsteps hold zeros
+    int duty_ctr = 0;  // my % duty_mod
     const int spe = a.T / BK;                                  // stages per example
     // plain stages up to the first example start, and the example that starts there
     const int head = (spe - (int)((uint32_t)(k_lo / BK) % (uint32_t)spe)) % spe;
@@ -596,7 +598,8 @@ __global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmBatchArgs b) {
     auto body = [&](auto rescale_tag) {
         constexpr bool RESCALE = decltype(rescale_tag)::value;
         const int buf1 = buf + 1 == DMA_NS ? 0 : buf + 1;
-        const bool bias_now = want_bias && (my % duty_mod) == duty;
+        const bool bias_now = want_bias && duty_ctr == duty;
+        duty_ctr = duty_ctr + 1 == duty_mod ? 0 : duty_ctr + 1;
         load_frags(buf, 1, fa1, fg1);
         if (RESCALE) {
             // factors of 64 examples sit in registers (lane = example mod 64), refilled every 64 examples
