@@ -91,10 +91,10 @@ dp_status dp_sqnorms_dense(dp_ctx* ctx, const void* A, const void* G, dp_dtype d
 
 /* n_layers dense layers of one shape in one call: the result is that of n_layers calls of dp_sqnorms_dense
  * with the same arguments (each layer's norms added to sqnorms[i], layers in index order).  On the Gram path
- * with T <= 128 and widths that are multiples of 64 the layers share launches of up to 16 layers, which keeps
- * the memory pipeline full across examples; their per-layer norms pass through the library workspace
- * (4 * B * 16 bytes) and are added in layer order.  A, G are HOST arrays of n_layers device pointers, read
- * during the call only. */
+ * with widths that are multiples of 64 the layers share launches of up to 16 layers, which keeps the memory
+ * pipeline full across examples; their per-layer norms (for T > 128: per layer and 128 x 128 block pair) pass
+ * through the library workspace and are added in a fixed order (DP_ERR_WORKSPACE if they do not fit).
+ * A, G are HOST arrays of n_layers device pointers, read during the call only. */
 dp_status dp_sqnorms_dense_batched(dp_ctx* ctx, int n_layers, const void* const* A, const void* const* G, dp_dtype dtype,
                                    int B, int T, int d_in, int d_out, int has_bias, dp_path path, float* sqnorms);
 
