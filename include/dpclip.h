@@ -118,7 +118,7 @@ dp_status dp_sqnorms_embedding(dp_ctx* ctx, const int32_t* ids, const void* G, d
  * ------------------------------------------------------------------------------------------------- */
 
 /* sum_W[p,q] += sum_i c_i sum_t A[i,t,p] G[i,t,q];  sum_b[q] += sum_i c_i sum_t G[i,t,q] (sum_b may be NULL).
- * DP_BF16, accumulation in fp32: for T a multiple of 32 and widths >= 256 the operands enter the matrix-core
+ * DP_BF16, accumulation in fp32: for T a multiple of 64 and widths >= 256 the operands enter the matrix-core
  * contraction unscaled (exact bf16 products) and the accumulators are rescaled by c_prev / c_next where the
  * example changes; for other shapes the clip factor multiplies G in fp32 and the product is rounded back to
  * bf16 (round-to-nearest-even) before the contraction (relative error of the sum about 1e-3). */

@@ -398,8 +398,10 @@ __global__ __launch_bounds__(64 * WVM * WVN) void wgemm_bf16_kernel(WgemmArgs a)
 //    stage it is about to publish and keeps the later stages in flight.  Ring of five 32 KiB stages: all of the CU's LDS.
 //  * The clip factor is not applied to the operands at all.  All rows of a stage belong to one example, so the
 //    accumulators carry sum_{j<=i} (c_j / c_i) A_j^T G_j: when the stage's example changes they are multiplied
-//    by c_prev / c_next (128 + 32 VALU multiplies per wave per example), and by the last c at the end.  The
-//    bf16 products are exact in fp32, so this path is more accurate than rounding c*g to bf16.
+//    by c_prev / c_next (128 + 32 VALU multiplies per wave per example, spread over the two half-iterations
+//    around the boundary), and by the last c at the end.  The bf16 products are exact in fp32, so this path is
+//    more accurate than rounding c*g to bf16.  Needs whole examples of at least two stages per row split
+//    (T a multiple of 64; the host aligns the splits); other shapes take the register-staged kernel.
 //  * Bias gradient: column sums of G are one more MFMA with an all-ones A fragment.  Every wave takes that duty
 //    for one stage in 2*tiles_m (tile row pm, wave row wr: stages s with s % (2*tiles_m) == 2*pm + wr), so the
 //    extra work is spread evenly; the partial sums of (split, pm, wr) are added in a fixed order afterwards.
@@ -546,19 +548,8 @@ __global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmBatchArgs b) {
 #pragma unroll
         for (int j = 0; j < NI; ++j) bacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, fg[j], bacc[j], 0, 0, 0);
     };
-    auto clip_of_stage = [&](int st) -> float {
-        long k = k_lo + (long)st * BK;
-        if (k >= a.K) k = a.K - 1;
-        // scalar load (the index is uniform): a vector load here would make the compiler drain every
-        // LDS-filling load in flight before it reads the value
-        const uint32_t off = __builtin_amdgcn_readfirstlane(((uint32_t)k / (uint32_t)a.T) * 4u);
-        float n;
-        asm volatile("s_load_dword %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=s"(n) : "s"(a.sqnorms), "s"(off) : "memory");
-        return dp_clip_factor(n, a.C);
-    };
-
     bf16x8_t fa0[MI], fg0[NI], fa1[MI], fg1[NI];
-    float c_cur = nsteps > 0 ? clip_of_stage(0) : 1.f;
+    float c_cur = 1.f;  // clip factor of the example being accumulated (set by the example's first stage)
 
     // prologue: DMA_NS - 1 stages in flight; publish stage 0
     constexpr int AHEAD = DMA_NS - 1;  // the newest stage in flight is AHEAD stages past the one being multiplied
@@ -570,17 +561,11 @@ __global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmBatchArgs b) {
     int ibuf = AHEAD; // ring slot the next load fills
     load_frags(buf, 0, fa0, fg0);
 
-    // One loop iteration = one stage = one barrier.  Iterations that start an example (RESCALE) multiply the
-    // accumulators by c_prev / c_next tile by tile, each tile's 16 multiplies directly before its MFMA, so that the
-    // matrix pipe works on tile t while the VALU rescales tile t+1; all other iterations are plain.  The two kinds
-    // are separate straight-line bodies in nested loops (a two-armed branch around the MFMAs costs the register
-    // allocator > 100 spilled VGPRs). 
+    // One loop iteration = one stage = one barrier.
     int my = 0;      // the stage being multiplied; stages >= nsteps hold zeros
     int duty_ctr = 0;  // my % duty_mod
-    const int spe = a.T / BK;                                  // stages per example
-    // plain stages up to the first example start, and the example that starts there
-    const int head = (spe - (int)((uint32_t)(k_lo / BK) % (uint32_t)spe)) % spe;
-    int ex_run = (int)((uint32_t)(k_lo / BK + head) / (uint32_t)spe);
+    const int spe = a.T / BK;                                  // stages per example (>= 2)
+    int ex_run = (int)((uint32_t)k_lo / (uint32_t)a.T);        // the next example to start (row splits begin on examples)
     const int nex = (int)(a.K / a.T);
     // lane l: clip factor c_e of example e = (ex & ~63) + l and the rescaling ratio c_{e-1} / c_e that applies when
     // example e starts.  Two plain loads per 64 examples; the compiler's wait for them also waits for the
@@ -595,36 +580,43 @@ __global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmBatchArgs b) {
     };
     if (nsteps > 0) load_factors(ex_run);
     int s_issue = AHEAD;
-    auto body = [&](auto rescale_tag) {
-        constexpr bool RESCALE = decltype(rescale_tag)::value;
+    // Rescaling at an example boundary is spread over the two half-iterations around it, so that the 128 multiplies
+    // hide behind 16 MFMAs instead of 8: in the second half of the example's last stage (PRE) a tile is multiplied two
+    // MFMAs after its last MFMA of that example went out (tiles 0..5), the remaining tiles (6, 7) directly before their
+    // first MFMA of the next example (POST).  Every stage kind is a straight-line body of its own (a two-armed branch
+    // around the MFMAs costs the register allocator > 100 spilled VGPRs).
+    constexpr int PLAIN = 0, POST = 1, PRE = 2;
+    float ratio = 1.f;  // c_prev / c_next of the boundary being worked on (set in PRE, used up in POST)
+    auto scale_tile = [&](int t) {
+        const int i = t / NI, j = t % NI;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] *= ratio;
+    };
+    auto body = [&](auto kind_tag) {
+        constexpr int KIND = decltype(kind_tag)::value;
         const int buf1 = buf + 1 == DMA_NS ? 0 : buf + 1;
         const bool bias_now = want_bias && duty_ctr == duty;
         duty_ctr = duty_ctr + 1 == duty_mod ? 0 : duty_ctr + 1;
         load_frags(buf, 1, fa1, fg1);
-        if (RESCALE) {
-            // factors of 64 examples sit in registers (lane = example mod 64), refilled every 64 examples
-            if ((ex_run & 63) == 0) load_factors(ex_run);
+        if (KIND == POST) {
+            // first stage of example ex_run: finish the rescaling PRE began, take over the example's factor
             const int el = __builtin_amdgcn_readfirstlane(ex_run & 63);
-            const float ratio = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, rvec), el));
             c_cur = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cvec), el));
             ++ex_run;
 #pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int j = 0; j < NI; ++j) {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[i][j][r] *= ratio;
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[i], fg0[j], acc[i][j], 0, 0, 0);
+            for (int t = 0; t < MI * NI; ++t) {
+                const int i = t / NI, j = t % NI;
+                if (t >= MI * NI - 2) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    scale_tile(t);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[i], fg0[j], acc[i][j], 0, 0, 0);
+            }
 #pragma unroll
             for (int j = 0; j < NI; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) bacc[j][r] *= ratio;
-#pragma unroll
-            for (int t = 0; t < MI * NI; ++t) {
-                __builtin_amdgcn_sched_group_barrier(0x002, 16, 0);  // 16 VALU
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
-            }
         } else {
             mma(fa0, fg0);
         }
@@ -634,6 +626,12 @@ __global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmBatchArgs b) {
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"((AHEAD - 2) * LPS) : "memory");
         __syncthreads();
         load_frags(buf1, 0, fa0, fg0);
+        if (KIND == PRE) {
+            // last stage of example ex_run - 1; the factors of 64 examples sit in registers (lane = example mod 64)
+            if ((ex_run & 63) == 0) load_factors(ex_run);
+            const int el = __builtin_amdgcn_readfirstlane(ex_run & 63);
+            ratio = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, rvec), el));
+        }
         // The four LDS-filling loads of the newest stage go out one after every second MFMA: issued back to back
         // right after the barrier by all eight waves they queue up in the address unit, and a wave that waits there
         // issues no MFMA either.
@@ -654,6 +652,11 @@ __global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmBatchArgs b) {
                         dma_load16(rG, __builtin_amdgcn_readfirstlane(ldsG[jj] + ibuf * (BK * BN * 2)), voffG[jj], soffG);
                     __builtin_amdgcn_sched_barrier(0);
                 }
+                if (KIND == PRE && t >= 2) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    scale_tile(t - 2);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
         }
         ++s_issue;
@@ -662,18 +665,16 @@ __global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmBatchArgs b) {
         buf = buf1;
         ++my;
     };
-    int left = nsteps;
-    {
-        int n = head < left ? head : left;
-        left -= n;
-        for (int q = 0; q < n; ++q) body(std::false_type{});
+    // The unit's rows are whole examples (the host aligns row splits to examples), at least two stages each.
+    const int n_ex_unit = nsteps / spe;
+    for (int e = 0; e + 1 < n_ex_unit; ++e) {
+        body(std::integral_constant<int, POST>{});
+        for (int q = 0; q < spe - 2; ++q) body(std::integral_constant<int, PLAIN>{});
+        body(std::integral_constant<int, PRE>{});
     }
-    while (left > 0) {
-        body(std::true_type{});
-        --left;
-        int n = spe - 1 < left ? spe - 1 : left;
-        left -= n;
-        for (int q = 0; q < n; ++q) body(std::false_type{});
+    if (n_ex_unit > 0) {
+        body(std::integral_constant<int, POST>{});
+        for (int q = 0; q < spe - 1; ++q) body(std::integral_constant<int, PLAIN>{});
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing may still be writing LDS when the workgroup ends
 
@@ -839,7 +840,7 @@ static long choose_nsplit(long total_tiles, long ksteps) {
 dp_status dpk_weighted_gemm_batched(dp_ctx* ctx, int n, const void* const* A, const void* const* G, dp_dtype dt, int B,
                                     int T, int d_in, int d_out, const float* sqnorms, float C, float* const* sum_W,
                                     float* const* sum_b) {
-    const bool dma = dt == DP_BF16 && d_in > 0 && use_dma_path(tile_cfg(d_in, d_out), T % BK == 0);
+    const bool dma = dt == DP_BF16 && d_in > 0 && use_dma_path(tile_cfg(d_in, d_out), T % (2 * BK) == 0);
     if (!dma) {
         for (int l = 0; l < n; ++l) {
             dp_status st = dpk_weighted_gemm(ctx, A[l], G[l], dt, B, T, d_in, d_out, sqnorms, C, sum_W[l], sum_b ? sum_b[l] : nullptr);
@@ -881,7 +882,8 @@ dp_status dpk_weighted_gemm_batched(dp_ctx* ctx, int n, const void* const* A, co
             if (part) break;
             nsplit = nsplit > 8 ? nsplit - 8 : nsplit / 2;  // shrink to what the workspace holds
         }
-        const long steps_per = (ksteps + nsplit - 1) / nsplit;
+        const long spe = T / BK;  // row splits begin on examples: the kernel rescales across example boundaries only
+        const long steps_per = ((ksteps + nsplit - 1) / nsplit + spe - 1) / spe * spe;
         a.rows_per_split = steps_per * BK;
         if (!range_ok(a.rows_per_split, d_in, d_out)) {
             DP_SET_ERR(ctx, "dp_clip_accumulate_dense: workspace too small to split %ld rows", K);
@@ -993,7 +995,7 @@ dp_status dpk_weighted_gemm(dp_ctx* ctx, const void* A, const void* G, dp_dtype 
         if (st != DP_OK) return st;
         return dpk_colstat_sums(ctx, nullptr, G, dt, B, T, d_out, ctx->cbuf, nullptr, sum_b);
     }
-    if (use_dma_path(tile_cfg(d_in, d_out), T % BK == 0))
+    if (use_dma_path(tile_cfg(d_in, d_out), T % (2 * BK) == 0))
         return dpk_weighted_gemm_batched(ctx, 1, &A, &G, dt, B, T, d_in, d_out, sqnorms, C, &sum_W, &sum_b);
     const bool big = big_tile(d_in, d_out);
     const int BM = big ? 256 : 128, BN = BM;

@@ -272,6 +272,9 @@ ACC_SHAPES = [
     ("bf16", 64, 128, 256, 256),   # 8192 rows: several XCD-interleaved splits
     ("bf16", 3, 50, 512, 264),     # rows not a multiple of the staged tile height
     ("bf16", 2, 7, 8, 8),
+    ("bf16", 5, 128, 256, 256),    # 5 examples over 3 row splits (2 + 2 + 1 whole examples)
+    ("bf16", 7, 64, 256, 512),     # two stages per example: every stage starts or ends one
+    ("bf16", 3, 192, 320, 256),    # six stages per example, ragged tile row
 ]
 
 
