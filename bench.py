@@ -32,6 +32,9 @@ def parse():
                          "examples accumulated, one update; the micro-batch buffers are reused), others for comparison")
     ap.add_argument("--path", default="auto", choices=["auto", "gram", "materialise"],
                     help="force the dense-layer norm path of pass 1 (comparison runs; auto is what the metric uses)")
+    ap.add_argument("--share-qkv", action="store_true",
+                    help="comparison run: the query, key and value layers of a block are given ONE input tensor, as in a "
+                         "real attention block (the metric's workload keeps an input tensor per layer)")
     ap.add_argument("--batch", type=int, default=0, help="override the micro-batch size (parity/debug only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-examples", type=int, default=0, help="examples in the oracle sample (0 = auto)")
@@ -89,7 +92,18 @@ def main():
                                      grad_std=cfg["grad_std"], data_seed=cfg["data_seed"], device=dev)
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
-    in_bytes = sum(t.numel() * t.element_size() for l in layers for k, t in l.items() if k in ("A", "G", "X", "ids"))
+    if args.share_qkv:
+        by_name = {l["name"]: l for l in layers}
+        for name, l in by_name.items():
+            if name.endswith(".k") or name.endswith(".v"):
+                l["A"] = by_name[name[:-2] + ".q"]["A"]
+        torch.cuda.empty_cache()
+    seen, in_bytes = set(), 0
+    for l in layers:
+        for k, t in l.items():
+            if k in ("A", "G", "X", "ids") and t.data_ptr() not in seen:
+                seen.add(t.data_ptr())
+                in_bytes += t.numel() * t.element_size()
 
     ctx = pkg.Context()
     run = pkg.StepRunner(ctx, manifest, B, device=dev)
@@ -177,7 +191,7 @@ def main():
                                f"micro-batch B={B}, seq T={T}, bf16 inputs / fp32 accumulation, C={cfg['C']}; "
                                f"one step = norms + clip-accumulate over all layers + noise/AdamW over all params"
                                if args.workload != "C2" else f"C2: BERT-Base-shaped stack, B={B}, T={T}",
-                   "params": int(run.P), "micro_batch": B, "micro_batches_per_step": n_micro, "seq_len": T, "norm_path": args.path,
+                   "params": int(run.P), "micro_batch": B, "micro_batches_per_step": n_micro, "seq_len": T, "norm_path": args.path, "shared_qkv_input": bool(args.share_qkv),
                    "input_bytes": int(in_bytes)},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,

@@ -98,6 +98,16 @@ dp_status dp_sqnorms_dense(dp_ctx* ctx, const void* A, const void* G, dp_dtype d
 dp_status dp_sqnorms_dense_batched(dp_ctx* ctx, int n_layers, const void* const* A, const void* const* G, dp_dtype dtype,
                                    int B, int T, int d_in, int d_out, int has_bias, dp_path path, float* sqnorms);
 
+/* Layers that share their input (the query, key and value projections of an attention block read the same
+ * activations): n_groups groups of n_out same-shaped layers, group g's layers having input A[g] and output
+ * gradients G[g * n_out + j], j < n_out.  The result is that of n_groups * n_out calls of dp_sqnorms_dense (every
+ * layer with its own bias if has_bias).  Because sum_j <A A^T (+1), G_j G_j^T> = <A A^T (+1), sum_j G_j G_j^T>, the
+ * Gram path (T <= 128, widths multiples of 64, n_out 2 or 3) forms A A^T once per group and reads A once: a
+ * third fewer bytes and matrix operations for a query/key/value group.  Other shapes are served layer by layer.
+ * A (n_groups entries) and G (n_groups * n_out entries) are HOST arrays of device pointers, read during the call. */
+dp_status dp_sqnorms_dense_shared(dp_ctx* ctx, int n_groups, const void* const* A, int n_out, const void* const* G,
+                                  dp_dtype dtype, int B, int T, int d_in, int d_out, int has_bias, float* sqnorms);
+
 /* LayerNorm y = gamma * xhat + beta, Xhat = the NORMALISED activations:
  * sqnorms[i] += sum_j (sum_t G[i,t,j] Xhat[i,t,j])^2 + sum_j (sum_t G[i,t,j])^2. */
 dp_status dp_sqnorms_layernorm(dp_ctx* ctx, const void* Xhat, const void* G, dp_dtype dtype, int B, int T, int d,

@@ -26,6 +26,7 @@ SIGNATURES = {
     "dp_last_error": [c_void_p],
     "dp_sqnorms_dense": [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p],
     "dp_sqnorms_dense_batched": [c_void_p, c_int, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p],
+    "dp_sqnorms_dense_shared": [c_void_p, c_int, c_void_p, c_int, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p],
     "dp_sqnorms_layernorm": [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_void_p],
     "dp_sqnorms_embedding": [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p],
     "dp_clip_factors": [c_void_p, c_void_p, c_int, c_float, c_void_p],
@@ -175,6 +176,26 @@ def dp_sqnorms_dense_batched(ctx, As, Gs, has_bias, path, sqnorms):
     st = load_library().dp_sqnorms_dense_batched(ctx, n, arr([_ptr(t) for t in As]), arr([_ptr(t) for t in Gs]),
                                                  _dtype_of(As[0]), B, T, d_in, d_out, int(has_bias), int(path), _f32(sqnorms))
     _check(ctx, st, "dp_sqnorms_dense_batched")
+
+
+def dp_sqnorms_dense_shared(ctx, As, Gs, has_bias, sqnorms):
+    """As: one input tensor per group; Gs: per group a list of the output-gradient tensors of the layers sharing it."""
+    ng, n_out = len(As), len(Gs[0])
+    B, T, d_in = As[0].shape
+    d_out = Gs[0][0].shape[-1]
+    flat = []
+    for a, gs in zip(As, Gs):
+        if tuple(a.shape) != (B, T, d_in) or len(gs) != n_out or a.dtype != As[0].dtype:
+            raise ValueError("all groups must share one shape, dtype and layer count")
+        for g in gs:
+            if tuple(g.shape) != (B, T, d_out) or g.dtype != a.dtype:
+                raise ValueError("all layers of a call must share one shape and dtype")
+            flat.append(g)
+    pa = (c_void_p * ng)(*[_ptr(t) for t in As])
+    pg = (c_void_p * len(flat))(*[_ptr(t) for t in flat])
+    st = load_library().dp_sqnorms_dense_shared(ctx, ng, pa, n_out, pg, _dtype_of(As[0]), B, T, d_in, d_out, int(has_bias),
+                                                _f32(sqnorms))
+    _check(ctx, st, "dp_sqnorms_dense_shared")
 
 
 def dp_sqnorms_layernorm(ctx, Xhat, G, sqnorms):

@@ -308,6 +308,30 @@ dp_status dp_sqnorms_dense_batched(dp_ctx* ctx, int n_layers, const void* const*
     return DP_OK;
 }
 
+dp_status dp_sqnorms_dense_shared(dp_ctx* ctx, int n_groups, const void* const* A, int n_out, const void* const* G,
+                                  dp_dtype dtype, int B, int T, int d_in, int d_out, int has_bias, float* sqnorms) {
+    REQUIRE_CTX(ctx);
+    TRY(check_dtype(ctx, dtype));
+    TRY(check_bt(ctx, B, T));
+    if (n_groups < 0 || n_out < 1 || d_in < 0 || d_out < 0) FAIL(ctx, DP_ERR_SHAPE, "negative count or width");
+    if (n_groups == 0) return DP_OK;
+    if (!A || !G) FAIL(ctx, DP_ERR_NULL, "a pointer table is NULL");
+    for (int g = 0; g < n_groups; ++g) {
+        TRY(check_tensor(ctx, "A[g]", A[g], dtype, d_in));
+        for (int j = 0; j < n_out; ++j) TRY(check_tensor(ctx, "G[g][j]", G[(size_t)g * n_out + j], dtype, d_out));
+    }
+    TRY(check_f32(ctx, "sqnorms", sqnorms));
+    if (B == 0 || T == 0 || d_out == 0) return DP_OK;
+    dp_path path = DP_PATH_GRAM;
+    if (d_in > 0) dp_choose_path(T, d_in, n_out * d_out, dtype, &path);  // one A A^T serves n_out output Grams
+    if (d_in > 0 && path == DP_PATH_GRAM)
+        return dpk_gram_sqnorms_shared(ctx, n_groups, A, n_out, G, dtype, B, T, d_in, d_out, has_bias, sqnorms);
+    for (int g = 0; g < n_groups; ++g)
+        for (int j = 0; j < n_out; ++j)
+            TRY(dp_sqnorms_dense(ctx, A[g], G[(size_t)g * n_out + j], dtype, B, T, d_in, d_out, has_bias, DP_PATH_AUTO, sqnorms));
+    return DP_OK;
+}
+
 dp_status dp_sqnorms_layernorm(dp_ctx* ctx, const void* Xhat, const void* G, dp_dtype dtype, int B, int T, int d,
                                float* sqnorms) {
     REQUIRE_CTX(ctx);

@@ -160,6 +160,8 @@ dp_status dpk_noise_adamw(dp_ctx*, float* params, float* m, float* v, float* sum
 
 dp_status dpk_gram_sqnorms_batched(dp_ctx*, int n_layers, const void* const* A, const void* const* G, dp_dtype, int B, int T,
                                    int d_in, int d_out, int has_bias, float* sqnorms);
+dp_status dpk_gram_sqnorms_shared(dp_ctx*, int n_groups, const void* const* A, int n_out, const void* const* G, dp_dtype, int B,
+                                  int T, int d_in, int d_out, int has_bias, float* sqnorms);
 dp_status dpk_gram_sqnorms(dp_ctx*, const void* A, const void* G, dp_dtype, int B, int T, int d_in, int d_out,
                            int has_bias, float* sqnorms);
 dp_status dpk_materialise_sqnorms(dp_ctx*, const void* A, const void* G, dp_dtype, int B, int T, int d_in, int d_out,

@@ -212,6 +212,12 @@ constexpr int GRAM_MAX_BATCH = 16;
 struct GramBatch {
     const uint16_t* A[GRAM_MAX_BATCH];
     const uint16_t* G[GRAM_MAX_BATCH];
+    // layers that share their input (Q, K, V of one block): entry l stands for n_out layers with input A[l] and
+    // output gradients G[l], G2[l], G3[l].  Their norms add up to <A A^T (+1), sum_j G_j G_j^T>, so A A^T is formed
+    // once and the G_j chunks all go into one accumulator (T <= 128 kernel only).
+    const uint16_t* G2[GRAM_MAX_BATCH];
+    const uint16_t* G3[GRAM_MAX_BATCH];
+    int n_out;
     int n_layers;
     int B;
 };
@@ -232,13 +238,15 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gram_dma_kernel(GramBatch gb,
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wr = wave >> 1, wc = wave & 1;
     const bool active = wr <= wc;  // the lower-left quadrant mirrors the upper-right one
-    const int nchA = d_in / GDK, nch = nchA + d_out / GDK;
+    const int nchA = d_in / GDK, nchG1 = d_out / GDK, nch = nchA + gb.n_out * nchG1;
     // chunk position c of row r holds global chunk c ^ swz(r): 16 consecutive rows -> 64 distinct banks
     auto swz = [](int r) { return CPR == 8 ? (r >> 1) & 7 : r & 15; };
 
     // rows >= T of the panel lie outside the example's byte range and read as zero
     const gram_i32x4 rA = gram_rsrc(A + (size_t)i * T * d_in, (uint32_t)((size_t)T * d_in * 2));
     const gram_i32x4 rG = gram_rsrc(G + (size_t)i * T * d_out, (uint32_t)((size_t)T * d_out * 2));
+    const gram_i32x4 rG2 = gram_rsrc((gb.n_out > 1 ? gb.G2[layer] : G) + (size_t)i * T * d_out, (uint32_t)((size_t)T * d_out * 2));
+    const gram_i32x4 rG3 = gram_rsrc((gb.n_out > 2 ? gb.G3[layer] : G) + (size_t)i * T * d_out, (uint32_t)((size_t)T * d_out * 2));
     // load j of this wave fills rows (LPS*wave + j)*RPI .. : lane l -> row + l/CPR, chunk position l%CPR
     int voffA[LPS], voffG[LPS];
     uint32_t ldsoff[LPS];
@@ -253,13 +261,17 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gram_dma_kernel(GramBatch gb,
     int ibuf = 0;  // buffer of the next stage to issue
     auto issue = [&](int st) {
         const bool isA = st < nchA;
-        const int soff = __builtin_amdgcn_readfirstlane((isA ? st : st - nchA) * GDK * 2);
+        const int cgi = st - nchA;                                             // chunk index over all output gradients
+        const int which = cgi >= 2 * nchG1 ? 2 : (cgi >= nchG1 ? 1 : 0);       // which of the (up to three) tensors
+        const int soff = __builtin_amdgcn_readfirstlane((isA ? st : cgi - which * nchG1) * GDK * 2);
 #pragma unroll
         for (int j = 0; j < LPS; ++j) {
             const uint32_t dst = __builtin_amdgcn_readfirstlane(ldsoff[j] + ibuf * (STAGE * 2));
             if (isA) gram_dma16(rA, dst, voffA[j], soff);
-            else if (st < nch) gram_dma16(rG, dst, voffG[j], soff);
-            else gram_dma16(rG, dst, voffG[j], 0x7FFFFFF0);  // past the end: reads zeros, keeps the load count uniform
+            else if (st >= nch) gram_dma16(rG, dst, voffG[j], 0x7FFFFFF0);  // past the end: reads zeros, keeps the load count uniform
+            else if (which == 0) gram_dma16(rG, dst, voffG[j], soff);
+            else if (which == 1) gram_dma16(rG2, dst, voffG[j], soff);
+            else gram_dma16(rG3, dst, voffG[j], soff);
         }
         ibuf = ibuf + 1 == NS ? 0 : ibuf + 1;
     };
@@ -611,8 +623,10 @@ dp_status dpk_gram_sqnorms_batched(dp_ctx* ctx, int n_layers, const void* const*
             for (int l = 0; l < GRAM_MAX_BATCH; ++l) {
                 gb.A[l] = (const uint16_t*)A[l0 + (l < nl ? l : 0)];
                 gb.G[l] = (const uint16_t*)G[l0 + (l < nl ? l : 0)];
+                gb.G2[l] = gb.G3[l] = gb.G[l];
             }
             gb.n_layers = nl;
+            gb.n_out = 1;
             gb.B = B;
             dp_status st = gram_pairs_launch(ctx, gb, T, d_in, d_out, has_bias, sqnorms);
             if (st != DP_OK) return st;
@@ -632,8 +646,10 @@ dp_status dpk_gram_sqnorms_batched(dp_ctx* ctx, int n_layers, const void* const*
         for (int l = 0; l < GRAM_MAX_BATCH; ++l) {
             gb.A[l] = (const uint16_t*)A[l0 + (l < nl ? l : 0)];
             gb.G[l] = (const uint16_t*)G[l0 + (l < nl ? l : 0)];
+            gb.G2[l] = gb.G3[l] = gb.G[l];
         }
         gb.n_layers = nl;
+        gb.n_out = 1;
         gb.B = B;
         const double bytes = 2.0 * (double)B * T * ((double)d_in + d_out) * nl;
         if (nl == 1) {
@@ -650,6 +666,52 @@ dp_status dpk_gram_sqnorms_batched(dp_ctx* ctx, int n_layers, const void* const*
         dp_status st = gram_dma_launch(ctx, gb, T, d_in, d_out, has_bias, part, bytes);
         if (st != DP_OK) return st;
         st = dpk_finish_partials(ctx, part, B, nl, sqnorms);   // layers added in index order
+        if (st != DP_OK) return st;
+    }
+    return DP_OK;
+}
+
+// n_groups groups of n_out (2 or 3) same-shaped layers, the layers of a group sharing their input A[g]; G is
+// group-major: G[g * n_out + j].
+dp_status dpk_gram_sqnorms_shared(dp_ctx* ctx, int n_groups, const void* const* A, int n_out, const void* const* G,
+                                  dp_dtype dt, int B, int T, int d_in, int d_out, int has_bias, float* sqnorms) {
+    if (dt != DP_BF16 || n_out < 2 || n_out > 3 || !gram_dma_ok(T, d_in, d_out) ||
+        (long)B * GRAM_MAX_BATCH > 0x7FFFFFFFl) {
+        for (int g = 0; g < n_groups; ++g)
+            for (int j = 0; j < n_out; ++j) {
+                dp_status st = dpk_gram_sqnorms(ctx, A[g], G[(size_t)g * n_out + j], dt, B, T, d_in, d_out, has_bias, sqnorms);
+                if (st != DP_OK) return st;
+            }
+        return DP_OK;
+    }
+    for (int g0 = 0; g0 < n_groups; g0 += GRAM_MAX_BATCH) {
+        const int ng = n_groups - g0 < GRAM_MAX_BATCH ? n_groups - g0 : GRAM_MAX_BATCH;
+        GramBatch gb;
+        for (int l = 0; l < GRAM_MAX_BATCH; ++l) {
+            const size_t g = (size_t)g0 + (l < ng ? l : 0);
+            gb.A[l] = (const uint16_t*)A[g];
+            gb.G[l] = (const uint16_t*)G[g * n_out];
+            gb.G2[l] = (const uint16_t*)G[g * n_out + 1];
+            gb.G3[l] = (const uint16_t*)G[g * n_out + (n_out > 2 ? 2 : 1)];
+        }
+        gb.n_layers = ng;
+        gb.n_out = n_out;
+        gb.B = B;
+        const double bytes = 2.0 * (double)B * T * ((double)d_in + (double)n_out * d_out) * ng;
+        if (ng == 1) {
+            dp_status st = gram_dma_launch(ctx, gb, T, d_in, d_out, has_bias, sqnorms, bytes);
+            if (st != DP_OK) return st;
+            continue;
+        }
+        dp_ws_alloc ws(ctx);
+        float* part = ws.get<float>((size_t)B * ng);
+        if (!part) {
+            DP_SET_ERR(ctx, "workspace too small for %d x %d norm partials", B, ng);
+            return DP_ERR_WORKSPACE;
+        }
+        dp_status st = gram_dma_launch(ctx, gb, T, d_in, d_out, has_bias, part, bytes);
+        if (st != DP_OK) return st;
+        st = dpk_finish_partials(ctx, part, B, ng, sqnorms);
         if (st != DP_OK) return st;
     }
     return DP_OK;
@@ -679,8 +741,10 @@ dp_status dpk_gram_sqnorms(dp_ctx* ctx, const void* A, const void* G, dp_dtype d
         for (int l = 0; l < GRAM_MAX_BATCH; ++l) {
             gb.A[l] = (const uint16_t*)A;
             gb.G[l] = (const uint16_t*)G;
+            gb.G2[l] = gb.G3[l] = gb.G[l];
         }
         gb.n_layers = 1;
+        gb.n_out = 1;
         gb.B = B;
         if (T > GB) return gram_pairs_launch(ctx, gb, T, d_in, d_out, has_bias, sqnorms);
         return gram_dma_launch(ctx, gb, T, d_in, d_out, has_bias, sqnorms, bytes);

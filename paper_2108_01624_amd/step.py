@@ -60,7 +60,19 @@ class StepRunner:
             else:
                 ctx.sqnorms_embedding(l["ids"], l["G"], l["V"], l["distinct"], n)
         for key, ls in groups.items():
-            ctx.sqnorms_dense_batched([l["A"] for l in ls], [l["G"] for l in ls], key[3], path, n)
+            # layers reading the very same input tensor (query / key / value projections) share its Gram matrix
+            by_input = {}
+            for l in ls:
+                by_input.setdefault(l["A"].data_ptr(), []).append(l)
+            shared = [v for v in by_input.values() if len(v) in (2, 3)] if path == B_.DP_PATH_AUTO else []
+            for width in (3, 2):
+                sel = [v for v in shared if len(v) == width]
+                if sel:
+                    ctx.sqnorms_dense_shared([v[0]["A"] for v in sel], [[l["G"] for l in v] for v in sel], key[3], n)
+            taken = {id(l) for v in shared for l in v}
+            rest = [l for l in ls if id(l) not in taken]
+            if rest:
+                ctx.sqnorms_dense_batched([l["A"] for l in rest], [l["G"] for l in rest], key[3], path, n)
         return n
 
     def pass2(self, layers, C, batch_dense=True):

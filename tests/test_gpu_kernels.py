@@ -603,6 +603,43 @@ def test_sqnorms_dense_batched(dp, n, B, T, d_in, d_out, has_bias):
     np.testing.assert_allclose(host(one), host(seq), rtol=1e-6)
 
 
+@pytest.mark.parametrize("ng,n_out,B,T,d_in,d_out,has_bias", [(2, 3, 5, 128, 256, 128, True), (1, 2, 3, 64, 64, 192, False),
+                                                               (18, 3, 2, 32, 64, 64, True), (2, 3, 2, 300, 128, 128, True),
+                                                               (1, 3, 4, 100, 72, 136, True)])
+def test_sqnorms_dense_shared_input(dp, ng, n_out, B, T, d_in, d_out, has_bias):
+    """Groups of layers reading one input (query / key / value): the norms are those of ng * n_out separate layers
+    (the oracle knows nothing of the sharing); fast-path shapes, more than 16 groups, and per-layer fallbacks."""
+    As = [gen((B, T, d_in), 1.0, 600 + g, "bf16") for g in range(ng)]
+    Gs = [[gen((B, T, d_out), 0.1, 640 + 4 * g + j, "bf16") for j in range(n_out)] for g in range(ng)]
+    ref = sum(orc.sqnorms_dense(As[g], Gs[g][j], has_bias) for g in range(ng) for j in range(n_out))
+    A_d = [to_dev(a) for a in As]
+    G_d = [[to_dev(x) for x in gs] for gs in Gs]
+    out = torch.full((B,), 2.0, dtype=torch.float32, device=DEV)
+    dp.sqnorms_dense_shared(A_d, G_d, has_bias, out)
+    dp.sync()
+    assert_norms_close(host(out).astype(np.float64) - 2.0, ref, 1e-4, "shared input")
+
+
+def test_step_runner_uses_shared_inputs(dp):
+    """A manifest whose q/k/v layers are handed the same input tensor gives the norms of the separate-layer definition."""
+    import paper_2108_01624_amd as pkg
+
+    man = syn.bert_manifest(1, 128, 256)
+    B, T = 4, 128
+    layers = syn.device_layer_inputs(man, B, T, dtype="bf16", act_std=1.0, grad_std=1e-2, data_seed=77, device=DEV)
+    q, k, v = [l for l in layers if l["kind"] == "dense"][:3]
+    k["A"] = q["A"]
+    v["A"] = q["A"]
+    run = pkg.StepRunner(dp, man, B, device=DEV)
+    n = run.pass1(layers)
+    dp.sync()
+    n_ref = orc.microbatch_sqnorms(syn.host_layer_slice(layers, range(B)))
+    assert_norms_close(host(n), n_ref, 1e-4, "norms with shared q/k/v input")
+    n_sep = host(run.pass1(layers, batch_dense=False)).copy()
+    dp.sync()
+    np.testing.assert_allclose(host(n), n_sep, rtol=1e-5)
+
+
 # ------------------------------------------------------------------------------------------------
 # Philox against an independent library (needs the HIP runtime, hence a GPU-box test)
 # ------------------------------------------------------------------------------------------------
