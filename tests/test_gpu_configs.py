@@ -1,4 +1,4 @@
-"""GPU parity on the five workloads (shapes, dtypes and scalars as listed in the benchmark spec), through the
+"""GPU parity on the five workloads (shapes, dtypes and scalars of the five benchmark configurations), through the
 C ABI, in the launch configuration bench.py times.
 
 Coverage contract (what the oracle computed is what is claimed):
