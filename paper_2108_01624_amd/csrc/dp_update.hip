@@ -99,6 +99,8 @@ __device__ __forceinline__ void snr_store(float sig, float noi, float* __restric
 }
 
 // Fast path: elem_offset % 4 == 0 and 16-byte aligned pointers.  Thread i owns local elements 4i .. 4i+3.
+// Every byte is touched exactly once per step, so loads and stores carry the non-temporal hint (no reuse to keep
+// in L2, and lines of the 4 x 1.3 GB state do not evict each other's neighbours).
 template <bool NOISE, bool ZERO, bool SNR>
 __global__ __launch_bounds__(256) void noise_adamw_vec4(float* __restrict__ params, float* __restrict__ m,
                                                         float* __restrict__ v, float* __restrict__ sum,
@@ -107,22 +109,30 @@ __global__ __launch_bounds__(256) void noise_adamw_vec4(float* __restrict__ para
     const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
     float sig = 0.f, noi = 0.f;
     if (i < nblocks4) {
-        float4 th = reinterpret_cast<float4*>(params)[i];
-        float4 mm = reinterpret_cast<float4*>(m)[i];
-        float4 vv = reinterpret_cast<float4*>(v)[i];
-        const float4 ss = reinterpret_cast<const float4*>(sum)[i];
+        f32x4_t* pt = reinterpret_cast<f32x4_t*>(params) + i;
+        f32x4_t* pm = reinterpret_cast<f32x4_t*>(m) + i;
+        f32x4_t* pv = reinterpret_cast<f32x4_t*>(v) + i;
+        f32x4_t* ps = reinterpret_cast<f32x4_t*>(sum) + i;
+        f32x4_t th = __builtin_nontemporal_load(pt);
+        f32x4_t mm = __builtin_nontemporal_load(pm);
+        f32x4_t vv = __builtin_nontemporal_load(pv);
+        const f32x4_t ss = __builtin_nontemporal_load(ps);
         float z[4] = {0.f, 0.f, 0.f, 0.f};
         if (NOISE) block_normals(block0 + i, seed, step, z);
-        adam_elem(th.x, mm.x, vv.x, ss.x, z[0], a);
-        adam_elem(th.y, mm.y, vv.y, ss.y, z[1], a);
-        adam_elem(th.z, mm.z, vv.z, ss.z, z[2], a);
-        adam_elem(th.w, mm.w, vv.w, ss.w, z[3], a);
-        reinterpret_cast<float4*>(params)[i] = th;
-        reinterpret_cast<float4*>(m)[i] = mm;
-        reinterpret_cast<float4*>(v)[i] = vv;
-        if (ZERO) reinterpret_cast<float4*>(sum)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            float t = th[k], mk = mm[k], vk = vv[k];
+            adam_elem(t, mk, vk, ss[k], z[k], a);
+            th[k] = t;
+            mm[k] = mk;
+            vv[k] = vk;
+        }
+        __builtin_nontemporal_store(th, pt);
+        __builtin_nontemporal_store(mm, pm);
+        __builtin_nontemporal_store(vv, pv);
+        if (ZERO) __builtin_nontemporal_store(f32x4_t{0.f, 0.f, 0.f, 0.f}, ps);
         if (SNR) {
-            sig = (ss.x * ss.x + ss.y * ss.y) + (ss.z * ss.z + ss.w * ss.w);
+            sig = (ss[0] * ss[0] + ss[1] * ss[1]) + (ss[2] * ss[2] + ss[3] * ss[3]);
             const float n0 = a.noise_scale * z[0], n1 = a.noise_scale * z[1], n2 = a.noise_scale * z[2],
                         n3 = a.noise_scale * z[3];
             noi = (n0 * n0 + n1 * n1) + (n2 * n2 + n3 * n3);
