@@ -187,11 +187,20 @@ __global__ __launch_bounds__(256, 2) void gram_bf16_kernel(const uint16_t* __res
 // ------------------------------------------------------------------------------------------------
 typedef int gram_i32x4 __attribute__((ext_vector_type(4)));
 
+// STREAM: non-temporal hint, for data that no other workgroup reads again (every byte of a T <= 128 example is read
+// once; +4 % there).  The block pairs of a longer example share their panels through L2 and must not use it.
+template <bool STREAM>
 __device__ __forceinline__ void gram_dma16(gram_i32x4 rsrc, uint32_t lds_byte_addr, int voff, int soff) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                 :
-                 : "s"(lds_byte_addr), "v"(voff), "s"(rsrc), "s"(soff)
-                 : "memory");
+    if (STREAM)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen nt lds"
+                     :
+                     : "s"(lds_byte_addr), "v"(voff), "s"(rsrc), "s"(soff)
+                     : "memory");
+    else
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                     :
+                     : "s"(lds_byte_addr), "v"(voff), "s"(rsrc), "s"(soff)
+                     : "memory");
 }
 
 __device__ __forceinline__ gram_i32x4 gram_rsrc(const void* base, uint32_t bytes) {
@@ -267,11 +276,11 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gram_dma_kernel(GramBatch gb,
 #pragma unroll
         for (int j = 0; j < LPS; ++j) {
             const uint32_t dst = __builtin_amdgcn_readfirstlane(ldsoff[j] + ibuf * (STAGE * 2));
-            if (isA) gram_dma16(rA, dst, voffA[j], soff);
-            else if (st >= nch) gram_dma16(rG, dst, voffG[j], 0x7FFFFFF0);  // past the end: reads zeros, keeps the load count uniform
-            else if (which == 0) gram_dma16(rG, dst, voffG[j], soff);
-            else if (which == 1) gram_dma16(rG2, dst, voffG[j], soff);
-            else gram_dma16(rG3, dst, voffG[j], soff);
+            if (isA) gram_dma16<true>(rA, dst, voffA[j], soff);
+            else if (st >= nch) gram_dma16<true>(rG, dst, voffG[j], 0x7FFFFFF0);  // past the end: reads zeros, keeps the load count uniform
+            else if (which == 0) gram_dma16<true>(rG, dst, voffG[j], soff);
+            else if (which == 1) gram_dma16<true>(rG2, dst, voffG[j], soff);
+            else gram_dma16<true>(rG3, dst, voffG[j], soff);
         }
         ibuf = ibuf + 1 == NS ? 0 : ibuf + 1;
     };
@@ -397,8 +406,8 @@ __device__ __forceinline__ float gram_pair_ring(const uint16_t* __restrict__ A, 
 #pragma unroll
             for (int j = 0; j < LPP; ++j) {
                 const uint32_t dst = __builtin_amdgcn_readfirstlane(ldsoff[j] + (ibuf * 2 * PANEL + pn * PANEL) * 2);
-                if (isA) gram_dma16(rA, dst, voffA[pn][j], soff);
-                else gram_dma16(rG, dst, voffG[pn][j], soff);
+                if (isA) gram_dma16<false>(rA, dst, voffA[pn][j], soff);
+                else gram_dma16<false>(rG, dst, voffG[pn][j], soff);
             }
         ibuf = ibuf + 1 == GP_NS ? 0 : ibuf + 1;
     };

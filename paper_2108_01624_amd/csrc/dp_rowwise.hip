@@ -12,20 +12,23 @@ namespace {
 // ------------------------------------------------------------------------------------------------
 // element access: VW consecutive elements starting at element index `idx`
 // ------------------------------------------------------------------------------------------------
+// (non-temporal: every input byte of these kernels is read once and by one workgroup)
+typedef uint32_t rw_u32x2 __attribute__((ext_vector_type(2)));
 template <bool BF16, int VW>
 __device__ __forceinline__ void load_vec(const void* __restrict__ base, size_t idx, float out[VW]) {
     if constexpr (BF16) {
         static_assert(VW == 4, "bf16 rows are read four elements at a time");
-        const uint2 w = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(base) + idx);
-        out[0] = dp_bf16_lo(w.x);
-        out[1] = dp_bf16_hi(w.x);
-        out[2] = dp_bf16_lo(w.y);
-        out[3] = dp_bf16_hi(w.y);
+        const rw_u32x2 w =
+            __builtin_nontemporal_load(reinterpret_cast<const rw_u32x2*>(reinterpret_cast<const uint16_t*>(base) + idx));
+        out[0] = dp_bf16_lo(w[0]);
+        out[1] = dp_bf16_hi(w[0]);
+        out[2] = dp_bf16_lo(w[1]);
+        out[3] = dp_bf16_hi(w[1]);
     } else if constexpr (VW == 4) {
-        const float4 w = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(base) + idx);
-        out[0] = w.x; out[1] = w.y; out[2] = w.z; out[3] = w.w;
+        const f32x4_t w = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(reinterpret_cast<const float*>(base) + idx));
+        out[0] = w[0]; out[1] = w[1]; out[2] = w[2]; out[3] = w[3];
     } else {
-        out[0] = reinterpret_cast<const float*>(base)[idx];
+        out[0] = __builtin_nontemporal_load(reinterpret_cast<const float*>(base) + idx);
     }
 }
 
