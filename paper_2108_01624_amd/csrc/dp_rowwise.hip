@@ -92,6 +92,7 @@ __global__ __launch_bounds__(256) void colstat_sqnorms_kernel(const void* __rest
 //   partial layout: part[r][0][d] = sum c g x,  part[r][1][d] = sum c g
 // ------------------------------------------------------------------------------------------------
 template <bool BF16, int VW, bool USE_X>
+// (the clip factors come precomputed: forming them here, a square root and a division per row and thread, cost 2 %)
 __global__ __launch_bounds__(256) void colstat_sums_kernel(const void* __restrict__ X, const void* __restrict__ G,
                                                            const float* __restrict__ c, int T, int d, long nrows,
                                                            int rows_per, float* __restrict__ part) {
@@ -206,6 +207,45 @@ __global__ __launch_bounds__(256) void reduce_partials_tall_kernel(const float4*
         o.z += (a.z + b.z) + (c.z + d.z);
         o.w += (a.w + b.w) + (c.w + d.w);
         out[j] = o;
+    }
+}
+
+// The two column-sum vectors of one partial buffer [R][2][d] in one launch: columns j < d4 go to out_x, the others to
+// out_1 (same order of additions as reduce_partials_tall_kernel).
+__global__ __launch_bounds__(256) void reduce_partials_pair_kernel(const float4* __restrict__ part, int R, size_t d4,
+                                                                   float4* __restrict__ out_x,
+                                                                   float4* __restrict__ out_1) {
+    __shared__ float4 red[4][64];
+    const int lane = threadIdx.x & 63, g = threadIdx.x >> 6;
+    const size_t j = (size_t)blockIdx.x * 64 + lane, n4 = 2 * d4;
+    float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (j < n4) {
+        int r = g;
+        for (; r + 28 < R; r += 32) {
+            float4 p[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) p[u] = part[(size_t)(r + 4 * u) * n4 + j];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                t.x += p[u].x; t.y += p[u].y; t.z += p[u].z; t.w += p[u].w;
+            }
+        }
+        for (; r < R; r += 4) {
+            const float4 p = part[(size_t)r * n4 + j];
+            t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
+        }
+    }
+    red[g][lane] = t;
+    __syncthreads();
+    if (g == 0 && j < n4) {
+        const float4 a = red[0][lane], b = red[1][lane], c = red[2][lane], e = red[3][lane];
+        float4* dst = j < d4 ? out_x + j : out_1 + (j - d4);
+        float4 o = *dst;
+        o.x += (a.x + b.x) + (c.x + e.x);
+        o.y += (a.y + b.y) + (c.y + e.y);
+        o.z += (a.z + b.z) + (c.z + e.z);
+        o.w += (a.w + b.w) + (c.w + e.w);
+        *dst = o;
     }
 }
 
@@ -572,6 +612,15 @@ static dp_status colstat_sums_launch(dp_ctx* ctx, const void* X, const void* G, 
     else
         hipLaunchKernelGGL((colstat_sums_kernel<BF16, VW, false>), grid, dim3(256), 0, ctx->stream, X, G, c, T, d, nrows, rows_per, part);
     DP_LAUNCH_CHECK(ctx, "colstat_sums");
+    if (out_x && out_1 && d % 4 == 0 && R >= 32 && d <= 32768 &&
+        (((uintptr_t)part | (uintptr_t)out_x | (uintptr_t)out_1) & 15) == 0) {
+        const size_t d4 = (size_t)d / 4;
+        hipLaunchKernelGGL(reduce_partials_pair_kernel, dim3((unsigned)((2 * d4 + 63) / 64)), dim3(256), 0, ctx->stream,
+                           reinterpret_cast<const float4*>(part), (int)R, d4, reinterpret_cast<float4*>(out_x),
+                           reinterpret_cast<float4*>(out_1));
+        DP_LAUNCH_CHECK(ctx, "reduce_partials_pair");
+        return DP_OK;
+    }
     dp_status st = DP_OK;
     if (out_x) st = dpk_reduce_partials(ctx, part, (int)R, (size_t)2 * d, d, out_x);
     if (st == DP_OK && out_1) st = dpk_reduce_partials(ctx, part + d, (int)R, (size_t)2 * d, d, out_1);
