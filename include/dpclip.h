@@ -152,6 +152,13 @@ dp_status dp_clip_accumulate_layernorm(dp_ctx* ctx, const void* Xhat, const void
 dp_status dp_clip_accumulate_embedding(dp_ctx* ctx, const int32_t* ids, const void* G, dp_dtype dtype, int B, int T,
                                        int d, int V, float C, const float* sqnorms, float* sum_E);
 
+/* The position-embedding case of dp_clip_accumulate_embedding: ids[i,t] = t for every example, so
+ * sum_E[t, :] += sum_i c_i G[i,t,:] for t < T (sum_E holds at least T rows of width d; the rows from T on are not
+ * touched).  No ids, no sort: one weighted sum over the B examples.  Same result as the general entry point
+ * up to fp32 summation order. */
+dp_status dp_clip_accumulate_positions(dp_ctx* ctx, const void* G, dp_dtype dtype, int B, int T, int d, float C,
+                                       const float* sqnorms, float* sum_E);
+
 /* The clip factors themselves (pass 2 computes them internally; exposed for checks): c[i], i < B. */
 dp_status dp_clip_factors(dp_ctx* ctx, const float* sqnorms, int B, float C, float* c);
 

@@ -39,6 +39,7 @@ SIGNATURES = {
                                      c_void_p, c_void_p],
     "dp_clip_accumulate_embedding": [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_float, c_void_p,
                                      c_void_p],
+    "dp_clip_accumulate_positions": [c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_float, c_void_p, c_void_p],
     "dp_noise_adamw": [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_uint64, c_uint64, c_float, c_float, c_uint64,
                        c_uint64, c_uint64, c_float, c_float, c_float, c_float, c_float, c_int],
     "dp_noise_adamw_snr": [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_uint64, c_uint64, c_float, c_float, c_uint64,
@@ -250,6 +251,14 @@ def dp_clip_accumulate_embedding(ctx, ids, G, V, C, sqnorms, sum_E):
     st = load_library().dp_clip_accumulate_embedding(ctx, _i32(ids), _ptr(G), _dtype_of(G), B, T, d, int(V), float(C),
                                                      _f32(sqnorms), _f32(sum_E))
     _check(ctx, st, "dp_clip_accumulate_embedding")
+
+
+def dp_clip_accumulate_positions(ctx, G, C, sqnorms, sum_E):
+    B, T, d = G.shape
+    if sum_E.numel() < T * d:
+        raise ValueError("sum_E must hold at least T rows")
+    st = load_library().dp_clip_accumulate_positions(ctx, _ptr(G), _dtype_of(G), B, T, d, float(C), _f32(sqnorms), _f32(sum_E))
+    _check(ctx, st, "dp_clip_accumulate_positions")
 
 
 def dp_noise_adamw(ctx, params, m, v, sum_, *, n=None, elem_offset=0, sigma, C, seed, step, batch_size, lr, beta1, beta2,

@@ -438,6 +438,24 @@ dp_status dp_clip_accumulate_embedding(dp_ctx* ctx, const int32_t* ids, const vo
     return dpk_embedding_sums(ctx, ids, G, dtype, B, T, d, V, ctx->cbuf, sum_E);
 }
 
+dp_status dp_clip_accumulate_positions(dp_ctx* ctx, const void* G, dp_dtype dtype, int B, int T, int d, float C,
+                                       const float* sqnorms, float* sum_E) {
+    REQUIRE_CTX(ctx);
+    TRY(check_dtype(ctx, dtype));
+    TRY(check_bt(ctx, B, T));
+    if (d < 0) FAIL(ctx, DP_ERR_SHAPE, "width must be >= 0");
+    TRY(check_tensor(ctx, "G", G, dtype, d));
+    TRY(check_f32(ctx, "sqnorms", sqnorms));
+    TRY(check_f32(ctx, "sum_E", sum_E));
+    TRY(check_clip(ctx, C, B));
+    if (B == 0 || T == 0 || d == 0) return DP_OK;
+    if ((long)T * d > 0x7FFFFFFFl) FAIL(ctx, DP_ERR_SHAPE, "T * d too large");
+    TRY(dpk_clip_factors(ctx, sqnorms, B, C, ctx->cbuf));
+    // token t of every example adds to row t: the first T rows of the table, read as one vector of T*d entries,
+    // receive sum_i c_i * (example i's gradient read as one row of T*d entries): a weighted column sum over B rows
+    return dpk_colstat_sums(ctx, nullptr, G, dtype, B, 1, T * d, ctx->cbuf, nullptr, sum_E);
+}
+
 static dp_status noise_adamw_checked(dp_ctx* ctx, float* params, float* m, float* v, float* sum, uint64_t n,
                                      uint64_t elem_offset, float sigma, float C, uint64_t seed, uint64_t step,
                                      uint64_t batch_size, float lr, float beta1, float beta2, float eps,

@@ -91,6 +91,8 @@ class StepRunner:
                     ctx.clip_accumulate_dense(l["A"], l["G"], C, n, self.view(self.S, k, 0), sb)
             elif l["kind"] == "layernorm":
                 ctx.clip_accumulate_layernorm(l["X"], l["G"], C, n, self.view(self.S, k, 0), self.view(self.S, k, 1))
+            elif l.get("distinct"):
+                ctx.clip_accumulate_positions(l["G"], C, n, self.view(self.S, k, 0))   # position ids: no sort needed
             else:
                 ctx.clip_accumulate_embedding(l["ids"], l["G"], l["V"], C, n, self.view(self.S, k, 0))
         for sel in groups.values():

@@ -534,6 +534,27 @@ def test_zero_and_empty_calls(dp):
     assert host(n).tolist() == [1, 1, 1, 1]
 
 
+@pytest.mark.parametrize("dtype,B,T,d,V", [("bf16", 9, 128, 64, 512), ("bf16", 3, 7, 8, 16), ("f32", 5, 33, 20, 40),
+                                           ("bf16", 70, 16, 256, 16)])
+def test_clip_accumulate_positions(dp, dtype, B, T, d, V):
+    """Position embedding without the sort: against the oracle's scatter with ids 0..T-1 and against the general path."""
+    C = 1.0
+    G = gen((B, T, d), 0.1, 700, dtype)
+    ids = syn.position_ids(B, T)
+    sq = syn.synthetic_sqnorms(B, C, 701)
+    c = orc.clip_factors(sq.astype(np.float64), C)
+    ref = orc.clip_accumulate_embedding(ids, G, c, V)
+    init = syn.normal_f32((V, d), float(np.abs(ref).mean()), 702)
+    S_fast, S_gen = f32_dev(init), f32_dev(init)
+    dp.clip_accumulate_positions(to_dev(G), C, f32_dev(sq), S_fast)
+    dp.clip_accumulate_embedding(to_dev(ids), to_dev(G), V, C, f32_dev(sq), S_gen)
+    dp.sync()
+    tol = 1e-5 if dtype == "f32" else 1e-4
+    assert_sums_close(host(S_fast) - init.astype(np.float64), ref, tol, "positions")
+    np.testing.assert_array_equal(host(S_fast)[T:], init[T:])          # rows from T on are untouched
+    np.testing.assert_allclose(host(S_fast), host(S_gen), rtol=1e-4, atol=1e-6 * np.abs(ref).max())
+
+
 # ------------------------------------------------------------------------------------------------
 # several same-shaped dense layers in one call
 # ------------------------------------------------------------------------------------------------
