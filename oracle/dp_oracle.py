@@ -23,7 +23,8 @@ Readings of points the paper leaves open (each also listed in the design notes):
     23-bit uniforms u = ((r >> 9) + 1/2) * 2^-23 (exact in fp32), Box-Muller on word pairs.
 
 Pins (tests/test_oracle_pins.py): brute-force autograd on a tiny BERT-like model for the
-gradient formulas, norms, clip factors and sums; closed forms (T = 1, rank one); clip
+gradient formulas, norms, clip factors and sums (a second tiny model, with its output projection tied
+to the lookup table, for tied_embedding_example_grad); closed forms (T = 1, rank one); clip
 invariant and clip no-op against a flat GEMM / bincount / index_add; torch.optim.AdamW and a
 hand-worked element for the update; statistical moments and exact-uniform checks for the
 normals.  Philox known-answer vectors are NOT in this repository: its raw stream is
@@ -97,6 +98,22 @@ def embedding_example_grad_dense(ids_i, G_i, V):
     return E
 
 
+def tied_embedding_example_grad(ids_i, dY_i, H_i, dL_i):
+    """A table E [V, d] that one example uses twice: as the lookup y_t = E[ids_t] of its T tokens (Section
+    4.3's word-piece table) and as the output projection logits = H_i E^T of M selected positions (the
+    masked-token head of BERT; the paper does not say whether its model ties the two, this is the gradient if it
+    does).  E is ONE parameter, so the example has ONE gradient for it, the sum of both uses:
+    the rows dY_i scattered to their ids, plus the outer-product form dL_i^T H_i of a fully connected layer whose
+    weight is E^T (input H_i [M, d], output gradient dL_i [M, V]).  Returned as the explicit [V, d] array."""
+    dL_i = to_f64(dL_i)
+    H_i = to_f64(H_i)
+    V = dL_i.shape[1]
+    g = embedding_example_grad_dense(ids_i, dY_i, V)
+    for m in range(dL_i.shape[0]):
+        g += np.outer(dL_i[m], H_i[m])
+    return g
+
+
 # --------------------------------------------------------------------------------------
 # pass 1: per-example squared norms of one layer
 # --------------------------------------------------------------------------------------
@@ -128,6 +145,15 @@ def sqnorms_embedding(ids, G, V: int) -> np.ndarray:
     for i in range(B):
         _, R = embedding_example_grad(ids[i], G[i], V)
         n[i] = np.sum(R * R)
+    return n
+
+
+def sqnorms_tied_embedding(ids, dY, H, dL) -> np.ndarray:
+    B = ids.shape[0]
+    n = np.zeros(B, dtype=np.float64)
+    for i in range(B):
+        g = tied_embedding_example_grad(ids[i], dY[i], H[i], dL[i])
+        n[i] = np.sum(g * g)
     return n
 
 
@@ -194,6 +220,13 @@ def clip_accumulate_embedding(ids, G, c, V: int):
     return S_E
 
 
+def clip_accumulate_tied_embedding(ids, dY, H, dL, c):
+    S_E = np.zeros((dL.shape[2], dY.shape[2]), dtype=np.float64)
+    for i in range(ids.shape[0]):
+        S_E += c[i] * tied_embedding_example_grad(ids[i], dY[i], H[i], dL[i])
+    return S_E
+
+
 # --------------------------------------------------------------------------------------
 # one micro-batch over a whole manifest of layers
 # --------------------------------------------------------------------------------------
@@ -209,6 +242,8 @@ def _layer_example_grads(layer: dict, i: int):
         return [gg, gb]
     if k == "embedding":
         return [embedding_example_grad(layer["ids"][i], layer["G"][i], layer["V"])]
+    if k == "tied_embedding":  # "G" is the gradient of the lookup's output (dY)
+        return [tied_embedding_example_grad(layer["ids"][i], layer["G"][i], layer["H"][i], layer["dL"][i])]
     raise ValueError(k)
 
 

@@ -30,6 +30,18 @@ MUTANTS = [
      "test_autograd_bruteforce_tiny_bert"),
     ("embedding_repeated_ids_overwrite", [("R[inv[t]] += G_i[t]", "R[inv[t]] = G_i[t]", None)], "test_embedding_counts_and_index_add"),
     ("embedding_no_range_check", [('raise IndexError("token id out of range")', "pass", None)], "test_embedding_rejects_out_of_range"),
+    ("tied_drops_output_projection", [("        g += np.outer(dL_i[m], H_i[m])", "        pass", None)], "test_tied_embedding_against_autograd"),
+    ("tied_output_projection_sign", [("        g += np.outer(dL_i[m], H_i[m])", "        g -= np.outer(dL_i[m], H_i[m])", None)],
+     "test_tied_embedding_special_cases_and_cross_term"),
+    ("tied_outer_product_transposed", [("np.outer(dL_i[m], H_i[m])", "(np.outer(H_i[m], dL_i[m]) if dL_i.shape[1] == H_i.shape[1] else np.outer(dL_i[m], H_i[m]))", None)],
+     "test_tied_embedding_square_table"),
+    ("tied_norms_add_instead_of_norm_of_sum", [("        g = tied_embedding_example_grad(ids[i], dY[i], H[i], dL[i])\n        n[i] = np.sum(g * g)",
+                                                "        g = tied_embedding_example_grad(ids[i], dY[i], H[i], np.zeros_like(dL[i]))\n"
+                                                "        h = tied_embedding_example_grad(ids[i], np.zeros_like(dY[i]), H[i], dL[i])\n"
+                                                "        n[i] = np.sum(g * g) + np.sum(h * h)", None)],
+     "test_tied_embedding_against_autograd"),
+    ("tied_sum_unweighted", [("S_E += c[i] * tied_embedding_example_grad", "S_E += tied_embedding_example_grad", None)],
+     "test_tied_embedding_special_cases_and_cross_term"),
     ("clip_uses_squared_norm", [("float(C) / np.sqrt(n[pos])", "float(C) / n[pos]", None)], "test_clip_invariant_and_all_clipped"),
     ("clip_without_min", [("np.minimum(1.0, float(C) / np.sqrt(n[pos]))", "float(C) / np.sqrt(n[pos])", None)], "test_clip_noop_equals_flat_gemm"),
     ("clip_zero_gradient_gets_zero", [("c = np.ones_like(n)", "c = np.zeros_like(n)", None)], "test_clip_zero_gradient_gets_factor_one"),

@@ -292,6 +292,124 @@ def test_embedding_rejects_out_of_range():
 
 
 # ----------------------------------------------------------------------------------------------
+# a table used as lookup AND as output projection (tied weights)
+# ----------------------------------------------------------------------------------------------
+
+
+def _tied_model(B=4, T=6, M=3, d=5, V=9, seed=3):
+    g = torch.Generator().manual_seed(seed)
+    rn = lambda *s: torch.randn(*s, generator=g, dtype=torch.float64)
+    P = dict(E=rn(V, d), W=rn(d, d) / math.sqrt(d))
+    for p in P.values():
+        p.requires_grad_(True)
+    ids = torch.randint(0, V, (B, T), generator=g)
+    ids[:, 2] = ids[:, 0]                               # repeated ids inside every example
+    mpos = torch.stack([torch.randperm(T, generator=g)[:M] for _ in range(B)])
+    labels = torch.randint(0, V, (B, M), generator=g)
+    labels[1, 0] = ids[1, 0]                            # a label that is also one of the example's input ids
+    w = torch.ones(B, M, dtype=torch.float64)
+    w[2, M - 1] = 0.0                                   # a padded prediction slot
+    return P, ids, mpos, labels, w
+
+
+def _tied_forward(P, ids, mpos, labels, w, keep=None):
+    B = ids.shape[0]
+    x = P["E"][ids]                                     # lookup
+    xw = x @ P["W"]
+    hm = torch.tanh(xw)[torch.arange(B)[:, None], mpos]  # the M selected positions
+    logits = hm @ P["E"].T                              # output projection with the SAME table
+    if keep is not None:
+        for k, t in dict(x=x, xw=xw, hm=hm, logits=logits).items():
+            t.retain_grad()
+            keep[k] = t
+    ce = torch.nn.functional.cross_entropy(logits.reshape(-1, logits.shape[-1]), labels.reshape(-1), reduction="none")
+    return (ce.reshape(B, -1) * w).sum(dim=1)
+
+
+@pytest.mark.parametrize("Cclip", [0.3, 1e9])
+def test_tied_embedding_against_autograd(Cclip):
+    P, ids, mpos, labels, w = _tied_model()
+    B = ids.shape[0]
+    keep = {}
+    _tied_forward(P, ids, mpos, labels, w, keep).sum().backward()
+    npy = lambda t: t.detach().numpy().copy()
+    ids_n = ids.numpy().astype(np.int32)
+    dY, H, dL = npy(keep["x"].grad), npy(keep["hm"]), npy(keep["logits"].grad)
+    assert np.all(dL[2, -1] == 0.0)                     # the padded slot has no gradient
+    layers = [dict(kind="tied_embedding", ids=ids_n, G=dY, H=H, dL=dL, V=P["E"].shape[0]),
+              dict(kind="dense", A=npy(keep["x"]), G=npy(keep["xw"].grad), has_bias=False)]
+    grads = []
+    for i in range(B):
+        for p in P.values():
+            p.grad = None
+        _tied_forward(P, ids[i:i + 1], mpos[i:i + 1], labels[i:i + 1], w[i:i + 1]).sum().backward()
+        grads.append({k: npy(p.grad) for k, p in P.items()})
+    for i in range(B):
+        g = orc.tied_embedding_example_grad(ids_n[i], dY[i], H[i], dL[i])
+        np.testing.assert_allclose(g, grads[i]["E"], rtol=1e-10, atol=1e-13)
+    n_E = np.array([float((grads[i]["E"] ** 2).sum()) for i in range(B)])
+    np.testing.assert_allclose(orc.sqnorms_tied_embedding(ids_n, dY, H, dL), n_E, rtol=1e-10)
+    n_true = n_E + np.array([float((grads[i]["W"] ** 2).sum()) for i in range(B)])
+    c_true = np.minimum(1.0, Cclip / np.sqrt(n_true))
+    sums, n, c = orc.microbatch_clip_sum(layers, Cclip)
+    np.testing.assert_allclose(n, n_true, rtol=1e-10)
+    np.testing.assert_allclose(orc.microbatch_sqnorms(layers), n_true, rtol=1e-10)
+    np.testing.assert_allclose(c, c_true, rtol=1e-10)
+    np.testing.assert_allclose(sums[0][0], sum(c_true[i] * grads[i]["E"] for i in range(B)), rtol=1e-9, atol=1e-13)
+    np.testing.assert_allclose(sums[1][0], sum(c_true[i] * grads[i]["W"] for i in range(B)), rtol=1e-9, atol=1e-13)
+    np.testing.assert_allclose(orc.clip_accumulate_tied_embedding(ids_n, dY, H, dL, c_true),
+                               sum(c_true[i] * grads[i]["E"] for i in range(B)), rtol=1e-9, atol=1e-13)
+
+
+def test_tied_embedding_special_cases_and_cross_term():
+    B, T, M, d, V = 3, 7, 4, 5, 8
+    ids = syn.zipf_ids(B, T, V, 1.1, 21)
+    dY = syn.normal_f32((B, T, d), 1.0, 22)
+    H = syn.normal_f32((B, M, d), 1.0, 23)
+    dL = syn.normal_f32((B, M, V), 0.5, 24)
+    zero = lambda a: np.zeros_like(a)
+    # no output-projection gradient: the plain lookup; no lookup gradient: a dense layer with input dL, output gradient H
+    np.testing.assert_allclose(orc.sqnorms_tied_embedding(ids, dY, H, zero(dL)), orc.sqnorms_embedding(ids, dY, V), rtol=1e-13)
+    np.testing.assert_allclose(orc.sqnorms_tied_embedding(ids, zero(dY), H, dL), orc.sqnorms_dense(dL, H, False), rtol=1e-13)
+    c = np.array([0.25, 1.0, 0.5])
+    np.testing.assert_allclose(orc.clip_accumulate_tied_embedding(ids, dY, H, dL, c),
+                               orc.clip_accumulate_embedding(ids, dY, c, V) + orc.clip_accumulate_dense(dL, H, c, False)[0],
+                               rtol=1e-12, atol=1e-14)
+    # entry by entry with plain loops, and the expansion of the square with its cross term
+    n = orc.sqnorms_tied_embedding(ids, dY, H, dL)
+    for i in range(B):
+        tot = 0.0
+        for v in range(V):
+            for k in range(d):
+                e = sum(float(dY[i, t, k]) for t in range(T) if ids[i, t] == v)
+                e += sum(float(dL[i, m, v]) * float(H[i, m, k]) for m in range(M))
+                tot += e * e
+        assert abs(tot - n[i]) <= 1e-11 * tot
+        cross = sum(float(dL[i, m, ids[i, t]]) * float(np.dot(dY[i, t].astype(np.float64), H[i, m].astype(np.float64)))
+                    for t in range(T) for m in range(M))
+        parts = orc.sqnorms_embedding(ids[i:i + 1], dY[i:i + 1], V)[0] + orc.sqnorms_dense(dL[i:i + 1], H[i:i + 1], False)[0]
+        assert abs(parts + 2.0 * cross - n[i]) <= 1e-11 * n[i]
+        assert abs(cross) > 1e-3 * n[i]                 # the cross term is not negligible in this case
+
+
+def test_tied_embedding_square_table():
+    """V == d: a transposed outer product would still have the right shape; autograd tells the two apart."""
+    E = torch.arange(16, dtype=torch.float64).reshape(4, 4).requires_grad_(True) / 10.0
+    E.retain_grad()
+    ids = torch.tensor([[1, 3, 1]])
+    x = E[ids]
+    x.retain_grad()
+    hm = torch.tanh(x[:, :2] * 0.7)
+    hm.retain_grad()
+    logits = hm @ E.T
+    logits.retain_grad()
+    (logits ** 2).sum().backward()
+    npy = lambda t: t.detach().numpy().copy()
+    g = orc.tied_embedding_example_grad(ids.numpy()[0].astype(np.int32), npy(x.grad)[0], npy(hm)[0], npy(logits.grad)[0])
+    np.testing.assert_allclose(g, npy(E.grad), rtol=1e-12, atol=1e-14)
+
+
+# ----------------------------------------------------------------------------------------------
 # mega-batch accumulation
 # ----------------------------------------------------------------------------------------------
 def test_accumulation_is_linear_over_microbatches():
