@@ -23,7 +23,8 @@ def _randn(shape, std, gen, dtype, device):
 
 def device_layer_inputs(manifest, B, T, *, dtype, act_std, grad_std, data_seed, device="cuda:0", zipf_s=1.1,
                         example_scale=None):
-    """One dict per layer with device tensors: dense {A, G}, layernorm {X, G}, embedding {ids, G}.
+    """One dict per layer with device tensors: dense {A, G}, layernorm {X, G}, embedding {ids, G},
+    tied_embedding {ids, G (gradient of the lookup output), H, dL}.
     `example_scale` (host fp32 [B]) multiplies example i's output gradients (mixed-clipping variant)."""
     import torch
 
@@ -48,6 +49,26 @@ def device_layer_inputs(manifest, B, T, *, dtype, act_std, grad_std, data_seed, 
         elif spec.kind == "layernorm":
             d["X"] = _randn((B, T, spec.d_out), act_std, gen, tdtype, device)
             d["G"] = grad(spec.d_out)
+        elif spec.kind == "tied_embedding":
+            # lookup gradients as for an embedding; the output-projection side: inputs H like activations, logit
+            # gradients dL dense and small with one large negative entry per used slot (the label's column, as in a
+            # softmax cross-entropy gradient), labels drawn like token ids; each example uses between M/2 and M
+            # of its M slots, the rows of the others are zero
+            V, M = spec.d_in, spec.n_pred
+            seed_k = int(data_seed) + 7919 * (k + 1)
+            ids = zipf_ids(B, T, V, zipf_s, seed_k)
+            d["ids"] = torch.from_numpy(ids).to(device)
+            d["G"] = grad(spec.d_out)
+            d["V"] = V
+            d["H"] = _randn((B, M, spec.d_out), act_std, gen, tdtype, device)
+            dL = _randn((B, M, V), grad_std / 8.0, gen, torch.float32, device)
+            labels = torch.from_numpy(zipf_ids(B, M, V, zipf_s, seed_k + 1).astype(np.int64)).to(device)
+            dL.scatter_add_(2, labels[:, :, None], torch.full((B, M, 1), -8.0 * grad_std, device=device))
+            used = torch.from_numpy(np.random.default_rng(seed_k + 2).integers((M + 1) // 2, M + 1, size=B)).to(device)
+            dL *= (torch.arange(M, device=device)[None, :] < used[:, None])[:, :, None]
+            if sc is not None:
+                dL *= sc
+            d["dL"] = dL.to(tdtype)
         else:
             ids = position_ids(B, T) if spec.distinct else zipf_ids(B, T, spec.d_in, zipf_s, int(data_seed) + 7919 * (k + 1))
             d["ids"] = torch.from_numpy(ids).to(device)
@@ -74,12 +95,12 @@ def host_layer_slice(layers, examples):
     out = []
     for l in layers:
         d = dict(kind=l["kind"])
-        for key in ("A", "G", "X", "ids"):
+        for key in ("A", "G", "X", "ids", "H", "dL"):
             if key in l:
                 d[key] = h(l[key])
         if l["kind"] == "dense":
             d["has_bias"] = l["has_bias"]
-        if l["kind"] == "embedding":
+        if l["kind"] in ("embedding", "tied_embedding"):
             d["V"] = l["V"]
         out.append(d)
     return out

@@ -11,11 +11,12 @@ from typing import List, Tuple
 @dataclass(frozen=True)
 class LayerSpec:
     name: str
-    kind: str  # "dense" | "layernorm" | "embedding"
+    kind: str  # "dense" | "layernorm" | "embedding" | "tied_embedding"
     d_in: int = 0  # dense: input width; embedding: number of rows V
     d_out: int = 0  # dense: output width; layernorm/embedding: width d
     has_bias: bool = False
     distinct: bool = False  # embedding: ids are distinct within an example (position ids)
+    n_pred: int = 0  # tied_embedding: prediction slots M per example whose logits use the table as output projection
 
     def tensors(self) -> List[Tuple[str, Tuple[int, ...]]]:
         if self.kind == "dense":
@@ -25,7 +26,7 @@ class LayerSpec:
             return t
         if self.kind == "layernorm":
             return [(self.name + ".gamma", (self.d_out,)), (self.name + ".beta", (self.d_out,))]
-        if self.kind == "embedding":
+        if self.kind in ("embedding", "tied_embedding"):
             return [(self.name + ".E", (self.d_in, self.d_out))]
         raise ValueError(self.kind)
 
@@ -43,11 +44,14 @@ def single_dense_manifest(d_in: int, d_out: int, has_bias: bool = False) -> List
     return [LayerSpec("dense0", "dense", d_in, d_out, has_bias)]
 
 
-def bert_manifest(n_layers: int, hidden: int, ffn: int, vocab: int = 0, max_pos: int = 0) -> List[LayerSpec]:
+def bert_manifest(n_layers: int, hidden: int, ffn: int, vocab: int = 0, max_pos: int = 0, tied_pred: int = 0) -> List[LayerSpec]:
     """Per block: Q, K, V, O dense hidden x hidden, LayerNorm, FFN hidden x ffn and ffn x hidden,
-    LayerNorm; all dense layers carry biases. Optional token and position embeddings first."""
+    LayerNorm; all dense layers carry biases. Optional token and position embeddings first.  With tied_pred = M
+    the token table is also the output projection of M prediction slots per example (one parameter, two uses)."""
     m: List[LayerSpec] = []
-    if vocab:
+    if vocab and tied_pred:
+        m.append(LayerSpec("emb.tok", "tied_embedding", vocab, hidden, n_pred=tied_pred))
+    elif vocab:
         m.append(LayerSpec("emb.tok", "embedding", vocab, hidden))
     if max_pos:
         m.append(LayerSpec("emb.pos", "embedding", max_pos, hidden, distinct=True))

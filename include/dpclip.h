@@ -159,6 +159,28 @@ dp_status dp_clip_accumulate_embedding(dp_ctx* ctx, const int32_t* ids, const vo
 dp_status dp_clip_accumulate_positions(dp_ctx* ctx, const void* G, dp_dtype dtype, int B, int T, int d, float C,
                                        const float* sqnorms, float* sum_E);
 
+/* A table E [V, d] that every example uses twice (tied weights): as the lookup y_t = E[ids_t] of its T tokens
+ * (Section 4.3's word-piece table) and as the output projection logits = H E^T of M selected positions (the
+ * masked-token head of BERT; the paper does not say whether its model ties the two: these two entry points are the
+ * path's form if it does).  E is one parameter, so an example has one gradient for it,
+ *     g_i = scatter(ids_i, dY_i) + dL_i^T H_i     [V, d],
+ * dY [B,T,d] the gradient of the lookup's output, H [B,M,d] the inputs of the output projection, dL [B,M,V] the
+ * gradient of the logits (rows of unused prediction slots are zero), all of `dtype`, row-major, device memory,
+ * caller-owned; bf16 needs d and V multiples of 8; with M = 0 H and dL are not read and may be NULL.  Never materialised:
+ *     sqnorms[i] += ||scatter||^2 + <dL_i dL_i^T, H_i H_i^T> + 2 sum_{t,m} dL[i,m,ids[i,t]] <dY[i,t,:], H[i,m,:]>
+ * (the embedding norm, the dense norm of a layer with input dL and output gradient H, and the cross term between
+ * them, which is not small when a predicted token also occurs in the input).  An id outside [0, V) sets the
+ * error flag that dp_sync reports, as in dp_sqnorms_embedding. */
+dp_status dp_sqnorms_tied_embedding(dp_ctx* ctx, const int32_t* ids, const void* dY, const void* H, const void* dL,
+                                    dp_dtype dtype, int B, int T, int M, int d, int V, float* sqnorms);
+
+/* sum_E += sum_i c_i (scatter(ids_i, dY_i) + dL_i^T H_i), sum_E [V, d] fp32 (16-byte aligned for bf16): the work of
+ * dp_clip_accumulate_embedding(ids, dY) followed by dp_clip_accumulate_dense(A = dL, G = H, no bias) into the same
+ * buffer. */
+dp_status dp_clip_accumulate_tied_embedding(dp_ctx* ctx, const int32_t* ids, const void* dY, const void* H,
+                                            const void* dL, dp_dtype dtype, int B, int T, int M, int d, int V, float C,
+                                            const float* sqnorms, float* sum_E);
+
 /* The clip factors themselves (pass 2 computes them internally; exposed for checks): c[i], i < B. */
 dp_status dp_clip_factors(dp_ctx* ctx, const float* sqnorms, int B, float C, float* c);
 

@@ -40,6 +40,10 @@ SIGNATURES = {
     "dp_clip_accumulate_embedding": [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_float, c_void_p,
                                      c_void_p],
     "dp_clip_accumulate_positions": [c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_float, c_void_p, c_void_p],
+    "dp_sqnorms_tied_embedding": [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int,
+                                  c_void_p],
+    "dp_clip_accumulate_tied_embedding": [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int,
+                                          c_int, c_float, c_void_p, c_void_p],
     "dp_noise_adamw": [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_uint64, c_uint64, c_float, c_float, c_uint64,
                        c_uint64, c_uint64, c_float, c_float, c_float, c_float, c_float, c_int],
     "dp_noise_adamw_snr": [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_uint64, c_uint64, c_float, c_float, c_uint64,
@@ -259,6 +263,32 @@ def dp_clip_accumulate_positions(ctx, G, C, sqnorms, sum_E):
         raise ValueError("sum_E must hold at least T rows")
     st = load_library().dp_clip_accumulate_positions(ctx, _ptr(G), _dtype_of(G), B, T, d, float(C), _f32(sqnorms), _f32(sum_E))
     _check(ctx, st, "dp_clip_accumulate_positions")
+
+
+def _tied_shapes(ids, dY, H, dL):
+    B, T, d = dY.shape
+    M, V = dL.shape[1], dL.shape[2]
+    if tuple(ids.shape) != (B, T) or tuple(H.shape) != (B, M, d) or dL.shape[0] != B:
+        raise ValueError("ids [B,T], dY [B,T,d], H [B,M,d], dL [B,M,V] expected")
+    if H.dtype != dY.dtype or dL.dtype != dY.dtype:
+        raise ValueError("dY, H and dL must share one dtype")
+    return B, T, M, d, V
+
+
+def dp_sqnorms_tied_embedding(ctx, ids, dY, H, dL, sqnorms):
+    B, T, M, d, V = _tied_shapes(ids, dY, H, dL)
+    st = load_library().dp_sqnorms_tied_embedding(ctx, _i32(ids), _ptr(dY), _ptr(H), _ptr(dL), _dtype_of(dY), B, T, M, d, V,
+                                                  _f32(sqnorms))
+    _check(ctx, st, "dp_sqnorms_tied_embedding")
+
+
+def dp_clip_accumulate_tied_embedding(ctx, ids, dY, H, dL, C, sqnorms, sum_E):
+    B, T, M, d, V = _tied_shapes(ids, dY, H, dL)
+    if sum_E.numel() != V * d:
+        raise ValueError("sum_E must be [V, d]")
+    st = load_library().dp_clip_accumulate_tied_embedding(ctx, _i32(ids), _ptr(dY), _ptr(H), _ptr(dL), _dtype_of(dY), B, T, M,
+                                                          d, V, float(C), _f32(sqnorms), _f32(sum_E))
+    _check(ctx, st, "dp_clip_accumulate_tied_embedding")
 
 
 def dp_noise_adamw(ctx, params, m, v, sum_, *, n=None, elem_offset=0, sigma, C, seed, step, batch_size, lr, beta1, beta2,

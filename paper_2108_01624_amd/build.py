@@ -12,7 +12,7 @@ INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
 LIB_PATH = os.path.join(PKG_DIR, "libdpclip.so")
 BUILD_DIR = os.path.join(PKG_DIR, "_build")
 
-SOURCES = ["dp_api.hip", "dp_update.hip", "dp_rowwise.hip", "dp_gram.hip", "dp_wgemm.hip"]
+SOURCES = ["dp_api.hip", "dp_update.hip", "dp_rowwise.hip", "dp_gram.hip", "dp_wgemm.hip", "dp_tied.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + INCLUDE, "-I" + CSRC,

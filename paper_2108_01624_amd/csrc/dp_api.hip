@@ -456,6 +456,53 @@ dp_status dp_clip_accumulate_positions(dp_ctx* ctx, const void* G, dp_dtype dtyp
     return dpk_colstat_sums(ctx, nullptr, G, dtype, B, 1, T * d, ctx->cbuf, nullptr, sum_E);
 }
 
+static dp_status check_tied(dp_ctx* ctx, const int32_t* ids, const void* dY, const void* H, const void* dL,
+                            dp_dtype dtype, int B, int T, int M, int d, int V, const float* sqnorms) {
+    TRY(check_dtype(ctx, dtype));
+    TRY(check_bt(ctx, B, T));
+    TRY(check_bt(ctx, B, M));
+    if (d < 0 || V <= 0) FAIL(ctx, DP_ERR_SHAPE, "width must be >= 0 and V > 0");
+    if ((long)M * V > (long)INT_MAX) FAIL(ctx, DP_ERR_SHAPE, "M * V = %ld exceeds 2^31", (long)M * V);
+    TRY(check_f32(ctx, "ids", ids));
+    TRY(check_tensor(ctx, "dY", dY, dtype, d));
+    if (M > 0) {
+        TRY(check_tensor(ctx, "H", H, dtype, d));
+        TRY(check_tensor(ctx, "dL", dL, dtype, V));
+    }
+    TRY(check_f32(ctx, "sqnorms", sqnorms));
+    return DP_OK;
+}
+
+dp_status dp_sqnorms_tied_embedding(dp_ctx* ctx, const int32_t* ids, const void* dY, const void* H, const void* dL,
+                                    dp_dtype dtype, int B, int T, int M, int d, int V, float* sqnorms) {
+    REQUIRE_CTX(ctx);
+    TRY(check_tied(ctx, ids, dY, H, dL, dtype, B, T, M, d, V, sqnorms));
+    if (B == 0 || d == 0) return DP_OK;
+    if (T > 0) TRY(dpk_embedding_sqnorms(ctx, ids, dY, dtype, B, T, d, V, 0, sqnorms));
+    if (M == 0) return DP_OK;
+    // the output projection as a dense layer with weight E: "input" dL_i [M, V], "output gradient" H_i [M, d];
+    // M is far below both widths, so the Gram form <dL dL^T, H H^T> is the cheap one
+    TRY(dpk_gram_sqnorms(ctx, dL, H, dtype, B, M, V, d, 0, sqnorms));
+    return dpk_tied_cross_sqnorms(ctx, ids, dY, H, dL, dtype, B, T, M, d, V, sqnorms);
+}
+
+dp_status dp_clip_accumulate_tied_embedding(dp_ctx* ctx, const int32_t* ids, const void* dY, const void* H,
+                                            const void* dL, dp_dtype dtype, int B, int T, int M, int d, int V, float C,
+                                            const float* sqnorms, float* sum_E) {
+    REQUIRE_CTX(ctx);
+    TRY(check_tied(ctx, ids, dY, H, dL, dtype, B, T, M, d, V, sqnorms));
+    TRY(check_f32(ctx, "sum_E", sum_E));
+    if (dtype == DP_BF16 && ((uintptr_t)sum_E & 15)) FAIL(ctx, DP_ERR_ALIGN, "sum_E is not 16-byte aligned");
+    TRY(check_clip(ctx, C, B));
+    if (B == 0 || d == 0) return DP_OK;
+    if (T > 0) {
+        TRY(dpk_clip_factors(ctx, sqnorms, B, C, ctx->cbuf));
+        TRY(dpk_embedding_sums(ctx, ids, dY, dtype, B, T, d, V, ctx->cbuf, sum_E));
+    }
+    if (M == 0) return DP_OK;
+    return dpk_weighted_gemm(ctx, dL, H, dtype, B, M, V, d, sqnorms, C, sum_E, nullptr);
+}
+
 static dp_status noise_adamw_checked(dp_ctx* ctx, float* params, float* m, float* v, float* sum, uint64_t n,
                                      uint64_t elem_offset, float sigma, float C, uint64_t seed, uint64_t step,
                                      uint64_t batch_size, float lr, float beta1, float beta2, float eps,

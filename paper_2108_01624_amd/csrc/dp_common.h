@@ -186,3 +186,5 @@ dp_status dpk_embedding_sqnorms(dp_ctx*, const int32_t* ids, const void* G, dp_d
                                 int distinct, float* sqnorms);
 dp_status dpk_embedding_sums(dp_ctx*, const int32_t* ids, const void* G, dp_dtype, int B, int T, int d, int V,
                              const float* c, float* sum_E);
+dp_status dpk_tied_cross_sqnorms(dp_ctx*, const int32_t* ids, const void* dY, const void* H, const void* dL, dp_dtype,
+                                 int B, int T, int M, int d, int V, float* sqnorms);

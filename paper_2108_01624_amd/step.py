@@ -57,6 +57,8 @@ class StepRunner:
                     ctx.sqnorms_dense(l["A"], l["G"], l["has_bias"], path, n)
             elif l["kind"] == "layernorm":
                 ctx.sqnorms_layernorm(l["X"], l["G"], n)
+            elif l["kind"] == "tied_embedding":   # lookup table that is also the output projection; G = dY
+                ctx.sqnorms_tied_embedding(l["ids"], l["G"], l["H"], l["dL"], n)
             else:
                 ctx.sqnorms_embedding(l["ids"], l["G"], l["V"], l["distinct"], n)
         for key, ls in groups.items():
@@ -91,6 +93,8 @@ class StepRunner:
                     ctx.clip_accumulate_dense(l["A"], l["G"], C, n, self.view(self.S, k, 0), sb)
             elif l["kind"] == "layernorm":
                 ctx.clip_accumulate_layernorm(l["X"], l["G"], C, n, self.view(self.S, k, 0), self.view(self.S, k, 1))
+            elif l["kind"] == "tied_embedding":
+                ctx.clip_accumulate_tied_embedding(l["ids"], l["G"], l["H"], l["dL"], C, n, self.view(self.S, k, 0))
             elif l.get("distinct"):
                 ctx.clip_accumulate_positions(l["G"], C, n, self.view(self.S, k, 0))   # position ids: no sort needed
             else:

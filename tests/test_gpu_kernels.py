@@ -556,6 +556,67 @@ def test_clip_accumulate_positions(dp, dtype, B, T, d, V):
 
 
 # ------------------------------------------------------------------------------------------------
+# a table used as lookup and as output projection (tied weights)
+# ------------------------------------------------------------------------------------------------
+def _tied_case(dtype, B, T, M, d, V, seed):
+    ids = syn.zipf_ids(B, T, V, 1.1, seed)
+    dY = gen((B, T, d), 0.3, seed + 1, dtype)
+    H = gen((B, M, d), 1.0, seed + 2, dtype)
+    dLf = syn.normal_f32((B, M, V), 0.02, seed + 3)
+    labels = syn.zipf_ids(B, max(M, 1), V, 1.1, seed + 4)
+    for i in range(B):
+        for m in range(M):
+            dLf[i, m, labels[i, m]] -= 0.5               # the label's column, as in a cross-entropy gradient
+            if m < min(M, T) and i % 2 == 0:
+                dLf[i, m, ids[i, m]] -= 0.25             # predicted tokens that also occur in the input: a large cross term
+    if M > 1:
+        dLf[B // 2, M - 1] = 0.0                         # an unused prediction slot
+    dL = syn.f32_to_bf16_bits(dLf) if dtype == "bf16" else dLf
+    return ids, dY, H, dL
+
+
+@pytest.mark.parametrize("dtype,B,T,M,d,V", [("bf16", 6, 128, 20, 128, 1024), ("bf16", 3, 40, 5, 72, 200), ("bf16", 2, 160, 80, 64, 512),
+                                             ("bf16", 4, 33, 33, 8, 64), ("f32", 5, 19, 7, 20, 50), ("f32", 2, 70, 3, 130, 33),
+                                             ("bf16", 3, 16, 0, 64, 64)])
+def test_tied_embedding_norms_and_sums(dp, dtype, B, T, M, d, V):
+    ids, dY, H, dL = _tied_case(dtype, B, T, M, d, V, 800)
+    n0 = np.linspace(0.5, 1.5, B).astype(np.float32)     # the entry point adds to what is there
+    n = f32_dev(n0)
+    args = (to_dev(ids), to_dev(dY), to_dev(H), to_dev(dL))
+    dp.sqnorms_tied_embedding(*args, n)
+    dp.sync()
+    ref = orc.sqnorms_tied_embedding(ids, dY, H, dL)
+    # bf16 products are exact in fp32 on both sides; what is left is fp32 summation order
+    tol = 2e-5 if dtype == "f32" else 1e-4
+    assert_norms_close(host(n).astype(np.float64) - n0, ref, tol, "tied norms")
+    if M and T:
+        parts = orc.sqnorms_embedding(ids, dY, V) + orc.sqnorms_dense(dL, H, False)
+        assert np.abs(ref - parts).max() > 20 * tol * ref.max()   # dropping the cross term would be far outside the bound
+    C = float(np.sqrt(np.median(ref)))                   # about half of the examples clipped
+    sq = ref.astype(np.float32)
+    c = orc.clip_factors(sq.astype(np.float64), C)
+    S_ref = orc.clip_accumulate_tied_embedding(ids, dY, H, dL, c)
+    init = syn.normal_f32((V, d), float(np.abs(S_ref).mean()), 801)
+    S = f32_dev(init)
+    dp.clip_accumulate_tied_embedding(*args, C, f32_dev(sq), S)
+    dp.sync()
+    assert_sums_close(host(S).astype(np.float64) - init, S_ref, 1e-5 if dtype == "f32" else TOL_BF16, "tied sum")
+
+
+def test_tied_embedding_out_of_range_id_is_reported(dp):
+    import paper_2108_01624_amd as pkg
+
+    ids, dY, H, dL = _tied_case("bf16", 2, 8, 3, 8, 16, 810)
+    ids[1, 2] = 16
+    n = torch.zeros(2, dtype=torch.float32, device=DEV)
+    dp.sqnorms_tied_embedding(to_dev(ids), to_dev(dY), to_dev(H), to_dev(dL), n)
+    with pytest.raises(pkg.DpError) as e:
+        dp.sync()
+    assert e.value.status == -6
+    dp.sync()
+
+
+# ------------------------------------------------------------------------------------------------
 # several same-shaped dense layers in one call
 # ------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("n,B,T,d_in,d_out", [(3, 8, 128, 256, 384), (18, 2, 32, 256, 256), (5, 16, 128, 512, 256),
