@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--share-qkv", action="store_true",
                     help="comparison run: the query, key and value layers of a block are given ONE input tensor, as in a "
                          "real attention block (the metric's workload keeps an input tensor per layer)")
+    ap.add_argument("--tied-pred", type=int, default=0,
+                    help="comparison run: the token table (padded to 30,528 rows) is also the output projection of this many "
+                         "prediction slots per example (tied weights); the metric's workload has none")
     ap.add_argument("--batch", type=int, default=0, help="override the micro-batch size (parity/debug only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-examples", type=int, default=0, help="examples in the oracle sample (0 = auto)")
@@ -86,6 +89,10 @@ def main():
     B = args.batch or cfg["B"]
     T = cfg["T"]
     manifest = cfg["manifest"]()
+    if args.tied_pred:
+        if args.workload == "C2":
+            raise SystemExit("--tied-pred needs a workload with a token table (C3, C4, C5)")
+        manifest = syn.bert_manifest(24, 1024, 4096, 30528, 512, tied_pred=args.tied_pred)
     upd = syn.CONFIGS["C4"]  # update hyper-parameters of the mega-batch workload
     t_gen = time.perf_counter()
     layers = syn.device_layer_inputs(manifest, B, T, dtype=cfg["dtype"], act_std=cfg["act_std"],
@@ -101,7 +108,7 @@ def main():
     seen, in_bytes = set(), 0
     for l in layers:
         for k, t in l.items():
-            if k in ("A", "G", "X", "ids") and t.data_ptr() not in seen:
+            if k in ("A", "G", "X", "ids", "H", "dL") and t.data_ptr() not in seen:
                 seen.add(t.data_ptr())
                 in_bytes += t.numel() * t.element_size()
 
@@ -191,7 +198,7 @@ def main():
                                f"micro-batch B={B}, seq T={T}, bf16 inputs / fp32 accumulation, C={cfg['C']}; "
                                f"one step = norms + clip-accumulate over all layers + noise/AdamW over all params"
                                if args.workload != "C2" else f"C2: BERT-Base-shaped stack, B={B}, T={T}",
-                   "params": int(run.P), "micro_batch": B, "micro_batches_per_step": n_micro, "seq_len": T, "norm_path": args.path, "shared_qkv_input": bool(args.share_qkv),
+                   "params": int(run.P), "micro_batch": B, "micro_batches_per_step": n_micro, "seq_len": T, "norm_path": args.path, "shared_qkv_input": bool(args.share_qkv), "tied_prediction_slots": int(args.tied_pred),
                    "input_bytes": int(in_bytes)},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,

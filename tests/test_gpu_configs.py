@@ -38,18 +38,18 @@ def _slice_layers(layers, n):
     out = []
     for l in layers:
         d = dict(l)
-        for k in ("A", "G", "X", "ids"):
+        for k in ("A", "G", "X", "ids", "H", "dL"):
             if k in d:
                 d[k] = d[k][:n]
         out.append(d)
     return out
 
 
-def _compare_all_tensors(run, man, sums_ref, tol):
+def _compare_all_tensors(run, man, sums_ref, tol, first=0):
     worst = 0.0
     for k, spec in enumerate(man):
         for j, (name, shp) in enumerate(spec.tensors()):
-            got = host(run.view(run.S, k, j))
+            got = host(run.view(run.S, first + k, j))
             worst = max(worst, assert_sums_close(got, sums_ref[k][j], tol, name))
     return worst
 
@@ -384,6 +384,85 @@ def test_c4_micro_batch_of_1024_dense_layer_and_linearity():
         Gc = G[:, :, torch.as_tensor(qs, device=DEV)].float().cpu().numpy()
         ref = orc.clip_accumulate_dense_entries(Ac, Gc, orc.clip_factors(host(sq).astype(np.float64), C))
         got = host(single[0])[ps, qs].astype(np.float64)
+        assert np.linalg.norm(got - ref) <= 5e-3 * np.linalg.norm(ref)
+
+
+# ------------------------------------------------------------------------------------------------
+# the token table tied to the output projection of the prediction slots
+# ------------------------------------------------------------------------------------------------
+def test_tied_output_projection_small_bert_all_tensors():
+    """One block with position table and a token table that is also the output projection of 8 prediction slots:
+    every tensor of the clip-weighted sum against the oracle, both clip branches."""
+    import paper_2108_01624_amd as pkg
+
+    B, T = 6, 48
+    man = syn.bert_manifest(1, 256, 512, vocab=1000, max_pos=64, tied_pred=8)
+    scale = np.array([30.0, 0.005, 30.0, 0.005, 1.0, 30.0], dtype=np.float32)
+    layers = syn.device_layer_inputs(man, B, T, dtype="bf16", act_std=1.0, grad_std=1e-2, data_seed=4242, device=DEV,
+                                     example_scale=scale)
+    hl = syn.host_layer_slice(layers, range(B))
+    sums_ref, n_ref, c_ref = orc.microbatch_clip_sum(hl, 1.0)
+    assert (c_ref < 1).any() and (c_ref == 1).any()
+    with pkg.Context() as ctx:
+        run = pkg.StepRunner(ctx, man, B, device=DEV)
+        n = run.pass1(layers)
+        run.pass2(layers, 1.0)
+        ctx.sync()
+        assert_norms_close(host(n), n_ref, 1e-4, "norms with a tied table")
+        _compare_all_tensors(run, man[1:], sums_ref[1:], TOL_BF16, first=1)
+        # the tied table: a few rows (labels, frequent tokens) are orders of magnitude larger than the rest, and the
+        # rounding of c*h to bf16 on the general GEMM path scales with the row, so entries are held against their row's rms
+        got, ref = host(run.view(run.S, 0, 0)).astype(np.float64), sums_ref[0][0]
+        assert np.linalg.norm(got - ref) <= 5e-3 * np.linalg.norm(ref)
+        row_rms = np.sqrt((ref ** 2).mean(axis=1, keepdims=True))
+        assert np.all(np.abs(got - ref) <= TOL_BF16 * (np.abs(ref) + row_rms)), np.abs(got - ref).max()
+        # the tied layer alone: its norm is not the sum of its two uses
+        tied = hl[0]
+        assert tied["kind"] == "tied_embedding"
+        whole = orc.sqnorms_tied_embedding(tied["ids"], tied["G"], tied["H"], tied["dL"])
+        parts = orc.sqnorms_embedding(tied["ids"], tied["G"], tied["V"]) + orc.sqnorms_dense(tied["dL"], tied["H"], False)
+        assert np.abs(whole - parts).max() > 1e-3 * whole.max()
+
+
+def test_tied_output_projection_full_size_sampled():
+    """BERT-Large word-piece table (30,522 rows padded to 30,528, width 1,024) tied to the output projection of 20
+    prediction slots, B = 512, T = 128: norms of sampled examples and sampled entries of the sum from the oracle."""
+    import paper_2108_01624_amd as pkg
+
+    B, T, M, V, d, C = 512, 128, 20, 30528, 1024, 1.0
+    man = [syn.LayerSpec("emb.tok", "tied_embedding", V, d, n_pred=M)]
+    l = syn.device_layer_inputs(man, B, T, dtype="bf16", act_std=1.0, grad_std=1e-2, data_seed=5151, device=DEV)[0]
+    rng = np.random.default_rng(5151)
+    with pkg.Context() as ctx:
+        n = torch.zeros(B, dtype=torch.float32, device=DEV)
+        ctx.sqnorms_tied_embedding(l["ids"], l["G"], l["H"], l["dL"], n)
+        ctx.sync()
+        n_gpu = host(n).astype(np.float64)
+        sample = [0, int(rng.integers(1, B - 1)), B - 1]
+        hs = syn.host_layer_slice([l], sample)[0]
+        n_ref = orc.sqnorms_tied_embedding(hs["ids"], hs["G"], hs["H"], hs["dL"])
+        assert_norms_close(n_gpu[sample], n_ref, 1e-4, "tied table, sampled norms")
+        assert np.isfinite(n_gpu).all() and (n_gpu > 0).all()
+
+        sq = syn.synthetic_sqnorms(B, C, 5156)
+        c_ref = orc.clip_factors(sq.astype(np.float64), C)
+        S = torch.zeros(V, d, dtype=torch.float32, device=DEV)
+        ctx.clip_accumulate_tied_embedding(l["ids"], l["G"], l["H"], l["dL"], C, f32_dev(sq), S)
+        ctx.sync()
+        ids_h = host(l["ids"])
+        frequent = np.bincount(ids_h.reshape(-1), minlength=V).argsort()[::-1][:12]   # rows that the lookup writes too
+        vs = np.concatenate([frequent, rng.integers(0, V, size=12)])
+        ks = rng.integers(0, d, size=vs.size)
+        kt = torch.as_tensor(ks, device=DEV)
+        # output-projection part: a dense sum with input dL and output gradient H, entry (v, k)
+        Ac = l["dL"][:, :, torch.as_tensor(vs, device=DEV)].float().cpu().numpy()
+        Gc = l["H"][:, :, kt].float().cpu().numpy()
+        ref = orc.clip_accumulate_dense_entries(Ac, Gc, c_ref)
+        # lookup part: the scatter restricted to the sampled columns
+        ref += orc.clip_accumulate_embedding(ids_h, l["G"][:, :, kt].float().cpu().numpy(), c_ref, V)[vs, np.arange(vs.size)]
+        got = host(S)[vs, ks].astype(np.float64)
+        scale = np.sqrt(np.mean(ref ** 2))
+        assert np.all(np.abs(got - ref) <= TOL_BF16 * (np.abs(ref) + scale)), (np.abs(got - ref).max(), scale)
         assert np.linalg.norm(got - ref) <= 5e-3 * np.linalg.norm(ref)
 
 
