@@ -500,7 +500,7 @@ dp_status dp_clip_accumulate_tied_embedding(dp_ctx* ctx, const int32_t* ids, con
         TRY(dpk_embedding_sums(ctx, ids, dY, dtype, B, T, d, V, ctx->cbuf, sum_E));
     }
     if (M == 0) return DP_OK;
-    return dpk_weighted_gemm(ctx, dL, H, dtype, B, M, V, d, sqnorms, C, sum_E, nullptr);
+    return dpk_tied_projection_sums(ctx, H, dL, dtype, B, M, d, V, sqnorms, C, sum_E);
 }
 
 static dp_status noise_adamw_checked(dp_ctx* ctx, float* params, float* m, float* v, float* sum, uint64_t n,

@@ -18,6 +18,7 @@ struct dp_ctx {
     int device;
     char* ws;         // device workspace
     size_t ws_bytes;
+    size_t ws_base;   // bytes at the start of the workspace held by an enclosing step of the current call
     int* err_word;    // device: bit 0 = token id out of range
     float* cbuf;      // device: clip factors of the current micro-batch
     int cbuf_cap;     // capacity of cbuf in floats
@@ -78,7 +79,7 @@ static inline size_t dp_align_up(size_t x, size_t a) { return (x + a - 1) / a * 
 struct dp_ws_alloc {
     dp_ctx* ctx;
     size_t off;
-    explicit dp_ws_alloc(dp_ctx* c) : ctx(c), off(0) {}
+    explicit dp_ws_alloc(dp_ctx* c) : ctx(c), off(c->ws_base) {}
     template <typename T>
     T* get(size_t count) {
         size_t o = dp_align_up(off, 256);
@@ -91,6 +92,14 @@ struct dp_ws_alloc {
         size_t o = dp_align_up(off, 256);
         return o >= ctx->ws_bytes ? 0 : ctx->ws_bytes - o;
     }
+};
+
+// Keeps what `a` has handed out so far while launchers called inside the scope take workspace of their own.
+struct dp_ws_hold {
+    dp_ctx* ctx;
+    size_t saved;
+    explicit dp_ws_hold(const dp_ws_alloc& a) : ctx(a.ctx), saved(a.ctx->ws_base) { ctx->ws_base = dp_align_up(a.off, 256); }
+    ~dp_ws_hold() { ctx->ws_base = saved; }
 };
 
 // ------------------------------------------------------------------------------------------------
@@ -186,5 +195,8 @@ dp_status dpk_embedding_sqnorms(dp_ctx*, const int32_t* ids, const void* G, dp_d
                                 int distinct, float* sqnorms);
 dp_status dpk_embedding_sums(dp_ctx*, const int32_t* ids, const void* G, dp_dtype, int B, int T, int d, int V,
                              const float* c, float* sum_E);
+// sum_E += sum_i c_i dL_i^T H_i   (the output-projection part of a tied table's clip-weighted sum)
+dp_status dpk_tied_projection_sums(dp_ctx*, const void* H, const void* dL, dp_dtype, int B, int M, int d, int V,
+                                   const float* sqnorms, float C, float* sum_E);
 dp_status dpk_tied_cross_sqnorms(dp_ctx*, const int32_t* ids, const void* dY, const void* H, const void* dL, dp_dtype,
                                  int B, int T, int M, int d, int V, float* sqnorms);

@@ -499,6 +499,194 @@ __global__ __launch_bounds__(256, WPC) void gram_pairs_dma_kernel(GramBatch gb, 
     if (threadIdx.x == 0) out[((size_t)i * gb.n_layers + layer) * npairs + pair] = tot;
 }
 
+// ------------------------------------------------------------------------------------------------
+// T <= 32 (the output projection of a tied table has 20 rows per example and a 30K-wide input): one 32 x 32 Gram tile
+// per operand, so the 128-row kernels above would spend their time on empty rows.  One workgroup per example, the
+// contraction split over the 8 waves in chunks of 128 columns; fragments come straight from global memory (lane =
+// (row, half) reads 128 contiguous bytes per chunk, the two lanes of a row 256; the MFMA's k slots take the same
+// columns for both operands of X X^T, which are the same registers).  The waves' accumulators meet in LDS.
+// Bound: HBM, B*T*(d_in+d_out)*2 bytes read once.
+// ------------------------------------------------------------------------------------------------
+constexpr int GS_WAVES = 8;   // waves per workgroup
+constexpr int GS_CHUNK = 128;  // columns per wave and step (each lane: 64 columns = 128 contiguous bytes)
+
+__device__ __forceinline__ void gram_small_load(const uint16_t* __restrict__ row, bool valid, int d, int kb, int half,
+                                                gram_i32x4 f[8]) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int k = kb + half * 64 + j * 8;  // widths are multiples of 8: a fragment lies inside the row or outside
+        if (valid && k < d) f[j] = __builtin_nontemporal_load(reinterpret_cast<const gram_i32x4*>(row + k));  // read once
+        else f[j] = gram_i32x4{0, 0, 0, 0};
+    }
+}
+
+__device__ __forceinline__ void gram_small_mfma(const gram_i32x4 f[8], f32x16_t& acc) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const bf16x8_t x = __builtin_bit_cast(bf16x8_t, f[j]);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, x, acc, 0, 0, 0);
+    }
+}
+
+// The loads of the next step are issued before the MFMAs of the current one (the kernel lives on bytes in flight):
+// two register sets take turns.
+__device__ __forceinline__ void gram_small_accumulate(const uint16_t* __restrict__ row, bool valid, int d, int wave, int half,
+                                                      f32x16_t& acc) {
+    constexpr int STEP = GS_WAVES * GS_CHUNK;
+    gram_i32x4 f0[8], f1[8];
+    int kb = wave * GS_CHUNK;
+    if (kb >= d) return;
+    gram_small_load(row, valid, d, kb, half, f0);
+    while (true) {
+        if (kb + STEP < d) gram_small_load(row, valid, d, kb + STEP, half, f1);
+        gram_small_mfma(f0, acc);
+        kb += STEP;
+        if (kb >= d) break;
+        if (kb + STEP < d) gram_small_load(row, valid, d, kb + STEP, half, f0);
+        gram_small_mfma(f1, acc);
+        kb += STEP;
+        if (kb >= d) break;
+    }
+}
+
+__global__ __launch_bounds__(64 * GS_WAVES, 4) void gram_small_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ G,
+                                                                   int T, int d_in, int d_out, int has_bias,
+                                                                   float* __restrict__ out) {
+    __shared__ float part[GS_WAVES / 2][2][16][64];
+    __shared__ float wred[GS_WAVES];
+    const int i = blockIdx.x;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r32 = lane & 31, half = lane >> 5;
+    const bool valid = r32 < T;  // rows from T on stay zero in both Gram tiles
+    const size_t row = (size_t)i * T + (valid ? r32 : 0);
+    f32x16_t accA, accG;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) accA[r] = 0.f;
+    gram_small_accumulate(A + row * d_in, valid, d_in, wave, half, accA);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) accG[r] = 0.f;
+    gram_small_accumulate(G + row * d_out, valid, d_out, wave, half, accG);
+    // waves w + 4 hand their tiles to waves w, then the four sums meet
+    constexpr int HW = GS_WAVES / 2;
+    if (wave >= HW) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            part[wave - HW][0][r][lane] = accA[r];
+            part[wave - HW][1][r][lane] = accG[r];
+        }
+    }
+    __syncthreads();
+    if (wave < HW) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            accA[r] += part[wave][0][r][lane];
+            accG[r] += part[wave][1][r][lane];
+        }
+    }
+    __syncthreads();
+    if (wave < HW) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            part[wave][0][r][lane] = accA[r];
+            part[wave][1][r][lane] = accG[r];
+        }
+    }
+    __syncthreads();
+    const float bias_term = has_bias ? 1.f : 0.f;
+    float s = 0.f;
+#pragma unroll
+    for (int q = 0; q < 16 / GS_WAVES; ++q) {  // wave w finishes accumulator registers 2w, 2w+1; partial tiles added in index order
+        const int r = wave * (16 / GS_WAVES) + q;
+        const float a = ((part[0][0][r][lane] + part[1][0][r][lane]) + part[2][0][r][lane]) + part[3][0][r][lane];
+        const float g = ((part[0][1][r][lane] + part[1][1][r][lane]) + part[2][1][r][lane]) + part[3][1][r][lane];
+        s += (a + bias_term) * g;
+    }
+    const float tot = dp_block_sum<64 * GS_WAVES>(s, wred);
+    if (threadIdx.x == 0) out[i] += tot;
+}
+
+// The same tile fed like gram_dma_kernel (widths multiples of 64): 128-byte row segments of the 32 rows go straight
+// into a ring of 4 KiB stages (one 16-byte-per-lane load per wave and stage, coalesced over 8 rows), and wave w takes
+// k step w of every stage: one fragment read and one MFMA per wave and stage.  Loading fragments from global memory
+// directly, as the kernel above does, touches 16 bytes of 40 different lines per instruction and was bound by L1/L2
+// traffic (1.9 TB/s); here every line crosses once.  NS - 1 stages in flight per workgroup, two workgroups per CU.
+template <int NS>
+__global__ __launch_bounds__(256, 2) void gram_small_dma_kernel(const uint16_t* __restrict__ A, const uint16_t* __restrict__ G,
+                                                                int T, int d_in, int d_out, int has_bias,
+                                                                float* __restrict__ out) {
+    constexpr int GDK = 64, ROWS = 32, STAGE = ROWS * GDK, CPR = 8, RPI = 8;  // 4 loads fill a stage: one per wave
+    static_assert(NS * STAGE * 2 >= 4 * 2 * 16 * 64 * 4, "the ring doubles as the reduction buffer");
+    __shared__ __attribute__((aligned(16))) uint16_t ring[NS][STAGE];
+    __shared__ float wred[4];
+    const int i = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nchA = d_in / GDK, nch = nchA + d_out / GDK;
+    auto swz = [](int r) { return (r >> 1) & 7; };  // chunk position c of row r holds global chunk c ^ swz(r)
+    // rows >= T lie outside the example's byte range and read as zero
+    const gram_i32x4 rA = gram_rsrc(A + (size_t)i * T * d_in, (uint32_t)((size_t)T * d_in * 2));
+    const gram_i32x4 rG = gram_rsrc(G + (size_t)i * T * d_out, (uint32_t)((size_t)T * d_out * 2));
+    const int lrow = wave * RPI + lane / CPR;
+    const int cg = (lane % CPR) ^ swz(lrow);
+    const int voffA = (lrow * d_in + cg * 8) * 2, voffG = (lrow * d_out + cg * 8) * 2;
+    const uint32_t ldsoff = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)&ring[0][wave * RPI * GDK];
+    int ibuf = 0;  // buffer of the next stage to issue
+    auto issue = [&](int st) {
+        const bool isA = st < nchA;
+        const int soff = __builtin_amdgcn_readfirstlane((isA ? st : st - nchA) * GDK * 2);
+        const uint32_t dst = __builtin_amdgcn_readfirstlane(ldsoff + ibuf * (STAGE * 2));
+        if (isA) gram_dma16<true>(rA, dst, voffA, soff);
+        else if (st >= nch) gram_dma16<true>(rG, dst, voffG, 0x7FFFFFF0);  // past the end: reads zeros, keeps the load count uniform
+        else gram_dma16<true>(rG, dst, voffG, soff);
+        ibuf = ibuf + 1 == NS ? 0 : ibuf + 1;
+    };
+    const int r = lane & 31;
+    const int fpos = r * GDK + (((2 * wave + (lane >> 5)) ^ swz(r)) << 3);  // this wave's k step of a stage
+    f32x16_t accA, accG;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) accA[q] = accG[q] = 0.f;
+#pragma unroll
+    for (int st = 0; st < NS - 1; ++st) issue(st);
+    int cbuf = 0, s = 0;
+    auto phase = [&](int end, f32x16_t& acc) {
+        for (; s < end; ++s) {
+            // my load of stage s has landed (later ones may be in flight); after the barrier everyone's have, and
+            // everyone is done reading stage s-1, whose buffer the newest stage overwrites
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NS - 2) : "memory");
+            __syncthreads();
+            issue(s + NS - 1);
+            const bf16x8_t x = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(ring[cbuf] + fpos));
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, x, acc, 0, 0, 0);
+            cbuf = cbuf + 1 == NS ? 0 : cbuf + 1;
+        }
+    };
+    phase(nchA, accA);
+    phase(nch, accG);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing may still be writing LDS when the ring is reused
+    __syncthreads();
+    float* part = reinterpret_cast<float*>(&ring[0][0]);  // [wave][A|G][register][lane]
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        part[((wave * 2 + 0) * 16 + q) * 64 + lane] = accA[q];
+        part[((wave * 2 + 1) * 16 + q) * 64 + lane] = accG[q];
+    }
+    __syncthreads();
+    const float bias_term = has_bias ? 1.f : 0.f;
+    float sum = 0.f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {  // wave w finishes accumulator registers 4w .. 4w+3, the waves' partial tiles added in index order
+        const int reg = wave * 4 + q;
+        float a = 0.f, g = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            a += part[((w * 2 + 0) * 16 + reg) * 64 + lane];
+            g += part[((w * 2 + 1) * 16 + reg) * 64 + lane];
+        }
+        sum += (a + bias_term) * g;
+    }
+    const float tot = dp_block_sum<256>(sum, wred);
+    if (threadIdx.x == 0) out[i] += tot;
+}
+
 // fp32 reference-precision paths (small shapes; parity configuration with fp32 inputs).
 // One workgroup per example; thread-strided loop over the pairs t <= s.
 __global__ __launch_bounds__(256) void gram_f32_kernel(const float* __restrict__ A, const float* __restrict__ G, int T,
@@ -732,6 +920,20 @@ dp_status dpk_gram_sqnorms(dp_ctx* ctx, const void* A, const void* G, dp_dtype d
         hipLaunchKernelGGL(gram_f32_kernel, dim3(B), dim3(256), 0, ctx->stream, (const float*)A, (const float*)G, T,
                            d_in, d_out, has_bias, sqnorms);
         DP_LAUNCH_CHECK(ctx, "gram_f32");
+        return DP_OK;
+    }
+    if (T <= 32 && d_in % 64 == 0 && d_out % 64 == 0 && 64l * (d_in > d_out ? d_in : d_out) < (1l << 31)) {
+        dp_prof_scope prof(ctx, DP_PROF_GRAM, 2.0 * (double)B * T * ((double)d_in + d_out));
+        hipLaunchKernelGGL((gram_small_dma_kernel<16>), dim3(B), dim3(256), 0, ctx->stream, (const uint16_t*)A,
+                           (const uint16_t*)G, T, d_in, d_out, has_bias, sqnorms);
+        DP_LAUNCH_CHECK(ctx, "gram_small_dma");
+        return DP_OK;
+    }
+    if (T <= 32) {
+        dp_prof_scope prof(ctx, DP_PROF_GRAM, 2.0 * (double)B * T * ((double)d_in + d_out));
+        hipLaunchKernelGGL(gram_small_kernel, dim3(B), dim3(64 * GS_WAVES), 0, ctx->stream, (const uint16_t*)A, (const uint16_t*)G, T,
+                           d_in, d_out, has_bias, sqnorms);
+        DP_LAUNCH_CHECK(ctx, "gram_small");
         return DP_OK;
     }
     const int nblk = (T + GB - 1) / GB;

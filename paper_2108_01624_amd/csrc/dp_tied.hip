@@ -10,6 +10,8 @@
 //
 // Roofline: HBM, B*(T+M)*d*E bytes read once plus B*T*M gathered elements (each its own 32-byte sector of dL);
 // 2*T*M*d flops per example are far below the machine balance.
+#include <stdlib.h>
+
 #include "dp_common.h"
 
 namespace {
@@ -102,7 +104,54 @@ __global__ __launch_bounds__(256) void tied_cross_f32_kernel(const int32_t* __re
     if (threadIdx.x == 0) sqnorms[i] += 2.f * tot;
 }
 
+// Hs[i, :] = bf16(c_i * H[i, :]) (round to nearest even), rows of `row_len` elements, 8 elements per thread.
+__global__ __launch_bounds__(256) void scale_rows_bf16_kernel(const uint16_t* __restrict__ H, const float* __restrict__ c,
+                                                              size_t n8, int row_len8, uint16_t* __restrict__ Hs) {
+    const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= n8) return;
+    const float ci = c[j / row_len8];
+    const uint4 w = *reinterpret_cast<const uint4*>(H + j * 8);
+    uint4 o;
+    o.x = dp_pack_bf16x2(ci * dp_bf16_lo(w.x), ci * dp_bf16_hi(w.x));
+    o.y = dp_pack_bf16x2(ci * dp_bf16_lo(w.y), ci * dp_bf16_hi(w.y));
+    o.z = dp_pack_bf16x2(ci * dp_bf16_lo(w.z), ci * dp_bf16_hi(w.z));
+    o.w = dp_pack_bf16x2(ci * dp_bf16_lo(w.w), ci * dp_bf16_hi(w.w));
+    *reinterpret_cast<uint4*>(Hs + j * 8) = o;
+}
+
 }  // namespace
+
+// The output projection's sum is a dense sum with input dL [B, M, V] and output gradient H [B, M, d].  M (20 or 80
+// prediction slots) is not a multiple of the fast GEMM's 64-row example granularity, but H is small: its rows are
+// multiplied by c_i once (rounded to bf16, which is what the general GEMM does with every element it stages), and
+// the B*M rows are then contracted as B*M/64 blocks of 64 rows with factor 1 by the fast kernel.
+dp_status dpk_tied_projection_sums(dp_ctx* ctx, const void* H, const void* dL, dp_dtype dt, int B, int M, int d, int V,
+                                   const float* sqnorms, float C, float* sum_E) {
+    static int flat = -1;
+    if (flat < 0) {  // DPCLIP_TIED_FLAT=0: always the general GEMM (tuning aid)
+        const char* e = getenv("DPCLIP_TIED_FLAT");
+        flat = (e && e[0] == '0') ? 0 : 1;
+    }
+    const long rows = (long)B * M;
+    if (flat && dt == DP_BF16 && rows % 64 == 0 && M % 64 != 0 && V >= 256 && d >= 256 && rows / 64 <= ctx->cbuf_cap) {
+        dp_ws_alloc ws(ctx);
+        uint16_t* Hs = ws.get<uint16_t>((size_t)rows * d);
+        float* zero = ws.get<float>((size_t)(rows / 64));
+        if (Hs && zero) {
+            dp_status st = dpk_clip_factors(ctx, sqnorms, B, C, ctx->cbuf);
+            if (st != DP_OK) return st;
+            const size_t n8 = (size_t)rows * d / 8;
+            hipLaunchKernelGGL(scale_rows_bf16_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, ctx->stream,
+                               (const uint16_t*)H, ctx->cbuf, n8, M * d / 8, Hs);
+            DP_LAUNCH_CHECK(ctx, "scale_rows_bf16");
+            st = dpk_zero_f32(ctx, zero, (uint64_t)(rows / 64));  // squared norm 0 -> factor 1 for every block of rows
+            if (st != DP_OK) return st;
+            dp_ws_hold hold(ws);
+            return dpk_weighted_gemm(ctx, dL, Hs, dt, (int)(rows / 64), 64, V, d, zero, C, sum_E, nullptr);
+        }
+    }
+    return dpk_weighted_gemm(ctx, dL, H, dt, B, M, V, d, sqnorms, C, sum_E, nullptr);
+}
 
 // sqnorms[i] += 2 * sum_{t,m} dL[i,m,ids[i,t]] * <dY[i,t,:], H[i,m,:]>
 dp_status dpk_tied_cross_sqnorms(dp_ctx* ctx, const int32_t* ids, const void* dY, const void* H, const void* dL,

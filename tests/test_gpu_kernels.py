@@ -222,6 +222,11 @@ DENSE_SHAPES = [
     ("bf16", 3, 300, 128, 192),   # 3 x 3 blocks, ragged last block, widths the block-pair ring kernel takes
     ("bf16", 2, 129, 64, 64),     # one row into the second block
     ("bf16", 11, 256, 320, 64),   # 2 x 2 blocks, 11 examples over the 8 XCD lanes
+    ("bf16", 4, 20, 1032, 72),    # T <= 32: the one-tile kernel, widths that end inside a 128-column chunk
+    ("bf16", 3, 32, 520, 256),    # T = 32 exactly
+    ("bf16", 2, 33, 128, 64),     # one row more: back to the 128-row kernels
+    ("bf16", 5, 20, 1984, 192),   # T <= 32, widths multiples of 64: the ring-fed one-tile kernel, more stages than the ring holds
+    ("bf16", 3, 32, 64, 128),     # ... and fewer
 ]
 
 
@@ -577,7 +582,7 @@ def _tied_case(dtype, B, T, M, d, V, seed):
 
 @pytest.mark.parametrize("dtype,B,T,M,d,V", [("bf16", 6, 128, 20, 128, 1024), ("bf16", 3, 40, 5, 72, 200), ("bf16", 2, 160, 80, 64, 512),
                                              ("bf16", 4, 33, 33, 8, 64), ("f32", 5, 19, 7, 20, 50), ("f32", 2, 70, 3, 130, 33),
-                                             ("bf16", 3, 16, 0, 64, 64)])
+                                             ("bf16", 3, 16, 0, 64, 64), ("bf16", 16, 24, 20, 256, 520)])
 def test_tied_embedding_norms_and_sums(dp, dtype, B, T, M, d, V):
     ids, dY, H, dL = _tied_case(dtype, B, T, M, d, V, 800)
     n0 = np.linspace(0.5, 1.5, B).astype(np.float32)     # the entry point adds to what is there
