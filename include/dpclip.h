@@ -113,6 +113,13 @@ dp_status dp_sqnorms_dense_shared(dp_ctx* ctx, int n_groups, const void* const* 
 dp_status dp_sqnorms_layernorm(dp_ctx* ctx, const void* Xhat, const void* G, dp_dtype dtype, int B, int T, int d,
                                float* sqnorms);
 
+/* n_layers LayerNorms of one shape in one call: the result of n_layers calls of dp_sqnorms_layernorm (layers added
+ * in index order).  Up to 16 layers share a launch; their per-example partial norms pass through the library
+ * workspace (DP_ERR_WORKSPACE if they do not fit).  Xhat, G: HOST arrays of n_layers device pointers, read during the
+ * call only. */
+dp_status dp_sqnorms_layernorm_batched(dp_ctx* ctx, int n_layers, const void* const* Xhat, const void* const* G,
+                                       dp_dtype dtype, int B, int T, int d, float* sqnorms);
+
 /* Embedding lookup y_t = E[ids_t] (Section 4.3 names the word-piece, positional and token-type tables):
  * sqnorms[i] += sum_v || sum_{t: ids[i,t] = v} G[i,t,:] ||^2.
  * distinct_per_example != 0 promises that no id repeats inside an example (position ids), which
@@ -147,6 +154,13 @@ dp_status dp_clip_accumulate_dense_batched(dp_ctx* ctx, int n_layers, const void
 /* sum_gamma[j] += sum_i c_i sum_t G[i,t,j] Xhat[i,t,j];  sum_beta[j] += sum_i c_i sum_t G[i,t,j]. */
 dp_status dp_clip_accumulate_layernorm(dp_ctx* ctx, const void* Xhat, const void* G, dp_dtype dtype, int B, int T,
                                        int d, float C, const float* sqnorms, float* sum_gamma, float* sum_beta);
+
+/* n_layers LayerNorms of one shape in one call: the result of n_layers calls of dp_clip_accumulate_layernorm, with
+ * one evaluation of the clip factors and up to 16 layers per launch.  Xhat, G, sum_gamma, sum_beta: HOST arrays of
+ * n_layers device pointers (none NULL), read during the call only. */
+dp_status dp_clip_accumulate_layernorm_batched(dp_ctx* ctx, int n_layers, const void* const* Xhat, const void* const* G,
+                                               dp_dtype dtype, int B, int T, int d, float C, const float* sqnorms,
+                                               float* const* sum_gamma, float* const* sum_beta);
 
 /* sum_E[ids[i,t], :] += c_i G[i,t,:] for every token.  Rows are added in ascending (i, t) order per id. */
 dp_status dp_clip_accumulate_embedding(dp_ctx* ctx, const int32_t* ids, const void* G, dp_dtype dtype, int B, int T,

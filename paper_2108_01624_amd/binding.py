@@ -40,6 +40,9 @@ SIGNATURES = {
     "dp_clip_accumulate_embedding": [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_float, c_void_p,
                                      c_void_p],
     "dp_clip_accumulate_positions": [c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_float, c_void_p, c_void_p],
+    "dp_sqnorms_layernorm_batched": [c_void_p, c_int, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_void_p],
+    "dp_clip_accumulate_layernorm_batched": [c_void_p, c_int, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_float,
+                                             c_void_p, c_void_p, c_void_p],
     "dp_sqnorms_tied_embedding": [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int,
                                   c_void_p],
     "dp_clip_accumulate_tied_embedding": [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int,
@@ -263,6 +266,34 @@ def dp_clip_accumulate_positions(ctx, G, C, sqnorms, sum_E):
         raise ValueError("sum_E must hold at least T rows")
     st = load_library().dp_clip_accumulate_positions(ctx, _ptr(G), _dtype_of(G), B, T, d, float(C), _f32(sqnorms), _f32(sum_E))
     _check(ctx, st, "dp_clip_accumulate_positions")
+
+
+def _same_shaped(Xs, Gs):
+    shp, dt = tuple(Xs[0].shape), Xs[0].dtype
+    for x, g in zip(Xs, Gs):
+        if tuple(x.shape) != shp or tuple(g.shape) != shp or x.dtype != dt or g.dtype != dt:
+            raise ValueError("all layers of a batch must share one shape and dtype")
+    return shp
+
+
+def dp_sqnorms_layernorm_batched(ctx, Xhats, Gs, sqnorms):
+    """Xhats, Gs: equally long lists of same-shaped tensors."""
+    n = len(Xhats)
+    B, T, d = _same_shaped(Xhats, Gs)
+    arr = lambda ptrs: (c_void_p * n)(*ptrs)
+    st = load_library().dp_sqnorms_layernorm_batched(ctx, n, arr([_ptr(t) for t in Xhats]), arr([_ptr(t) for t in Gs]),
+                                                     _dtype_of(Gs[0]), B, T, d, _f32(sqnorms))
+    _check(ctx, st, "dp_sqnorms_layernorm_batched")
+
+
+def dp_clip_accumulate_layernorm_batched(ctx, Xhats, Gs, C, sqnorms, sum_gammas, sum_betas):
+    n = len(Xhats)
+    B, T, d = _same_shaped(Xhats, Gs)
+    arr = lambda ptrs: (c_void_p * n)(*ptrs)
+    st = load_library().dp_clip_accumulate_layernorm_batched(
+        ctx, n, arr([_ptr(t) for t in Xhats]), arr([_ptr(t) for t in Gs]), _dtype_of(Gs[0]), B, T, d, float(C), _f32(sqnorms),
+        arr([_f32(t) for t in sum_gammas]), arr([_f32(t) for t in sum_betas]))
+    _check(ctx, st, "dp_clip_accumulate_layernorm_batched")
 
 
 def _tied_shapes(ids, dY, H, dL):

@@ -422,6 +422,44 @@ dp_status dp_clip_accumulate_layernorm(dp_ctx* ctx, const void* Xhat, const void
     return dpk_colstat_sums(ctx, Xhat, G, dtype, B, T, d, ctx->cbuf, sum_gamma, sum_beta);
 }
 
+dp_status dp_sqnorms_layernorm_batched(dp_ctx* ctx, int n_layers, const void* const* Xhat, const void* const* G,
+                                       dp_dtype dtype, int B, int T, int d, float* sqnorms) {
+    REQUIRE_CTX(ctx);
+    TRY(check_dtype(ctx, dtype));
+    TRY(check_bt(ctx, B, T));
+    if (n_layers < 0 || d < 0) FAIL(ctx, DP_ERR_SHAPE, "negative layer count or width");
+    if (n_layers == 0) return DP_OK;
+    if (!Xhat || !G) FAIL(ctx, DP_ERR_NULL, "a pointer table is NULL");
+    for (int l = 0; l < n_layers; ++l) {
+        TRY(check_tensor(ctx, "Xhat[l]", Xhat[l], dtype, d));
+        TRY(check_tensor(ctx, "G[l]", G[l], dtype, d));
+    }
+    TRY(check_f32(ctx, "sqnorms", sqnorms));
+    return dpk_colstat_sqnorms_batched(ctx, n_layers, Xhat, G, dtype, B, T, d, 1, 1, sqnorms);
+}
+
+dp_status dp_clip_accumulate_layernorm_batched(dp_ctx* ctx, int n_layers, const void* const* Xhat, const void* const* G,
+                                               dp_dtype dtype, int B, int T, int d, float C, const float* sqnorms,
+                                               float* const* sum_gamma, float* const* sum_beta) {
+    REQUIRE_CTX(ctx);
+    TRY(check_dtype(ctx, dtype));
+    TRY(check_bt(ctx, B, T));
+    if (n_layers < 0 || d < 0) FAIL(ctx, DP_ERR_SHAPE, "negative layer count or width");
+    if (n_layers == 0) return DP_OK;
+    if (!Xhat || !G || !sum_gamma || !sum_beta) FAIL(ctx, DP_ERR_NULL, "a pointer table is NULL");
+    for (int l = 0; l < n_layers; ++l) {
+        TRY(check_tensor(ctx, "Xhat[l]", Xhat[l], dtype, d));
+        TRY(check_tensor(ctx, "G[l]", G[l], dtype, d));
+        TRY(check_f32(ctx, "sum_gamma[l]", sum_gamma[l]));
+        TRY(check_f32(ctx, "sum_beta[l]", sum_beta[l]));
+    }
+    TRY(check_f32(ctx, "sqnorms", sqnorms));
+    TRY(check_clip(ctx, C, B));
+    if (B == 0 || T == 0 || d == 0) return DP_OK;
+    TRY(dpk_clip_factors(ctx, sqnorms, B, C, ctx->cbuf));
+    return dpk_colstat_sums_batched(ctx, n_layers, Xhat, G, dtype, B, T, d, ctx->cbuf, sum_gamma, sum_beta);
+}
+
 dp_status dp_clip_accumulate_embedding(dp_ctx* ctx, const int32_t* ids, const void* G, dp_dtype dtype, int B, int T,
                                        int d, int V, float C, const float* sqnorms, float* sum_E) {
     REQUIRE_CTX(ctx);

@@ -191,6 +191,11 @@ dp_status dpk_colstat_sqnorms(dp_ctx*, const void* X, const void* G, dp_dtype, i
 dp_status dpk_colstat_sums(dp_ctx*, const void* X, const void* G, dp_dtype, int B, int T, int d, const float* c,
                            float* out_x, float* out_1);
 
+dp_status dpk_colstat_sqnorms_batched(dp_ctx*, int n, const void* const* X, const void* const* G, dp_dtype, int B, int T, int d,
+                                      int use_x, int use_1, float* sqnorms);
+dp_status dpk_colstat_sums_batched(dp_ctx*, int n, const void* const* X, const void* const* G, dp_dtype, int B, int T, int d,
+                                   const float* c, float* const* out_x, float* const* out_1);
+
 dp_status dpk_embedding_sqnorms(dp_ctx*, const int32_t* ids, const void* G, dp_dtype, int B, int T, int d, int V,
                                 int distinct, float* sqnorms);
 dp_status dpk_embedding_sums(dp_ctx*, const int32_t* ids, const void* G, dp_dtype, int B, int T, int d, int V,

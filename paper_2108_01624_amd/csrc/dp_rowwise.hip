@@ -36,12 +36,26 @@ __device__ __forceinline__ void load_vec(const void* __restrict__ base, size_t i
 // column statistics, per example (pass 1)
 //   grid (B, ceil(d / (64*VW))), 256 threads = 4 row groups x 64 column lanes
 // ------------------------------------------------------------------------------------------------
+// Up to COL_MAX_BATCH same-shaped layers per launch (blockIdx.z = layer): the 48 LayerNorms of the model are 3 launches
+// per pass instead of 48, and their per-example partials meet in one ordered reduction.
+constexpr int COL_MAX_BATCH = 16;
+struct ColBatch {
+    const void* X[COL_MAX_BATCH];
+    const void* G[COL_MAX_BATCH];
+};
+struct ColOut {
+    float* out_x[COL_MAX_BATCH];
+    float* out_1[COL_MAX_BATCH];
+};
+
+// out: direct (one layer, one column block): sqnorms, "+="; otherwise partials [B][layers * J], stored
 template <bool BF16, int VW, bool USE_X, bool USE_1>
-__global__ __launch_bounds__(256) void colstat_sqnorms_kernel(const void* __restrict__ X, const void* __restrict__ G,
-                                                              int T, int d, float* __restrict__ out, int J,
+__global__ __launch_bounds__(256) void colstat_sqnorms_kernel(ColBatch cb, int T, int d, float* __restrict__ out, int J,
                                                               int direct) {
     __shared__ float red[4][64][2 * VW];
     __shared__ float wred[4];
+    const void* __restrict__ X = cb.X[blockIdx.z];
+    const void* __restrict__ G = cb.G[blockIdx.z];
     const int i = blockIdx.x;
     const int lane = threadIdx.x & 63, tg = threadIdx.x >> 6;
     const int col = (blockIdx.y * 64 + lane) * VW;
@@ -82,21 +96,22 @@ __global__ __launch_bounds__(256) void colstat_sqnorms_kernel(const void* __rest
     const float tot = dp_block_sum<256>(val, wred);
     if (threadIdx.x == 0) {
         if (direct) out[i] += tot;
-        else out[(size_t)i * J + blockIdx.y] = tot;
+        else out[((size_t)i * gridDim.z + blockIdx.z) * J + blockIdx.y] = tot;
     }
 }
 
 // ------------------------------------------------------------------------------------------------
 // clip-weighted column sums (pass 2)
 //   grid (R, ceil(d / (64*VW))): WG r reduces rows [r*rows_per, (r+1)*rows_per) of the B*T rows
-//   partial layout: part[r][0][d] = sum c g x,  part[r][1][d] = sum c g
+//   partial layout: part[layer][r][0][d] = sum c g x,  part[layer][r][1][d] = sum c g   (blockIdx.z = layer)
 // ------------------------------------------------------------------------------------------------
 template <bool BF16, int VW, bool USE_X>
 // (the clip factors come precomputed: forming them here, a square root and a division per row and thread, cost 2 %)
-__global__ __launch_bounds__(256) void colstat_sums_kernel(const void* __restrict__ X, const void* __restrict__ G,
-                                                           const float* __restrict__ c, int T, int d, long nrows,
-                                                           int rows_per, float* __restrict__ part) {
+__global__ __launch_bounds__(256) void colstat_sums_kernel(ColBatch cb, const float* __restrict__ c, int T, int d,
+                                                           long nrows, int rows_per, float* __restrict__ part) {
     __shared__ float red[4][64][2 * VW];
+    const void* __restrict__ X = cb.X[blockIdx.z];
+    const void* __restrict__ G = cb.G[blockIdx.z];
     const int lane = threadIdx.x & 63, tg = threadIdx.x >> 6;
     const int col = (blockIdx.y * 64 + lane) * VW;
     const long r0 = (long)blockIdx.x * rows_per;
@@ -127,7 +142,7 @@ __global__ __launch_bounds__(256) void colstat_sums_kernel(const void* __restric
     }
     __syncthreads();
     if (tg == 0 && col < d) {
-        float* p = part + (size_t)blockIdx.x * 2 * d;
+        float* p = part + ((size_t)blockIdx.z * gridDim.x + blockIdx.x) * 2 * d;
 #pragma unroll
         for (int k = 0; k < VW; ++k) {
             p[col + k] = (red[0][lane][k] + red[1][lane][k]) + (red[2][lane][k] + red[3][lane][k]);
@@ -210,14 +225,16 @@ __global__ __launch_bounds__(256) void reduce_partials_tall_kernel(const float4*
     }
 }
 
-// The two column-sum vectors of one partial buffer [R][2][d] in one launch: columns j < d4 go to out_x, the others to
-// out_1 (same order of additions as reduce_partials_tall_kernel).
+// The two column-sum vectors of every layer's partial buffer [R][2][d] in one launch: columns j < d4 go to out_x, the
+// others to out_1 (same order of additions as reduce_partials_tall_kernel).
 __global__ __launch_bounds__(256) void reduce_partials_pair_kernel(const float4* __restrict__ part, int R, size_t d4,
-                                                                   float4* __restrict__ out_x,
-                                                                   float4* __restrict__ out_1) {
+                                                                   ColOut co) {
     __shared__ float4 red[4][64];
     const int lane = threadIdx.x & 63, g = threadIdx.x >> 6;
     const size_t j = (size_t)blockIdx.x * 64 + lane, n4 = 2 * d4;
+    part += (size_t)blockIdx.y * R * n4;  // blockIdx.y = layer
+    float4* __restrict__ out_x = reinterpret_cast<float4*>(co.out_x[blockIdx.y]);
+    float4* __restrict__ out_1 = reinterpret_cast<float4*>(co.out_1[blockIdx.y]);
     float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
     if (j < n4) {
         int r = g;
@@ -555,84 +572,134 @@ dp_status dpk_reduce_partials(dp_ctx* ctx, const float* part, int R, size_t stri
 }
 
 template <bool BF16, int VW>
-static dp_status colstat_sqnorms_launch(dp_ctx* ctx, const void* X, const void* G, int B, int T, int d, int use_x,
-                                        int use_1, float* sqnorms) {
+static dp_status colstat_sqnorms_launch(dp_ctx* ctx, int L, const void* const* X, const void* const* G, int B, int T, int d,
+                                        int use_x, int use_1, float* sqnorms) {
     const int J = (d + 64 * VW - 1) / (64 * VW);
+    ColBatch cb;
+    for (int l = 0; l < COL_MAX_BATCH; ++l) {
+        cb.X[l] = use_x ? X[l < L ? l : 0] : nullptr;
+        cb.G[l] = G[l < L ? l : 0];
+    }
     float* out = sqnorms;
     int direct = 1;
-    if (J > 1) {
+    if (J > 1 || L > 1) {
         dp_ws_alloc ws(ctx);
-        out = ws.get<float>((size_t)B * J);
+        out = ws.get<float>((size_t)B * L * J);
         if (!out) {
-            DP_SET_ERR(ctx, "workspace too small for %d x %d norm partials", B, J);
+            DP_SET_ERR(ctx, "workspace too small for %d x %d norm partials", B, L * J);
             return DP_ERR_WORKSPACE;
         }
         direct = 0;
     }
-    dim3 grid(B, J);
+    dim3 grid(B, J, L);
     if (use_x && use_1)
-        hipLaunchKernelGGL((colstat_sqnorms_kernel<BF16, VW, true, true>), grid, dim3(256), 0, ctx->stream, X, G, T, d, out, J, direct);
+        hipLaunchKernelGGL((colstat_sqnorms_kernel<BF16, VW, true, true>), grid, dim3(256), 0, ctx->stream, cb, T, d, out, J, direct);
     else if (use_x)
-        hipLaunchKernelGGL((colstat_sqnorms_kernel<BF16, VW, true, false>), grid, dim3(256), 0, ctx->stream, X, G, T, d, out, J, direct);
+        hipLaunchKernelGGL((colstat_sqnorms_kernel<BF16, VW, true, false>), grid, dim3(256), 0, ctx->stream, cb, T, d, out, J, direct);
     else
-        hipLaunchKernelGGL((colstat_sqnorms_kernel<BF16, VW, false, true>), grid, dim3(256), 0, ctx->stream, X, G, T, d, out, J, direct);
+        hipLaunchKernelGGL((colstat_sqnorms_kernel<BF16, VW, false, true>), grid, dim3(256), 0, ctx->stream, cb, T, d, out, J, direct);
     DP_LAUNCH_CHECK(ctx, "colstat_sqnorms");
-    if (!direct) return dpk_finish_partials(ctx, out, B, J, sqnorms);
+    if (!direct) return dpk_finish_partials(ctx, out, B, L * J, sqnorms);  // layers, then column blocks, in index order
+    return DP_OK;
+}
+
+dp_status dpk_colstat_sqnorms_batched(dp_ctx* ctx, int n, const void* const* X, const void* const* G, dp_dtype dt, int B, int T,
+                                      int d, int use_x, int use_1, float* sqnorms) {
+    if (B == 0 || T == 0 || d == 0 || n == 0 || (!use_x && !use_1)) return DP_OK;
+    bool v4 = true;
+    for (int l = 0; l < n; ++l) v4 = v4 && vec4_ok(dt, d, use_x ? X[l] : G[l], G[l]);
+    for (int l0 = 0; l0 < n; l0 += COL_MAX_BATCH) {
+        const int L = n - l0 < COL_MAX_BATCH ? n - l0 : COL_MAX_BATCH;
+        const void* const* Xl = use_x ? X + l0 : nullptr;
+        dp_status st;
+        if (dt == DP_BF16) st = colstat_sqnorms_launch<true, 4>(ctx, L, Xl, G + l0, B, T, d, use_x, use_1, sqnorms);
+        else if (v4) st = colstat_sqnorms_launch<false, 4>(ctx, L, Xl, G + l0, B, T, d, use_x, use_1, sqnorms);
+        else st = colstat_sqnorms_launch<false, 1>(ctx, L, Xl, G + l0, B, T, d, use_x, use_1, sqnorms);
+        if (st != DP_OK) return st;
+    }
     return DP_OK;
 }
 
 dp_status dpk_colstat_sqnorms(dp_ctx* ctx, const void* X, const void* G, dp_dtype dt, int B, int T, int d, int use_x,
                               int use_1, float* sqnorms) {
-    if (B == 0 || T == 0 || d == 0 || (!use_x && !use_1)) return DP_OK;
-    if (dt == DP_BF16) return colstat_sqnorms_launch<true, 4>(ctx, X, G, B, T, d, use_x, use_1, sqnorms);
-    if (vec4_ok(dt, d, use_x ? X : G, G)) return colstat_sqnorms_launch<false, 4>(ctx, X, G, B, T, d, use_x, use_1, sqnorms);
-    return colstat_sqnorms_launch<false, 1>(ctx, X, G, B, T, d, use_x, use_1, sqnorms);
+    return dpk_colstat_sqnorms_batched(ctx, 1, &X, &G, dt, B, T, d, use_x, use_1, sqnorms);
 }
 
+// out_x / out_1: tables of L pointers, or NULL when that statistic is not wanted (the same for every layer of the call)
 template <bool BF16, int VW>
-static dp_status colstat_sums_launch(dp_ctx* ctx, const void* X, const void* G, int B, int T, int d, const float* c,
-                                     float* out_x, float* out_1) {
+static dp_status colstat_sums_launch(dp_ctx* ctx, int L, const void* const* X, const void* const* G, int B, int T, int d,
+                                     const float* c, float* const* out_x, float* const* out_1) {
     const long nrows = (long)B * T;
     const int J = (d + 64 * VW - 1) / (64 * VW);
-    long R = 1024 / J;  // about 1024 workgroups
+    long R = 1024 / J;  // about 1024 workgroups per layer
     if (R < 1) R = 1;
     const long maxR = (nrows + 63) / 64;
     if (R > maxR) R = maxR;
     const int rows_per = (int)((nrows + R - 1) / R);
     R = (nrows + rows_per - 1) / rows_per;
     dp_ws_alloc ws(ctx);
-    float* part = ws.get<float>((size_t)R * 2 * d);
+    float* part = ws.get<float>((size_t)L * R * 2 * d);
     if (!part) {
-        DP_SET_ERR(ctx, "workspace too small for column-sum partials (%ld x 2 x %d floats)", R, d);
+        DP_SET_ERR(ctx, "workspace too small for column-sum partials (%d x %ld x 2 x %d floats)", L, R, d);
         return DP_ERR_WORKSPACE;
     }
-    dim3 grid((unsigned)R, J);
+    ColBatch cb;
+    for (int l = 0; l < COL_MAX_BATCH; ++l) {
+        cb.X[l] = out_x ? X[l < L ? l : 0] : nullptr;
+        cb.G[l] = G[l < L ? l : 0];
+    }
+    dim3 grid((unsigned)R, J, L);
     if (out_x)
-        hipLaunchKernelGGL((colstat_sums_kernel<BF16, VW, true>), grid, dim3(256), 0, ctx->stream, X, G, c, T, d, nrows, rows_per, part);
+        hipLaunchKernelGGL((colstat_sums_kernel<BF16, VW, true>), grid, dim3(256), 0, ctx->stream, cb, c, T, d, nrows, rows_per, part);
     else
-        hipLaunchKernelGGL((colstat_sums_kernel<BF16, VW, false>), grid, dim3(256), 0, ctx->stream, X, G, c, T, d, nrows, rows_per, part);
+        hipLaunchKernelGGL((colstat_sums_kernel<BF16, VW, false>), grid, dim3(256), 0, ctx->stream, cb, c, T, d, nrows, rows_per, part);
     DP_LAUNCH_CHECK(ctx, "colstat_sums");
-    if (out_x && out_1 && d % 4 == 0 && R >= 32 && d <= 32768 &&
-        (((uintptr_t)part | (uintptr_t)out_x | (uintptr_t)out_1) & 15) == 0) {
+    bool pair = out_x && out_1 && d % 4 == 0 && R >= 32 && d <= 32768 && ((uintptr_t)part & 15) == 0;
+    for (int l = 0; pair && l < L; ++l) pair = (((uintptr_t)out_x[l] | (uintptr_t)out_1[l]) & 15) == 0;
+    if (pair) {
+        ColOut co;
+        for (int l = 0; l < COL_MAX_BATCH; ++l) {
+            co.out_x[l] = out_x[l < L ? l : 0];
+            co.out_1[l] = out_1[l < L ? l : 0];
+        }
         const size_t d4 = (size_t)d / 4;
-        hipLaunchKernelGGL(reduce_partials_pair_kernel, dim3((unsigned)((2 * d4 + 63) / 64)), dim3(256), 0, ctx->stream,
-                           reinterpret_cast<const float4*>(part), (int)R, d4, reinterpret_cast<float4*>(out_x),
-                           reinterpret_cast<float4*>(out_1));
+        hipLaunchKernelGGL(reduce_partials_pair_kernel, dim3((unsigned)((2 * d4 + 63) / 64), L), dim3(256), 0, ctx->stream,
+                           reinterpret_cast<const float4*>(part), (int)R, d4, co);
         DP_LAUNCH_CHECK(ctx, "reduce_partials_pair");
         return DP_OK;
     }
-    dp_status st = DP_OK;
-    if (out_x) st = dpk_reduce_partials(ctx, part, (int)R, (size_t)2 * d, d, out_x);
-    if (st == DP_OK && out_1) st = dpk_reduce_partials(ctx, part + d, (int)R, (size_t)2 * d, d, out_1);
-    return st;
+    for (int l = 0; l < L; ++l) {
+        const float* pl = part + (size_t)l * R * 2 * d;
+        dp_status st = DP_OK;
+        if (out_x) st = dpk_reduce_partials(ctx, pl, (int)R, (size_t)2 * d, d, out_x[l]);
+        if (st == DP_OK && out_1) st = dpk_reduce_partials(ctx, pl + d, (int)R, (size_t)2 * d, d, out_1[l]);
+        if (st != DP_OK) return st;
+    }
+    return DP_OK;
+}
+
+dp_status dpk_colstat_sums_batched(dp_ctx* ctx, int n, const void* const* X, const void* const* G, dp_dtype dt, int B, int T,
+                                   int d, const float* c, float* const* out_x, float* const* out_1) {
+    if (B == 0 || T == 0 || d == 0 || n == 0 || (!out_x && !out_1)) return DP_OK;
+    bool v4 = true;
+    for (int l = 0; l < n; ++l) v4 = v4 && vec4_ok(dt, d, out_x ? X[l] : G[l], G[l]);
+    for (int l0 = 0; l0 < n; l0 += COL_MAX_BATCH) {
+        const int L = n - l0 < COL_MAX_BATCH ? n - l0 : COL_MAX_BATCH;
+        const void* const* Xl = out_x ? X + l0 : nullptr;
+        float* const* ox = out_x ? out_x + l0 : nullptr;
+        float* const* o1 = out_1 ? out_1 + l0 : nullptr;
+        dp_status st;
+        if (dt == DP_BF16) st = colstat_sums_launch<true, 4>(ctx, L, Xl, G + l0, B, T, d, c, ox, o1);
+        else if (v4) st = colstat_sums_launch<false, 4>(ctx, L, Xl, G + l0, B, T, d, c, ox, o1);
+        else st = colstat_sums_launch<false, 1>(ctx, L, Xl, G + l0, B, T, d, c, ox, o1);
+        if (st != DP_OK) return st;
+    }
+    return DP_OK;
 }
 
 dp_status dpk_colstat_sums(dp_ctx* ctx, const void* X, const void* G, dp_dtype dt, int B, int T, int d, const float* c,
                            float* out_x, float* out_1) {
-    if (B == 0 || T == 0 || d == 0 || (!out_x && !out_1)) return DP_OK;
-    if (dt == DP_BF16) return colstat_sums_launch<true, 4>(ctx, X, G, B, T, d, c, out_x, out_1);
-    if (vec4_ok(dt, d, out_x ? X : G, G)) return colstat_sums_launch<false, 4>(ctx, X, G, B, T, d, c, out_x, out_1);
-    return colstat_sums_launch<false, 1>(ctx, X, G, B, T, d, c, out_x, out_1);
+    return dpk_colstat_sums_batched(ctx, 1, &X, &G, dt, B, T, d, c, out_x ? &out_x : nullptr, out_1 ? &out_1 : nullptr);
 }
 
 template <bool BF16, int VW>

@@ -43,12 +43,12 @@ class StepRunner:
 
     def pass1(self, layers, path=B_.DP_PATH_AUTO, batch_dense=True):
         """Per-example squared global norms of one micro-batch: sqnorms[:B] = sum over all layers.  The norm is a sum
-        over layers, so dense layers of one shape are handed over together."""
+        over layers, so dense layers of one shape, and LayerNorms of one shape, are handed over together."""
         ctx = self.ctx
         nB = layers[0]["G"].shape[0]
         n = self.sqnorms[:nB]
         ctx.zero_f32(n)
-        groups = {}
+        groups, ln_groups = {}, {}
         for l in layers:
             if l["kind"] == "dense":
                 if batch_dense:
@@ -56,11 +56,16 @@ class StepRunner:
                 else:
                     ctx.sqnorms_dense(l["A"], l["G"], l["has_bias"], path, n)
             elif l["kind"] == "layernorm":
-                ctx.sqnorms_layernorm(l["X"], l["G"], n)
+                if batch_dense:
+                    ln_groups.setdefault((tuple(l["X"].shape), l["X"].dtype), []).append(l)
+                else:
+                    ctx.sqnorms_layernorm(l["X"], l["G"], n)
             elif l["kind"] == "tied_embedding":   # lookup table that is also the output projection; G = dY
                 ctx.sqnorms_tied_embedding(l["ids"], l["G"], l["H"], l["dL"], n)
             else:
                 ctx.sqnorms_embedding(l["ids"], l["G"], l["V"], l["distinct"], n)
+        for ls in ln_groups.values():
+            ctx.sqnorms_layernorm_batched([l["X"] for l in ls], [l["G"] for l in ls], n)
         for key, ls in groups.items():
             # layers reading the very same input tensor (query / key / value projections) share its Gram matrix
             by_input = {}
@@ -83,7 +88,7 @@ class StepRunner:
         ctx = self.ctx
         nB = layers[0]["G"].shape[0]
         n = self.sqnorms[:nB]
-        groups = {}
+        groups, ln_groups = {}, {}
         for k, l in enumerate(layers):
             if l["kind"] == "dense":
                 if batch_dense:
@@ -92,13 +97,19 @@ class StepRunner:
                     sb = self.view(self.S, k, 1) if l["has_bias"] else None
                     ctx.clip_accumulate_dense(l["A"], l["G"], C, n, self.view(self.S, k, 0), sb)
             elif l["kind"] == "layernorm":
-                ctx.clip_accumulate_layernorm(l["X"], l["G"], C, n, self.view(self.S, k, 0), self.view(self.S, k, 1))
+                if batch_dense:
+                    ln_groups.setdefault((tuple(l["X"].shape), l["X"].dtype), []).append(k)
+                else:
+                    ctx.clip_accumulate_layernorm(l["X"], l["G"], C, n, self.view(self.S, k, 0), self.view(self.S, k, 1))
             elif l["kind"] == "tied_embedding":
                 ctx.clip_accumulate_tied_embedding(l["ids"], l["G"], l["H"], l["dL"], C, n, self.view(self.S, k, 0))
             elif l.get("distinct"):
                 ctx.clip_accumulate_positions(l["G"], C, n, self.view(self.S, k, 0))   # position ids: no sort needed
             else:
                 ctx.clip_accumulate_embedding(l["ids"], l["G"], l["V"], C, n, self.view(self.S, k, 0))
+        for sel in ln_groups.values():
+            ctx.clip_accumulate_layernorm_batched([layers[k]["X"] for k in sel], [layers[k]["G"] for k in sel], C, n,
+                                                  [self.view(self.S, k, 0) for k in sel], [self.view(self.S, k, 1) for k in sel])
         for sel in groups.values():
             ctx.clip_accumulate_dense_batched(
                 [layers[k]["A"] for k in sel], [layers[k]["G"] for k in sel], C, n,

@@ -385,6 +385,33 @@ def test_layernorm_norms_and_sums(dp, dtype, B, T, d):
     assert_sums_close(host(S_b).astype(np.float64) - 1.0, Sb_ref, t, "sum_beta")
 
 
+@pytest.mark.parametrize("dtype,n,B,T,d", [("bf16", 3, 9, 128, 1024), ("bf16", 19, 4, 33, 264), ("f32", 2, 5, 17, 20), ("bf16", 1, 3, 8, 64),
+                                          ("f32", 17, 2, 9, 6)])
+def test_layernorm_batched(dp, dtype, n, B, T, d):
+    """Several LayerNorms of one shape in one call (more than one launch's worth at n > 16): each layer against the oracle,
+    the norms against the sum over layers."""
+    Xs = [gen((B, T, d), 1.0, 900 + l, dtype) for l in range(n)]
+    Gs = [gen((B, T, d), 0.1 * (1 + l % 3), 950 + l, dtype) for l in range(n)]
+    Xd, Gd = [to_dev(x) for x in Xs], [to_dev(g) for g in Gs]
+    nrm = f32_dev(np.full(B, 0.25, np.float32))
+    dp.sqnorms_layernorm_batched(Xd, Gd, nrm)
+    dp.sync()
+    ref = sum(orc.sqnorms_layernorm(x, g) for x, g in zip(Xs, Gs))
+    assert_norms_close(host(nrm).astype(np.float64) - 0.25, ref, 1e-5 if dtype == "f32" else 1e-4, "batched LN norms")
+    C = 1.0
+    sq = syn.synthetic_sqnorms(B, C, 990)
+    c = orc.clip_factors(sq.astype(np.float64), C)
+    Sg = [torch.full((d,), 2.0, dtype=torch.float32, device=DEV) for _ in range(n)]
+    Sb = [torch.full((d,), -1.0, dtype=torch.float32, device=DEV) for _ in range(n)]
+    dp.clip_accumulate_layernorm_batched(Xd, Gd, C, f32_dev(sq), Sg, Sb)
+    dp.sync()
+    t = 1e-5 if dtype == "f32" else 1e-4
+    for l in range(n):
+        g_ref, b_ref = orc.clip_accumulate_layernorm(Xs[l], Gs[l], c)
+        assert_sums_close(host(Sg[l]).astype(np.float64) - 2.0, g_ref, t, f"layer {l} sum_gamma")
+        assert_sums_close(host(Sb[l]).astype(np.float64) + 1.0, b_ref, t, f"layer {l} sum_beta")
+
+
 # ------------------------------------------------------------------------------------------------
 # embeddings
 # ------------------------------------------------------------------------------------------------
