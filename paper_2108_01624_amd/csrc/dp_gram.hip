@@ -244,9 +244,10 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gram_dma_kernel(GramBatch gb,
     const int layer = blockIdx.x / gb.B, i = blockIdx.x - layer * gb.B;
     const uint16_t* __restrict__ A = gb.A[layer];
     const uint16_t* __restrict__ G = gb.G[layer];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wr = wave >> 1, wc = wave & 1;
     const bool active = wr <= wc;  // the lower-left quadrant mirrors the upper-right one
+    const bool diagw = wr == wc;   // ... and inside a diagonal quadrant the lower-left 32 x 32 tile the upper-right one
     const int nchA = d_in / GDK, nchG1 = d_out / GDK, nch = nchA + gb.n_out * nchG1;
     // chunk position c of row r holds global chunk c ^ swz(r): 16 consecutive rows -> 64 distinct banks
     auto swz = [](int r) { return CPR == 8 ? (r >> 1) & 7 : r & 15; };
@@ -327,13 +328,15 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gram_dma_kernel(GramBatch gb,
                     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
                         for (int nt = 0; nt < 2; ++nt)
-                            accA[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mt], b0[nt], accA[mt][nt], 0, 0, 0);
+                            if (!(mt == 1 && nt == 0 && diagw))
+                                accA[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mt], b0[nt], accA[mt][nt], 0, 0, 0);
                 } else {
 #pragma unroll
                     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
                         for (int nt = 0; nt < 2; ++nt)
-                            accG[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mt], b0[nt], accG[mt][nt], 0, 0, 0);
+                            if (!(mt == 1 && nt == 0 && diagw))
+                                accG[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mt], b0[nt], accG[mt][nt], 0, 0, 0);
                 }
             }
         }
@@ -347,7 +350,8 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gram_dma_kernel(GramBatch gb,
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) sum += (accA[a][b][r] + bias_term) * accG[a][b][r];
+            for (int r = 0; r < 16; ++r)
+                sum += (a == 0 && b == 1 && diagw ? 2.f : 1.f) * ((accA[a][b][r] + bias_term) * accG[a][b][r]);  // skipped tiles hold zeros
     sum *= wr == wc ? 1.f : (wr < wc ? 2.f : 0.f);
     const float tot = dp_block_sum<256>(sum, wred);
     if (threadIdx.x == 0) {
