@@ -434,7 +434,7 @@ __global__ __launch_bounds__(256) void sort_scatter(const uint32_t* __restrict__
 // inside the chunk is added to sum_E directly (this workgroup is its only writer).  A run that continues
 // from the previous chunk goes to first[pc], a run that starts here and continues into the next chunk goes
 // to last[pc]; segment_fixup_kernel adds those pieces in chunk order.
-constexpr int SEG_CHUNK = 256;
+constexpr int SEG_CHUNK = 32;
 
 template <bool BF16, int VW>
 __global__ __launch_bounds__(64) void segment_sums_kernel(const uint32_t* __restrict__ keys,
@@ -508,8 +508,10 @@ __global__ __launch_bounds__(64) void segment_sums_kernel(const uint32_t* __rest
     }
 }
 
-// One workgroup per chunk pc whose last run starts in pc and continues into pc+1: add last[pc], then
-// first[q] for q = pc+1, pc+2, ... while the run goes on, and add the total to sum_E[key].
+// Workgroups (pc, column block) for every chunk pc whose last run starts in pc and continues into pc+1: add last[pc],
+// then first[q] for the chunks q = pc+1 .. that the run reaches, in that order, and add the total to sum_E[key].
+// The end of the run is found by bisection of the sorted keys (the most frequent token spans hundreds of chunks);
+// the pieces are then loaded eight at a time and added in chunk order.
 __global__ __launch_bounds__(256) void segment_fixup_kernel(const uint32_t* __restrict__ keys, int N, int d, int V,
                                                             int nchunks, const float* __restrict__ first,
                                                             const float* __restrict__ last,
@@ -521,16 +523,26 @@ __global__ __launch_bounds__(256) void segment_fixup_kernel(const uint32_t* __re
     if (key >= (uint32_t)V || keys[pend] != key) return;             // no run crosses this boundary
     const int p0 = pc * SEG_CHUNK;
     if (p0 > 0 && keys[p0 - 1] == key && keys[p0] == key) return;    // the run started earlier: not its head
-    for (int col = threadIdx.x; col < d; col += 256) {
-        float acc = last[(size_t)pc * d + col];
-        for (int q = pc + 1; q < nchunks; ++q) {
-            if (keys[q * SEG_CHUNK] != key) break;
-            acc += first[(size_t)q * d + col];
-            const int qend = (q + 1) * SEG_CHUNK;
-            if (qend >= N || keys[qend - 1] != key) break;  // (cheap early exit; the next test would fail too)
-        }
-        sum_E[(size_t)key * d + col] += acc;
+    int lo = pend, hi = N;  // keys[lo] == key; the run ends at the first position in (lo, hi] whose key differs
+    while (hi - lo > 1) {
+        const int mid = lo + (hi - lo) / 2;
+        if (keys[mid] == key) lo = mid;
+        else hi = mid;
     }
+    const int qlast = lo / SEG_CHUNK;  // every chunk pc+1 .. qlast starts inside the run, so its first[] holds a piece
+    const int col = blockIdx.y * 256 + threadIdx.x;
+    if (col >= d) return;
+    float acc = last[(size_t)pc * d + col];
+    int q = pc + 1;
+    for (; q + 8 <= qlast + 1; q += 8) {
+        float f[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) f[u] = first[(size_t)(q + u) * d + col];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += f[u];
+    }
+    for (; q <= qlast; ++q) acc += first[(size_t)q * d + col];
+    sum_E[(size_t)key * d + col] += acc;
 }
 
 inline int bit_length(uint32_t v) {
@@ -778,7 +790,7 @@ static dp_status embedding_sums_launch(dp_ctx* ctx, const int32_t* ids, const vo
     hipLaunchKernelGGL((segment_sums_kernel<BF16, VW>), dim3(nseg, J), dim3(64), 0, ctx->stream, k0, v0, G, c, N, T, d, V, sum_E, first, last);
     DP_LAUNCH_CHECK(ctx, "segment_sums");
     if (nseg > 1) {
-        hipLaunchKernelGGL(segment_fixup_kernel, dim3(nseg - 1), dim3(256), 0, ctx->stream, k0, N, d, V, nseg, first, last, sum_E);
+        hipLaunchKernelGGL(segment_fixup_kernel, dim3(nseg - 1, (d + 255) / 256), dim3(256), 0, ctx->stream, k0, N, d, V, nseg, first, last, sum_E);
         DP_LAUNCH_CHECK(ctx, "segment_fixup");
     }
     return DP_OK;
