@@ -545,6 +545,24 @@ def test_argument_errors(dp):
     assert lib.dp_noise_adamw(h, *kw, 0.0, 1.0, 0, 1, 8, 1e-3, 1.0, 0.999, 1e-11, 0.0, 0) == -5   # beta1 = 1
     assert lib.dp_noise_adamw(h, p, p, None, p, 4, 0, 0.0, 1.0, 0, 1, 8, 1e-3, 0.9, 0.999, 1e-11, 0.0, 0) == -1
     assert "beta" in pkg.dp_last_error(h) or pkg.dp_last_error(h)
+    # tied table: (ctx, ids, dY, H, dL, dtype, B, T, M, d, V, ...)
+    assert lib.dp_sqnorms_tied_embedding(h, p, p, p, p, 1, 1, 4, 2, 8, 12, p) == -2       # bf16: V not a multiple of 8
+    assert lib.dp_sqnorms_tied_embedding(h, p, p, None, p, 0, 1, 4, 2, 8, 12, p) == -1    # M > 0 needs H
+    assert lib.dp_sqnorms_tied_embedding(h, p, p, p, p, 0, 1, 4, 2, 8, 0, p) == -2        # V = 0
+    assert lib.dp_sqnorms_tied_embedding(h, p, p, p, p, 0, 1, 4, -1, 8, 16, p) == -2      # negative M
+    assert lib.dp_sqnorms_tied_embedding(h, p, p, p, p, 0, 0, 4, 2, 8, 16, p) == 0        # empty batch
+    assert lib.dp_clip_accumulate_tied_embedding(h, p, p, p, p, 0, 1, 4, 2, 8, 16, -1.0, p, p) == -5
+    assert lib.dp_clip_accumulate_tied_embedding(h, p, p, p, p, 1, 1, 4, 2, 8, 16, 1.0, p, p + 4) == -4  # bf16: sum_E alignment
+    # pointer tables
+    import ctypes
+    tab = (ctypes.c_void_p * 2)(p, None)
+    good = (ctypes.c_void_p * 2)(p, p)
+    assert lib.dp_sqnorms_layernorm_batched(h, 2, tab, good, 0, 1, 1, 4, p) == -1
+    assert lib.dp_sqnorms_layernorm_batched(h, 2, None, good, 0, 1, 1, 4, p) == -1
+    assert lib.dp_sqnorms_layernorm_batched(h, -1, good, good, 0, 1, 1, 4, p) == -2
+    assert lib.dp_sqnorms_layernorm_batched(h, 0, None, None, 0, 1, 1, 4, p) == 0
+    assert lib.dp_clip_accumulate_layernorm_batched(h, 2, good, good, 0, 1, 1, 4, 1.0, p, good, tab) == -1
+    assert lib.dp_clip_accumulate_layernorm_batched(h, 2, good, good, 0, 1, 1, 4, 0.0, p, good, good) == -5
     dp.sync()
     assert not host(x).any()
 
