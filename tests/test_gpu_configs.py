@@ -466,6 +466,45 @@ def test_tied_output_projection_full_size_sampled():
         assert np.linalg.norm(got - ref) <= 5e-3 * np.linalg.norm(ref)
 
 
+def test_whole_step_is_reproducible_bit_for_bit():
+    """Every reduction of the path has a fixed order (no atomics on floating point), so two runs of the same two-micro-batch
+    step over a manifest with every layer kind (tied table, position table, LayerNorms, dense layers with shared inputs)
+    give identical bits in the norms, the accumulated sum and the updated parameters."""
+    import paper_2108_01624_amd as pkg
+
+    B, T = 24, 64
+    man = syn.bert_manifest(2, 256, 512, vocab=1024, max_pos=64, tied_pred=10)
+    batches = [syn.device_layer_inputs(man, B, T, dtype="bf16", act_std=1.0, grad_std=1e-2, data_seed=6000 + k, device=DEV)
+               for k in range(2)]
+    for layers in batches:
+        by_name = {l["name"]: l for l in layers}
+        for name, l in by_name.items():
+            if name.endswith(".k") or name.endswith(".v"):
+                l["A"] = by_name[name[:-2] + ".q"]["A"]
+    results = []
+    for rep in range(2):
+        with pkg.Context() as ctx:
+            run = pkg.StepRunner(ctx, man, B, device=DEV)
+            run.theta.copy_(f32_dev(syn.normal_f32((run.P,), 0.02, 6100)))
+            norms = []
+            for layers in batches:
+                n = run.pass1(layers)
+                ctx.sync()
+                norms.append(host(n).copy())
+                run.pass2(layers, 0.05)
+            ctx.sync()
+            S = host(run.S).copy()
+            run.update(sigma=0.7, C=0.05, seed=77, step=1, batch_size=2 * B, lr=1e-3, beta1=0.9, beta2=0.999, weight_decay=0.01)
+            ctx.sync()
+            results.append((norms, S, host(run.theta).copy(), host(run.m).copy(), host(run.v).copy()))
+    (n0, S0, th0, m0, v0), (n1, S1, th1, m1, v1) = results
+    for a, b in zip(n0, n1):
+        np.testing.assert_array_equal(a.view(np.uint32), b.view(np.uint32))
+    for a, b in ((S0, S1), (th0, th1), (m0, m1), (v0, v1)):
+        np.testing.assert_array_equal(a.view(np.uint32), b.view(np.uint32))
+    assert np.abs(S0).max() > 0 and np.isfinite(th0).all()
+
+
 # ------------------------------------------------------------------------------------------------
 # schedule-driven steps: q_t micro-batches per step, eta_t per step, bias correction at t > 1
 # ------------------------------------------------------------------------------------------------
