@@ -380,9 +380,10 @@ __device__ __forceinline__ float gram_pair_ring(const uint16_t* __restrict__ A, 
     constexpr int PANEL = GB * GP_K;        // bf16 elements of one panel of a stage
     constexpr int LPP = 4;                  // loads per wave per panel: 8 rows of 8 chunks each
     constexpr int LPS = OFFDIAG ? 2 * LPP : LPP;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wr = wave >> 1, wc = wave & 1;
     const bool active = OFFDIAG || wr <= wc;
+    const bool diagw = !OFFDIAG && wr == wc;  // a diagonal quadrant of a diagonal block: its lower-left tile mirrors the upper-right one
     const int nchA = d_in / GP_K, nch = nchA + d_out / GP_K;
     auto swz = [](int r) { return (r >> 1) & 7; };
     // rows >= T lie outside the example's byte range and read as zero
@@ -454,7 +455,8 @@ __device__ __forceinline__ float gram_pair_ring(const uint16_t* __restrict__ A, 
                 for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
                     for (int nt = 0; nt < 2; ++nt)
-                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mt], b0[nt], acc[mt][nt], 0, 0, 0);
+                        if (!(mt == 1 && nt == 0 && diagw))
+                            acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mt], b0[nt], acc[mt][nt], 0, 0, 0);
             }
         }
         cbuf = cbuf + 1 == GP_NS ? 0 : cbuf + 1;
@@ -468,7 +470,8 @@ __device__ __forceinline__ float gram_pair_ring(const uint16_t* __restrict__ A, 
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) sum += (accA[a][b][r] + bias_term) * accG[a][b][r];
+            for (int r = 0; r < 16; ++r)
+                sum += (a == 0 && b == 1 && diagw ? 2.f : 1.f) * ((accA[a][b][r] + bias_term) * accG[a][b][r]);  // skipped tiles hold zeros
     return sum * (OFFDIAG ? 2.f : (wr == wc ? 1.f : (wr < wc ? 2.f : 0.f)));
 }
 
