@@ -162,6 +162,19 @@ dp_status dp_clip_accumulate_layernorm_batched(dp_ctx* ctx, int n_layers, const 
                                                dp_dtype dtype, int B, int T, int d, float C, const float* sqnorms,
                                                float* const* sum_gamma, float* const* sum_beta);
 
+/* LayerNorm gradients are small (2 d numbers per example and layer), so pass 1 can keep them and pass 2 need not read
+ * Xhat and G again: dp_sqnorms_layernorm_keep does what dp_sqnorms_layernorm_batched does and also WRITES every
+ * example's gradient to grads[l] (device, fp32, [B][2][d]: row 0 the gain gradient sum_t G Xhat, row 1 the offset
+ * gradient sum_t G; 16-byte aligned, d a multiple of 4, caller-owned, overwritten);
+ * dp_clip_accumulate_layernorm_kept then adds sum_i c_i grads[l][i] to sum_gamma[l] / sum_beta[l] (16-byte aligned),
+ * reading 8 d bytes per example instead of 2 T d elements.  Same sums as dp_clip_accumulate_layernorm up to fp32
+ * summation order (examples are added in a fixed order).  The caller must not change grads between the two calls
+ * of a micro-batch.  All tables are HOST arrays of n_layers device pointers, read during the call only. */
+dp_status dp_sqnorms_layernorm_keep(dp_ctx* ctx, int n_layers, const void* const* Xhat, const void* const* G, dp_dtype dtype,
+                                    int B, int T, int d, float* sqnorms, float* const* grads);
+dp_status dp_clip_accumulate_layernorm_kept(dp_ctx* ctx, int n_layers, float* const* grads, int B, int d, float C,
+                                            const float* sqnorms, float* const* sum_gamma, float* const* sum_beta);
+
 /* sum_E[ids[i,t], :] += c_i G[i,t,:] for every token.  Rows are added in ascending (i, t) order per id. */
 dp_status dp_clip_accumulate_embedding(dp_ctx* ctx, const int32_t* ids, const void* G, dp_dtype dtype, int B, int T,
                                        int d, int V, float C, const float* sqnorms, float* sum_E);

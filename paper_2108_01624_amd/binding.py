@@ -43,6 +43,8 @@ SIGNATURES = {
     "dp_sqnorms_layernorm_batched": [c_void_p, c_int, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_void_p],
     "dp_clip_accumulate_layernorm_batched": [c_void_p, c_int, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_float,
                                              c_void_p, c_void_p, c_void_p],
+    "dp_sqnorms_layernorm_keep": [c_void_p, c_int, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_void_p, c_void_p],
+    "dp_clip_accumulate_layernorm_kept": [c_void_p, c_int, c_void_p, c_int, c_int, c_float, c_void_p, c_void_p, c_void_p],
     "dp_sqnorms_tied_embedding": [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int,
                                   c_void_p],
     "dp_clip_accumulate_tied_embedding": [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int,
@@ -294,6 +296,28 @@ def dp_clip_accumulate_layernorm_batched(ctx, Xhats, Gs, C, sqnorms, sum_gammas,
         ctx, n, arr([_ptr(t) for t in Xhats]), arr([_ptr(t) for t in Gs]), _dtype_of(Gs[0]), B, T, d, float(C), _f32(sqnorms),
         arr([_f32(t) for t in sum_gammas]), arr([_f32(t) for t in sum_betas]))
     _check(ctx, st, "dp_clip_accumulate_layernorm_batched")
+
+
+def dp_sqnorms_layernorm_keep(ctx, Xhats, Gs, sqnorms, grads):
+    """grads: one float32 tensor [B, 2, d] per layer, overwritten with every example's gain / offset gradient."""
+    n = len(Xhats)
+    B, T, d = _same_shaped(Xhats, Gs)
+    for g in grads:
+        if g.numel() < B * 2 * d:
+            raise ValueError("grads[l] must hold B x 2 x d floats")
+    arr = lambda ptrs: (c_void_p * n)(*ptrs)
+    st = load_library().dp_sqnorms_layernorm_keep(ctx, n, arr([_ptr(t) for t in Xhats]), arr([_ptr(t) for t in Gs]),
+                                                  _dtype_of(Gs[0]), B, T, d, _f32(sqnorms), arr([_f32(t) for t in grads]))
+    _check(ctx, st, "dp_sqnorms_layernorm_keep")
+
+
+def dp_clip_accumulate_layernorm_kept(ctx, grads, B, d, C, sqnorms, sum_gammas, sum_betas):
+    n = len(grads)
+    arr = lambda ptrs: (c_void_p * n)(*ptrs)
+    st = load_library().dp_clip_accumulate_layernorm_kept(ctx, n, arr([_f32(t) for t in grads]), int(B), int(d), float(C),
+                                                          _f32(sqnorms), arr([_f32(t) for t in sum_gammas]),
+                                                          arr([_f32(t) for t in sum_betas]))
+    _check(ctx, st, "dp_clip_accumulate_layernorm_kept")
 
 
 def _tied_shapes(ids, dY, H, dL):

@@ -435,7 +435,52 @@ dp_status dp_sqnorms_layernorm_batched(dp_ctx* ctx, int n_layers, const void* co
         TRY(check_tensor(ctx, "G[l]", G[l], dtype, d));
     }
     TRY(check_f32(ctx, "sqnorms", sqnorms));
-    return dpk_colstat_sqnorms_batched(ctx, n_layers, Xhat, G, dtype, B, T, d, 1, 1, sqnorms);
+    return dpk_colstat_sqnorms_batched(ctx, n_layers, Xhat, G, dtype, B, T, d, 1, 1, sqnorms, nullptr);
+}
+
+dp_status dp_sqnorms_layernorm_keep(dp_ctx* ctx, int n_layers, const void* const* Xhat, const void* const* G, dp_dtype dtype,
+                                    int B, int T, int d, float* sqnorms, float* const* grads) {
+    REQUIRE_CTX(ctx);
+    TRY(check_dtype(ctx, dtype));
+    TRY(check_bt(ctx, B, T));
+    if (n_layers < 0 || d < 0) FAIL(ctx, DP_ERR_SHAPE, "negative layer count or width");
+    if (d % 4) FAIL(ctx, DP_ERR_SHAPE, "width %d is not a multiple of 4", d);
+    if (n_layers == 0) return DP_OK;
+    if (!Xhat || !G || !grads) FAIL(ctx, DP_ERR_NULL, "a pointer table is NULL");
+    for (int l = 0; l < n_layers; ++l) {
+        TRY(check_tensor(ctx, "Xhat[l]", Xhat[l], dtype, d));
+        TRY(check_tensor(ctx, "G[l]", G[l], dtype, d));
+        TRY(check_f32(ctx, "grads[l]", grads[l]));
+        if ((uintptr_t)grads[l] & 15) FAIL(ctx, DP_ERR_ALIGN, "grads[%d] is not 16-byte aligned", l);
+    }
+    TRY(check_f32(ctx, "sqnorms", sqnorms));
+    if (B == 0 || d == 0) return DP_OK;
+    if (T == 0) {  // no tokens: every example's gradient is zero
+        for (int l = 0; l < n_layers; ++l) TRY(dpk_zero_f32(ctx, grads[l], (uint64_t)B * 2 * d));
+        return DP_OK;
+    }
+    return dpk_colstat_sqnorms_batched(ctx, n_layers, Xhat, G, dtype, B, T, d, 1, 1, sqnorms, grads);
+}
+
+dp_status dp_clip_accumulate_layernorm_kept(dp_ctx* ctx, int n_layers, float* const* grads, int B, int d, float C,
+                                            const float* sqnorms, float* const* sum_gamma, float* const* sum_beta) {
+    REQUIRE_CTX(ctx);
+    if (B < 0 || n_layers < 0 || d < 0) FAIL(ctx, DP_ERR_SHAPE, "negative count or width");
+    if (d % 4) FAIL(ctx, DP_ERR_SHAPE, "width %d is not a multiple of 4", d);
+    if (n_layers == 0) return DP_OK;
+    if (!grads || !sum_gamma || !sum_beta) FAIL(ctx, DP_ERR_NULL, "a pointer table is NULL");
+    for (int l = 0; l < n_layers; ++l) {
+        TRY(check_f32(ctx, "grads[l]", grads[l]));
+        TRY(check_f32(ctx, "sum_gamma[l]", sum_gamma[l]));
+        TRY(check_f32(ctx, "sum_beta[l]", sum_beta[l]));
+        if (((uintptr_t)grads[l] | (uintptr_t)sum_gamma[l] | (uintptr_t)sum_beta[l]) & 15)
+            FAIL(ctx, DP_ERR_ALIGN, "grads, sum_gamma and sum_beta must be 16-byte aligned (layer %d)", l);
+    }
+    TRY(check_f32(ctx, "sqnorms", sqnorms));
+    TRY(check_clip(ctx, C, B));
+    if (B == 0 || d == 0) return DP_OK;
+    TRY(dpk_clip_factors(ctx, sqnorms, B, C, ctx->cbuf));
+    return dpk_kept_sums_batched(ctx, n_layers, grads, B, d, ctx->cbuf, sum_gamma, sum_beta);
 }
 
 dp_status dp_clip_accumulate_layernorm_batched(dp_ctx* ctx, int n_layers, const void* const* Xhat, const void* const* G,

@@ -192,7 +192,9 @@ dp_status dpk_colstat_sums(dp_ctx*, const void* X, const void* G, dp_dtype, int 
                            float* out_x, float* out_1);
 
 dp_status dpk_colstat_sqnorms_batched(dp_ctx*, int n, const void* const* X, const void* const* G, dp_dtype, int B, int T, int d,
-                                      int use_x, int use_1, float* sqnorms);
+                                      int use_x, int use_1, float* sqnorms, float* const* keep /* or NULL */);
+dp_status dpk_kept_sums_batched(dp_ctx*, int n, float* const* keep, int B, int d, const float* c, float* const* sum_x,
+                                float* const* sum_1);
 dp_status dpk_colstat_sums_batched(dp_ctx*, int n, const void* const* X, const void* const* G, dp_dtype, int B, int T, int d,
                                    const float* c, float* const* out_x, float* const* out_1);
 

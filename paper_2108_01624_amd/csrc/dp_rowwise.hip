@@ -47,11 +47,16 @@ struct ColOut {
     float* out_x[COL_MAX_BATCH];
     float* out_1[COL_MAX_BATCH];
 };
+struct ColKeep {
+    float* keep[COL_MAX_BATCH];  // per layer: [B][2][d] fp32, the per-example column statistics themselves
+};
 
-// out: direct (one layer, one column block): sqnorms, "+="; otherwise partials [B][layers * J], stored
-template <bool BF16, int VW, bool USE_X, bool USE_1>
-__global__ __launch_bounds__(256) void colstat_sqnorms_kernel(ColBatch cb, int T, int d, float* __restrict__ out, int J,
-                                                              int direct) {
+// out: direct (one layer, one column block): sqnorms, "+="; otherwise partials [B][layers * J], stored.
+// KEEP: the statistics of example i (sum_t g x and sum_t g per column: its LayerNorm gain / offset gradient) are also
+// written to ck.keep[layer][i], so that pass 2 can weight and add 8 KB per example instead of reading X and G again.
+template <bool BF16, int VW, bool USE_X, bool USE_1, bool KEEP>
+__global__ __launch_bounds__(256) void colstat_sqnorms_kernel(ColBatch cb, ColKeep ck, int T, int d, float* __restrict__ out,
+                                                              int J, int direct) {
     __shared__ float red[4][64][2 * VW];
     __shared__ float wred[4];
     const void* __restrict__ X = cb.X[blockIdx.z];
@@ -86,11 +91,27 @@ __global__ __launch_bounds__(256) void colstat_sqnorms_kernel(ColBatch cb, int T
     __syncthreads();
     float val = 0.f;
     if (tg == 0) {
+        float sv[2 * VW];
 #pragma unroll
         for (int k = 0; k < 2 * VW; ++k) {
-            const float s = (red[0][lane][k] + red[1][lane][k]) + (red[2][lane][k] + red[3][lane][k]);
+            sv[k] = (red[0][lane][k] + red[1][lane][k]) + (red[2][lane][k] + red[3][lane][k]);
             const bool on = k < VW ? USE_X : USE_1;
-            if (on) val += s * s;
+            if (on) val += sv[k] * sv[k];
+        }
+        if constexpr (KEEP) {
+            if (col < d) {
+                float* __restrict__ kp = ck.keep[blockIdx.z] + (size_t)i * 2 * d + col;
+                if constexpr (VW == 4) {  // d % 4 == 0 and a 16-byte aligned buffer are checked at the API
+                    *reinterpret_cast<float4*>(kp) = make_float4(sv[0], sv[1], sv[2], sv[3]);
+                    *reinterpret_cast<float4*>(kp + d) = make_float4(sv[4], sv[5], sv[6], sv[7]);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < VW; ++k) {
+                        kp[k] = sv[k];
+                        kp[d + k] = sv[VW + k];
+                    }
+                }
+            }
         }
     }
     const float tot = dp_block_sum<256>(val, wred);
@@ -148,6 +169,52 @@ __global__ __launch_bounds__(256) void colstat_sums_kernel(ColBatch cb, const fl
             p[col + k] = (red[0][lane][k] + red[1][lane][k]) + (red[2][lane][k] + red[3][lane][k]);
             p[d + col + k] = (red[0][lane][VW + k] + red[1][lane][VW + k]) + (red[2][lane][VW + k] + red[3][lane][VW + k]);
         }
+    }
+}
+
+// Pass 2 from kept per-example statistics: out_x[j] += sum_i c_i keep[i][0][j], out_1[j] += sum_i c_i keep[i][1][j].
+// grid (ceil(2d / 256), layers); 256 threads = 64 float4 columns x 4 example groups; group g adds the examples
+// i = g, g+4, ... in ascending order, the four group sums are added as (0+1)+(2+3): fixed order.
+__global__ __launch_bounds__(256) void kept_sums_kernel(ColKeep ck, ColOut co, const float* __restrict__ c, int B, int d) {
+    __shared__ float4 red[4][64];
+    const int lane = threadIdx.x & 63, g = threadIdx.x >> 6;
+    const int n4 = 2 * d / 4, d4 = d / 4;
+    const int j = blockIdx.x * 64 + lane;
+    const float4* __restrict__ src = reinterpret_cast<const float4*>(ck.keep[blockIdx.y]);
+    float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (j < n4) {
+        int i = g;
+        for (; i + 28 < B; i += 32) {
+            float4 p[8];
+            float w[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                p[u] = src[(size_t)(i + 4 * u) * n4 + j];
+                w[u] = c[i + 4 * u];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                t.x += w[u] * p[u].x; t.y += w[u] * p[u].y; t.z += w[u] * p[u].z; t.w += w[u] * p[u].w;
+            }
+        }
+        for (; i < B; i += 4) {
+            const float4 p = src[(size_t)i * n4 + j];
+            const float w = c[i];
+            t.x += w * p.x; t.y += w * p.y; t.z += w * p.z; t.w += w * p.w;
+        }
+    }
+    red[g][lane] = t;
+    __syncthreads();
+    if (g == 0 && j < n4) {
+        const float4 a = red[0][lane], b = red[1][lane], e = red[2][lane], f = red[3][lane];
+        float4* dst = j < d4 ? reinterpret_cast<float4*>(co.out_x[blockIdx.y]) + j
+                             : reinterpret_cast<float4*>(co.out_1[blockIdx.y]) + (j - d4);
+        float4 o = *dst;
+        o.x += (a.x + b.x) + (e.x + f.x);
+        o.y += (a.y + b.y) + (e.y + f.y);
+        o.z += (a.z + b.z) + (e.z + f.z);
+        o.w += (a.w + b.w) + (e.w + f.w);
+        *dst = o;
     }
 }
 
@@ -585,12 +652,14 @@ dp_status dpk_reduce_partials(dp_ctx* ctx, const float* part, int R, size_t stri
 
 template <bool BF16, int VW>
 static dp_status colstat_sqnorms_launch(dp_ctx* ctx, int L, const void* const* X, const void* const* G, int B, int T, int d,
-                                        int use_x, int use_1, float* sqnorms) {
+                                        int use_x, int use_1, float* sqnorms, float* const* keep) {
     const int J = (d + 64 * VW - 1) / (64 * VW);
     ColBatch cb;
+    ColKeep ck;
     for (int l = 0; l < COL_MAX_BATCH; ++l) {
         cb.X[l] = use_x ? X[l < L ? l : 0] : nullptr;
         cb.G[l] = G[l < L ? l : 0];
+        ck.keep[l] = keep ? keep[l < L ? l : 0] : nullptr;
     }
     float* out = sqnorms;
     int direct = 1;
@@ -604,19 +673,22 @@ static dp_status colstat_sqnorms_launch(dp_ctx* ctx, int L, const void* const* X
         direct = 0;
     }
     dim3 grid(B, J, L);
-    if (use_x && use_1)
-        hipLaunchKernelGGL((colstat_sqnorms_kernel<BF16, VW, true, true>), grid, dim3(256), 0, ctx->stream, cb, T, d, out, J, direct);
+    if (keep)  // (LayerNorm only: both statistics)
+        hipLaunchKernelGGL((colstat_sqnorms_kernel<BF16, VW, true, true, true>), grid, dim3(256), 0, ctx->stream, cb, ck, T, d, out, J, direct);
+    else if (use_x && use_1)
+        hipLaunchKernelGGL((colstat_sqnorms_kernel<BF16, VW, true, true, false>), grid, dim3(256), 0, ctx->stream, cb, ck, T, d, out, J, direct);
     else if (use_x)
-        hipLaunchKernelGGL((colstat_sqnorms_kernel<BF16, VW, true, false>), grid, dim3(256), 0, ctx->stream, cb, T, d, out, J, direct);
+        hipLaunchKernelGGL((colstat_sqnorms_kernel<BF16, VW, true, false, false>), grid, dim3(256), 0, ctx->stream, cb, ck, T, d, out, J, direct);
     else
-        hipLaunchKernelGGL((colstat_sqnorms_kernel<BF16, VW, false, true>), grid, dim3(256), 0, ctx->stream, cb, T, d, out, J, direct);
+        hipLaunchKernelGGL((colstat_sqnorms_kernel<BF16, VW, false, true, false>), grid, dim3(256), 0, ctx->stream, cb, ck, T, d, out, J, direct);
     DP_LAUNCH_CHECK(ctx, "colstat_sqnorms");
     if (!direct) return dpk_finish_partials(ctx, out, B, L * J, sqnorms);  // layers, then column blocks, in index order
     return DP_OK;
 }
 
+// keep: NULL, or n pointers to [B][2][d] fp32 buffers that receive every example's two statistics (then use_x = use_1 = 1)
 dp_status dpk_colstat_sqnorms_batched(dp_ctx* ctx, int n, const void* const* X, const void* const* G, dp_dtype dt, int B, int T,
-                                      int d, int use_x, int use_1, float* sqnorms) {
+                                      int d, int use_x, int use_1, float* sqnorms, float* const* keep) {
     if (B == 0 || T == 0 || d == 0 || n == 0 || (!use_x && !use_1)) return DP_OK;
     bool v4 = true;
     for (int l = 0; l < n; ++l) v4 = v4 && vec4_ok(dt, d, use_x ? X[l] : G[l], G[l]);
@@ -624,9 +696,10 @@ dp_status dpk_colstat_sqnorms_batched(dp_ctx* ctx, int n, const void* const* X, 
         const int L = n - l0 < COL_MAX_BATCH ? n - l0 : COL_MAX_BATCH;
         const void* const* Xl = use_x ? X + l0 : nullptr;
         dp_status st;
-        if (dt == DP_BF16) st = colstat_sqnorms_launch<true, 4>(ctx, L, Xl, G + l0, B, T, d, use_x, use_1, sqnorms);
-        else if (v4) st = colstat_sqnorms_launch<false, 4>(ctx, L, Xl, G + l0, B, T, d, use_x, use_1, sqnorms);
-        else st = colstat_sqnorms_launch<false, 1>(ctx, L, Xl, G + l0, B, T, d, use_x, use_1, sqnorms);
+        float* const* kl = keep ? keep + l0 : nullptr;
+        if (dt == DP_BF16) st = colstat_sqnorms_launch<true, 4>(ctx, L, Xl, G + l0, B, T, d, use_x, use_1, sqnorms, kl);
+        else if (v4) st = colstat_sqnorms_launch<false, 4>(ctx, L, Xl, G + l0, B, T, d, use_x, use_1, sqnorms, kl);
+        else st = colstat_sqnorms_launch<false, 1>(ctx, L, Xl, G + l0, B, T, d, use_x, use_1, sqnorms, kl);
         if (st != DP_OK) return st;
     }
     return DP_OK;
@@ -634,7 +707,26 @@ dp_status dpk_colstat_sqnorms_batched(dp_ctx* ctx, int n, const void* const* X, 
 
 dp_status dpk_colstat_sqnorms(dp_ctx* ctx, const void* X, const void* G, dp_dtype dt, int B, int T, int d, int use_x,
                               int use_1, float* sqnorms) {
-    return dpk_colstat_sqnorms_batched(ctx, 1, &X, &G, dt, B, T, d, use_x, use_1, sqnorms);
+    return dpk_colstat_sqnorms_batched(ctx, 1, &X, &G, dt, B, T, d, use_x, use_1, sqnorms, nullptr);
+}
+
+// sum_x[l][j] += sum_i c_i keep[l][i][0][j], sum_1[l][j] += sum_i c_i keep[l][i][1][j]; d % 4 == 0, 16-byte aligned buffers
+dp_status dpk_kept_sums_batched(dp_ctx* ctx, int n, float* const* keep, int B, int d, const float* c, float* const* sum_x,
+                                float* const* sum_1) {
+    if (B == 0 || d == 0 || n == 0) return DP_OK;
+    for (int l0 = 0; l0 < n; l0 += COL_MAX_BATCH) {
+        const int L = n - l0 < COL_MAX_BATCH ? n - l0 : COL_MAX_BATCH;
+        ColKeep ck;
+        ColOut co;
+        for (int l = 0; l < COL_MAX_BATCH; ++l) {
+            ck.keep[l] = keep[l0 + (l < L ? l : 0)];
+            co.out_x[l] = sum_x[l0 + (l < L ? l : 0)];
+            co.out_1[l] = sum_1[l0 + (l < L ? l : 0)];
+        }
+        hipLaunchKernelGGL(kept_sums_kernel, dim3((unsigned)((2 * d / 4 + 63) / 64), L), dim3(256), 0, ctx->stream, ck, co, c, B, d);
+        DP_LAUNCH_CHECK(ctx, "kept_sums");
+    }
+    return DP_OK;
 }
 
 // out_x / out_1: tables of L pointers, or NULL when that statistic is not wanted (the same for every layer of the call)

@@ -33,6 +33,11 @@ class StepRunner:
         self.m = torch.zeros(self.P, dtype=torch.float32, device=device)
         self.v = torch.zeros(self.P, dtype=torch.float32, device=device)
         self.sqnorms = torch.zeros(max_batch, dtype=torch.float32, device=device)
+        # per-example LayerNorm gradients kept from pass 1 for pass 2 (2 d floats per example and layer)
+        self.max_batch = max_batch
+        self.device = device
+        self.ln_keep = {}
+        self._kept_for = None
 
     def view(self, buf, layer, k):
         off, shp = self.offsets[layer][k]
@@ -40,6 +45,21 @@ class StepRunner:
         for s in shp:
             n *= s
         return buf[off:off + n].view(*shp)
+
+    def _keep_buffer(self, k, d):
+        """[max_batch, 2, d] floats for layer k of the manifest, allocated on first use."""
+        import torch
+
+        buf = self.ln_keep.get(k)
+        if buf is None or buf.numel() < self.max_batch * 2 * d:
+            buf = torch.empty(self.max_batch * 2 * d, dtype=torch.float32, device=self.device)
+            self.ln_keep[k] = buf
+        return buf
+
+    @staticmethod
+    def _ln_token(layers, nB):
+        """Identifies the micro-batch whose LayerNorm gradients the keep buffers hold: batch size and input buffers."""
+        return (nB, tuple((l["X"].data_ptr(), l["G"].data_ptr()) for l in layers if l["kind"] == "layernorm"))
 
     def pass1(self, layers, path=B_.DP_PATH_AUTO, batch_dense=True):
         """Per-example squared global norms of one micro-batch: sqnorms[:B] = sum over all layers.  The norm is a sum
@@ -49,7 +69,7 @@ class StepRunner:
         n = self.sqnorms[:nB]
         ctx.zero_f32(n)
         groups, ln_groups = {}, {}
-        for l in layers:
+        for k, l in enumerate(layers):
             if l["kind"] == "dense":
                 if batch_dense:
                     groups.setdefault((tuple(l["A"].shape), tuple(l["G"].shape), l["A"].dtype, bool(l["has_bias"])), []).append(l)
@@ -57,15 +77,23 @@ class StepRunner:
                     ctx.sqnorms_dense(l["A"], l["G"], l["has_bias"], path, n)
             elif l["kind"] == "layernorm":
                 if batch_dense:
-                    ln_groups.setdefault((tuple(l["X"].shape), l["X"].dtype), []).append(l)
+                    ln_groups.setdefault((tuple(l["X"].shape), l["X"].dtype), []).append(k)
                 else:
                     ctx.sqnorms_layernorm(l["X"], l["G"], n)
             elif l["kind"] == "tied_embedding":   # lookup table that is also the output projection; G = dY
                 ctx.sqnorms_tied_embedding(l["ids"], l["G"], l["H"], l["dL"], n)
             else:
                 ctx.sqnorms_embedding(l["ids"], l["G"], l["V"], l["distinct"], n)
-        for ls in ln_groups.values():
-            ctx.sqnorms_layernorm_batched([l["X"] for l in ls], [l["G"] for l in ls], n)
+        self._kept_for = None
+        for sel in ln_groups.values():
+            Xs, Gs = [layers[k]["X"] for k in sel], [layers[k]["G"] for k in sel]
+            d = Xs[0].shape[-1]
+            if d % 4 == 0:
+                ctx.sqnorms_layernorm_keep(Xs, Gs, n, [self._keep_buffer(k, d) for k in sel])
+            else:
+                ctx.sqnorms_layernorm_batched(Xs, Gs, n)
+        if ln_groups and all(k[0][-1] % 4 == 0 for k in ln_groups):
+            self._kept_for = self._ln_token(layers, nB)
         for key, ls in groups.items():
             # layers reading the very same input tensor (query / key / value projections) share its Gram matrix
             by_input = {}
@@ -107,9 +135,14 @@ class StepRunner:
                 ctx.clip_accumulate_positions(l["G"], C, n, self.view(self.S, k, 0))   # position ids: no sort needed
             else:
                 ctx.clip_accumulate_embedding(l["ids"], l["G"], l["V"], C, n, self.view(self.S, k, 0))
+        kept = self._kept_for is not None and self._kept_for == self._ln_token(layers, nB)   # pass 1 of this very micro-batch left the LayerNorm gradients behind
         for sel in ln_groups.values():
-            ctx.clip_accumulate_layernorm_batched([layers[k]["X"] for k in sel], [layers[k]["G"] for k in sel], C, n,
-                                                  [self.view(self.S, k, 0) for k in sel], [self.view(self.S, k, 1) for k in sel])
+            sg, sb = [self.view(self.S, k, 0) for k in sel], [self.view(self.S, k, 1) for k in sel]
+            if kept:
+                d = layers[sel[0]]["X"].shape[-1]
+                ctx.clip_accumulate_layernorm_kept([self.ln_keep[k] for k in sel], nB, d, C, n, sg, sb)
+            else:
+                ctx.clip_accumulate_layernorm_batched([layers[k]["X"] for k in sel], [layers[k]["G"] for k in sel], C, n, sg, sb)
         for sel in groups.values():
             ctx.clip_accumulate_dense_batched(
                 [layers[k]["A"] for k in sel], [layers[k]["G"] for k in sel], C, n,

@@ -410,6 +410,28 @@ def test_layernorm_batched(dp, dtype, n, B, T, d):
         g_ref, b_ref = orc.clip_accumulate_layernorm(Xs[l], Gs[l], c)
         assert_sums_close(host(Sg[l]).astype(np.float64) - 2.0, g_ref, t, f"layer {l} sum_gamma")
         assert_sums_close(host(Sb[l]).astype(np.float64) + 1.0, b_ref, t, f"layer {l} sum_beta")
+    if d % 4:
+        return
+    # the same through kept per-example gradients: pass 1 writes them, pass 2 only weights and adds them
+    keep = [torch.full((B, 2, d), 7.0, dtype=torch.float32, device=DEV) for _ in range(n)]
+    nrm2 = f32_dev(np.full(B, 0.25, np.float32))
+    dp.sqnorms_layernorm_keep(Xd, Gd, nrm2, keep)
+    dp.sync()
+    np.testing.assert_array_equal(host(nrm2), host(nrm))                   # same kernel, same order: same bits
+    for l in (0, n - 1):
+        for i in (0, B - 1):
+            gg, gb = orc.layernorm_example_grads(Xs[l][i], Gs[l][i])
+            k = host(keep[l][i]).astype(np.float64)
+            np.testing.assert_allclose(k[0], gg, rtol=t, atol=t * np.abs(gg).max())
+            np.testing.assert_allclose(k[1], gb, rtol=t, atol=t * np.abs(gb).max())
+    Sg2 = [torch.full((d,), 2.0, dtype=torch.float32, device=DEV) for _ in range(n)]
+    Sb2 = [torch.full((d,), -1.0, dtype=torch.float32, device=DEV) for _ in range(n)]
+    dp.clip_accumulate_layernorm_kept(keep, B, d, C, f32_dev(sq), Sg2, Sb2)
+    dp.sync()
+    for l in range(n):
+        g_ref, b_ref = orc.clip_accumulate_layernorm(Xs[l], Gs[l], c)
+        assert_sums_close(host(Sg2[l]).astype(np.float64) - 2.0, g_ref, t, f"layer {l} sum_gamma from kept gradients")
+        assert_sums_close(host(Sb2[l]).astype(np.float64) + 1.0, b_ref, t, f"layer {l} sum_beta from kept gradients")
 
 
 # ------------------------------------------------------------------------------------------------
