@@ -102,8 +102,8 @@ __global__ __launch_bounds__(256) void colstat_sqnorms_kernel(ColBatch cb, ColKe
             if (col < d) {
                 float* __restrict__ kp = ck.keep[blockIdx.z] + (size_t)i * 2 * d + col;
                 if constexpr (VW == 4) {  // d % 4 == 0 and a 16-byte aligned buffer are checked at the API
-                    *reinterpret_cast<float4*>(kp) = make_float4(sv[0], sv[1], sv[2], sv[3]);
-                    *reinterpret_cast<float4*>(kp + d) = make_float4(sv[4], sv[5], sv[6], sv[7]);
+                    __builtin_nontemporal_store(f32x4_t{sv[0], sv[1], sv[2], sv[3]}, reinterpret_cast<f32x4_t*>(kp));
+                    __builtin_nontemporal_store(f32x4_t{sv[4], sv[5], sv[6], sv[7]}, reinterpret_cast<f32x4_t*>(kp + d));
                 } else {
 #pragma unroll
                     for (int k = 0; k < VW; ++k) {
