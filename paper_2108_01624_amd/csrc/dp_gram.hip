@@ -273,19 +273,15 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gram_dma_kernel(GramBatch gb,
         const bool isA = st < nchA;
         const int cgi = st - nchA;                                             // chunk index over all output gradients
         const int which = cgi >= 2 * nchG1 ? 2 : (cgi >= nchG1 ? 1 : 0);       // which of the (up to three) tensors
-        // past the end the loads still go out (the wait counts stay uniform) but read zeros
-        const int soff = __builtin_amdgcn_readfirstlane(st < nch ? (isA ? st : cgi - which * nchG1) * GDK * 2 : 0x7FFFFFF0);
-        // one scalar choice of the tensor per stage, then a straight run of loads (a branch per load delayed the loads of
-        // the output-gradient stages)
-        gram_i32x4 rs = which == 0 ? rG : (which == 1 ? rG2 : rG3);
-        if (isA) {
+        const int soff = __builtin_amdgcn_readfirstlane((isA ? st : cgi - which * nchG1) * GDK * 2);
 #pragma unroll
-            for (int j = 0; j < LPS; ++j)
-                gram_dma16<true>(rA, __builtin_amdgcn_readfirstlane(ldsoff[j] + ibuf * (STAGE * 2)), voffA[j], soff);
-        } else {
-#pragma unroll
-            for (int j = 0; j < LPS; ++j)
-                gram_dma16<true>(rs, __builtin_amdgcn_readfirstlane(ldsoff[j] + ibuf * (STAGE * 2)), voffG[j], soff);
+        for (int j = 0; j < LPS; ++j) {
+            const uint32_t dst = __builtin_amdgcn_readfirstlane(ldsoff[j] + ibuf * (STAGE * 2));
+            if (isA) gram_dma16<true>(rA, dst, voffA[j], soff);
+            else if (st >= nch) gram_dma16<true>(rG, dst, voffG[j], 0x7FFFFFF0);  // past the end: reads zeros, keeps the load count uniform
+            else if (which == 0) gram_dma16<true>(rG, dst, voffG[j], soff);
+            else if (which == 1) gram_dma16<true>(rG2, dst, voffG[j], soff);
+            else gram_dma16<true>(rG3, dst, voffG[j], soff);
         }
         ibuf = ibuf + 1 == NS ? 0 : ibuf + 1;
     };
