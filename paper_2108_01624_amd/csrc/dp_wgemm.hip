@@ -598,6 +598,8 @@ __global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmBatchArgs b) {
         const bool bias_now = want_bias && duty_ctr == duty;
         duty_ctr = duty_ctr + 1 == duty_mod ? 0 : duty_ctr + 1;
         load_frags(buf, 1, fa1, fg1);
+        // of the two waves that share a SIMD, the one inside an MFMA run goes first (+1 to 3 % measured)
+        __builtin_amdgcn_s_setprio(1);
         if (KIND == POST) {
             // first stage of example ex_run: finish the rescaling PRE began, take over the example's factor
             const int el = __builtin_amdgcn_readfirstlane(ex_run & 63);
@@ -621,6 +623,7 @@ __global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmBatchArgs b) {
             mma(fa0, fg0);
         }
         if (bias_now) mma_bias(fg0);
+        __builtin_amdgcn_s_setprio(0);
         // my loads of the next stage have landed (later stages may still be in flight); after the barrier every
         // wave's have, and every wave has finished reading the stage whose ring slot the newest stage now overwrites
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"((AHEAD - 2) * LPS) : "memory");
@@ -636,6 +639,7 @@ __global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmBatchArgs b) {
         // right after the barrier by all eight waves they queue up in the address unit, and a wave that waits there
         // issues no MFMA either.
         {
+            __builtin_amdgcn_s_setprio(1);
             const int stc = s_issue < nsteps ? s_issue : (nsteps > 0 ? nsteps - 1 : 0);
             const int soffA = __builtin_amdgcn_readfirstlane(stc * BK * a.d_in * 2);
             const int soffG = __builtin_amdgcn_readfirstlane(stc * BK * a.d_out * 2);
@@ -659,6 +663,7 @@ __global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmBatchArgs b) {
                 }
             }
         }
+        __builtin_amdgcn_s_setprio(0);
         ++s_issue;
         ibuf = ibuf + 1 == DMA_NS ? 0 : ibuf + 1;
         if (bias_now) mma_bias(fg1);
