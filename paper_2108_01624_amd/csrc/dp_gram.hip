@@ -274,15 +274,19 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gram_dma_kernel(GramBatch gb,
         const int cgi = st - nchA;                                             // chunk index over all output gradients
         const int which = cgi >= 2 * nchG1 ? 2 : (cgi >= nchG1 ? 1 : 0);       // which of the (up to three) tensors
         const int soff = __builtin_amdgcn_readfirstlane((isA ? st : cgi - which * nchG1) * GDK * 2);
+        // one choice of the source per stage, then a straight run of loads (every descriptor is a variable of its own
+        // and stays in scalar registers; with the choice inside the loop each load of an output-gradient stage went
+        // through a chain of branches)
+        auto run = [&](const gram_i32x4& rs, const int (&voff)[LPS], int so) {
 #pragma unroll
-        for (int j = 0; j < LPS; ++j) {
-            const uint32_t dst = __builtin_amdgcn_readfirstlane(ldsoff[j] + ibuf * (STAGE * 2));
-            if (isA) gram_dma16<true>(rA, dst, voffA[j], soff);
-            else if (st >= nch) gram_dma16<true>(rG, dst, voffG[j], 0x7FFFFFF0);  // past the end: reads zeros, keeps the load count uniform
-            else if (which == 0) gram_dma16<true>(rG, dst, voffG[j], soff);
-            else if (which == 1) gram_dma16<true>(rG2, dst, voffG[j], soff);
-            else gram_dma16<true>(rG3, dst, voffG[j], soff);
-        }
+            for (int j = 0; j < LPS; ++j)
+                gram_dma16<true>(rs, __builtin_amdgcn_readfirstlane(ldsoff[j] + ibuf * (STAGE * 2)), voff[j], so);
+        };
+        if (isA) run(rA, voffA, soff);
+        else if (st >= nch) run(rG, voffG, 0x7FFFFFF0);  // past the end: reads zeros, keeps the load count uniform
+        else if (which == 0) run(rG, voffG, soff);
+        else if (which == 1) run(rG2, voffG, soff);
+        else run(rG3, voffG, soff);
         ibuf = ibuf + 1 == NS ? 0 : ibuf + 1;
     };
     // fragment addresses (elements) inside a stage for k step 0
