@@ -410,14 +410,15 @@ __device__ __forceinline__ float gram_pair_ring(const uint16_t* __restrict__ A, 
         const bool isA = st < nchA;
         // past the last chunk the loads still go out (the wait counts stay uniform) but read zeros
         const int soff = __builtin_amdgcn_readfirstlane(st < nch ? (isA ? st : st - nchA) * GP_K * 2 : 0x7FFFFFF0);
+        auto run = [&](const gram_i32x4& rs, const int (&voff)[2][LPP]) {  // (the choice of the source stays outside the run of loads)
 #pragma unroll
-        for (int pn = 0; pn < (OFFDIAG ? 2 : 1); ++pn)
+            for (int pn = 0; pn < (OFFDIAG ? 2 : 1); ++pn)
 #pragma unroll
-            for (int j = 0; j < LPP; ++j) {
-                const uint32_t dst = __builtin_amdgcn_readfirstlane(ldsoff[j] + (ibuf * 2 * PANEL + pn * PANEL) * 2);
-                if (isA) gram_dma16<false>(rA, dst, voffA[pn][j], soff);
-                else gram_dma16<false>(rG, dst, voffG[pn][j], soff);
-            }
+                for (int j = 0; j < LPP; ++j)
+                    gram_dma16<false>(rs, __builtin_amdgcn_readfirstlane(ldsoff[j] + (ibuf * 2 * PANEL + pn * PANEL) * 2), voff[pn][j], soff);
+        };
+        if (isA) run(rA, voffA);
+        else run(rG, voffG);
         ibuf = ibuf + 1 == GP_NS ? 0 : ibuf + 1;
     };
     int fr[2], fc[2];
