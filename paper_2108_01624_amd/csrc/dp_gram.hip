@@ -14,6 +14,8 @@
 // T flop/B, below the machine balance of ~310 flop/B); each row panel is read once per block it is in.
 #include <stdlib.h>
 
+#include <type_traits>
+
 #include "dp_common.h"
 
 namespace {
@@ -307,45 +309,46 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gram_dma_kernel(GramBatch gb,
 
 #pragma unroll
     for (int st = 0; st < NS - 1; ++st) issue(st);
-    int cbuf = 0;
-    for (int s = 0; s < nch; ++s) {
-        // my loads of chunk s have landed (later chunks may be in flight); after the barrier everyone's have,
-        // and everyone is done reading chunk s-1, whose buffer the newest chunk overwrites
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * LPS) : "memory");
-        __syncthreads();
-        issue(s + NS - 1);
-        if (active) {
-            const uint16_t* st = ring[cbuf];
-            const bool isA = s < nchA;
+    int cbuf = 0, s = 0;
+    // The multiply of one stage is straight-line code: which Gram matrix it feeds and whether the wave owns a diagonal
+    // quadrant are decided outside it (a branch per MFMA pair otherwise).
+    auto compute = [&](f32x16_t (&acc)[2][2], auto diag_tag) {
+        constexpr bool DG = decltype(diag_tag)::value;
+        const uint16_t* st = ring[cbuf];
 #pragma unroll
-            for (int kk = 0; kk < GDK / 16; ++kk) {
-                bf16x8_t a0[2], b0[2];
+        for (int kk = 0; kk < GDK / 16; ++kk) {
+            bf16x8_t a0[2], b0[2];
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    // k chunk 2*kk + lane/32: its swizzled position differs from the kk = 0 one by XOR 2*kk
-                    const int xr = fr[u] ^ ((2 * kk) << 3), xc = fc[u] ^ ((2 * kk) << 3);
-                    a0[u] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(st + xr));
-                    b0[u] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(st + xc));
-                }
-                if (isA) {
-#pragma unroll
-                    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                        for (int nt = 0; nt < 2; ++nt)
-                            if (!(mt == 1 && nt == 0 && diagw))
-                                accA[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mt], b0[nt], accA[mt][nt], 0, 0, 0);
-                } else {
-#pragma unroll
-                    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                        for (int nt = 0; nt < 2; ++nt)
-                            if (!(mt == 1 && nt == 0 && diagw))
-                                accG[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mt], b0[nt], accG[mt][nt], 0, 0, 0);
-                }
+            for (int u = 0; u < 2; ++u) {
+                // k chunk 2*kk + lane/32: its swizzled position differs from the kk = 0 one by XOR 2*kk
+                const int xr = fr[u] ^ ((2 * kk) << 3), xc = fc[u] ^ ((2 * kk) << 3);
+                a0[u] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(st + xr));
+                b0[u] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(st + xc));
             }
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
+                    if (!(DG && mt == 1 && nt == 0))
+                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mt], b0[nt], acc[mt][nt], 0, 0, 0);
         }
-        cbuf = cbuf + 1 == NS ? 0 : cbuf + 1;
-    }
+    };
+    auto phase = [&](int end, f32x16_t (&acc)[2][2]) {
+        for (; s < end; ++s) {
+            // my loads of chunk s have landed (later chunks may be in flight); after the barrier everyone's have,
+            // and everyone is done reading chunk s-1, whose buffer the newest chunk overwrites
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * LPS) : "memory");
+            __syncthreads();
+            issue(s + NS - 1);
+            if (active) {
+                if (diagw) compute(acc, std::true_type{});
+                else compute(acc, std::false_type{});
+            }
+            cbuf = cbuf + 1 == NS ? 0 : cbuf + 1;
+        }
+    };
+    phase(nchA, accA);
+    phase(nch, accG);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing may still be writing LDS when the workgroup ends
     const float bias_term = has_bias ? 1.f : 0.f;
     float sum = 0.f;
