@@ -90,34 +90,35 @@ __global__ __launch_bounds__(256) void colstat_sqnorms_kernel(ColBatch cb, ColKe
     }
     __syncthreads();
     float val = 0.f;
+    float sv[2 * VW];
     if (tg == 0) {
-        float sv[2 * VW];
 #pragma unroll
         for (int k = 0; k < 2 * VW; ++k) {
             sv[k] = (red[0][lane][k] + red[1][lane][k]) + (red[2][lane][k] + red[3][lane][k]);
             const bool on = k < VW ? USE_X : USE_1;
             if (on) val += sv[k] * sv[k];
         }
-        if constexpr (KEEP) {
-            if (col < d) {
-                float* __restrict__ kp = ck.keep[blockIdx.z] + (size_t)i * 2 * d + col;
-                if constexpr (VW == 4) {  // d % 4 == 0 and a 16-byte aligned buffer are checked at the API
-                    __builtin_nontemporal_store(f32x4_t{sv[0], sv[1], sv[2], sv[3]}, reinterpret_cast<f32x4_t*>(kp));
-                    __builtin_nontemporal_store(f32x4_t{sv[4], sv[5], sv[6], sv[7]}, reinterpret_cast<f32x4_t*>(kp + d));
-                } else {
-#pragma unroll
-                    for (int k = 0; k < VW; ++k) {
-                        kp[k] = sv[k];
-                        kp[d + k] = sv[VW + k];
-                    }
-                }
-            }
-        }
     }
     const float tot = dp_block_sum<256>(val, wred);
     if (threadIdx.x == 0) {
         if (direct) out[i] += tot;
         else out[((size_t)i * gridDim.z + blockIdx.z) * J + blockIdx.y] = tot;
+    }
+    // The kept statistics go out last: a store ahead of the reduction's barrier would make every workgroup wait for it.
+    if constexpr (KEEP) {
+        if (tg == 0 && col < d) {
+            float* __restrict__ kp = ck.keep[blockIdx.z] + (size_t)i * 2 * d + col;
+            if constexpr (VW == 4) {  // d % 4 == 0 and a 16-byte aligned buffer are checked at the API
+                __builtin_nontemporal_store(f32x4_t{sv[0], sv[1], sv[2], sv[3]}, reinterpret_cast<f32x4_t*>(kp));
+                __builtin_nontemporal_store(f32x4_t{sv[4], sv[5], sv[6], sv[7]}, reinterpret_cast<f32x4_t*>(kp + d));
+            } else {
+#pragma unroll
+                for (int k = 0; k < VW; ++k) {
+                    kp[k] = sv[k];
+                    kp[d + k] = sv[VW + k];
+                }
+            }
+        }
     }
 }
 
