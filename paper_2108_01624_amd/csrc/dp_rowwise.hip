@@ -432,29 +432,43 @@ __global__ __launch_bounds__(256) void sort_keys_init(const int32_t* __restrict_
     vals[r] = (uint32_t)r;
 }
 
-// hist[b * nchunks + c] = number of keys of chunk c whose digit is b
+// hist[b * nchunks + c] = number of keys of chunk c whose digit is b (integer counters in LDS: the order of the
+// additions does not matter)
 __global__ __launch_bounds__(256) void sort_hist(const uint32_t* __restrict__ keys, int N, int shift,
                                                  uint32_t* __restrict__ hist, int nchunks) {
-    __shared__ uint32_t dig[SORT_CHUNK];
+    __shared__ uint32_t cnt[256];
     const int c = blockIdx.x;
     const int n0 = c * SORT_CHUNK;
     const int valid = N - n0 < SORT_CHUNK ? N - n0 : SORT_CHUNK;
-    for (int k = threadIdx.x; k < valid; k += 256) dig[k] = (keys[n0 + k] >> shift) & 255u;
+    cnt[threadIdx.x] = 0;
     __syncthreads();
-    const uint32_t b = threadIdx.x;
-    uint32_t cnt = 0;
-    for (int k = 0; k < valid; ++k) cnt += dig[k] == b;
-    hist[(size_t)b * nchunks + c] = cnt;
+    for (int k = threadIdx.x; k < valid; k += 256) atomicAdd(&cnt[(keys[n0 + k] >> shift) & 255u], 1u);
+    __syncthreads();
+    hist[(size_t)threadIdx.x * nchunks + c] = cnt[threadIdx.x];
 }
 
-// in-place exclusive scan of `n` counters by one workgroup
+// In-place exclusive prefix sum of hist[0..n): one workgroup, thread t owns a contiguous slice, read and written as
+// 16-byte vectors, eight in flight (n is a multiple of 1024 here: 256 digits x chunks, slices of a multiple of 4).
 __global__ __launch_bounds__(256) void sort_scan(uint32_t* __restrict__ hist, int n) {
     __shared__ uint32_t tsum[256];
-    const int per = (n + 255) / 256;
+    const int per = (n + 255) / 256;  // n % 256 == 0: every slice is full
     const int lo = threadIdx.x * per;
     const int hi = lo + per < n ? lo + per : n;
+    const bool vec = per % 4 == 0;
     uint32_t s = 0;
-    for (int k = lo; k < hi; ++k) s += hist[k];
+    if (vec) {
+        const uint4* p4 = reinterpret_cast<const uint4*>(hist + lo);
+        const int n4 = (hi - lo) / 4;
+        for (int k = 0; k < n4; k += 8) {
+            uint4 t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = k + u < n4 ? p4[k + u] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += (t[u].x + t[u].y) + (t[u].z + t[u].w);
+        }
+    } else {
+        for (int k = lo; k < hi; ++k) s += hist[k];
+    }
     tsum[threadIdx.x] = s;
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -467,33 +481,89 @@ __global__ __launch_bounds__(256) void sort_scan(uint32_t* __restrict__ hist, in
     }
     __syncthreads();
     uint32_t run = tsum[threadIdx.x];
-    for (int k = lo; k < hi; ++k) {
-        const uint32_t t = hist[k];
-        hist[k] = run;
-        run += t;
+    if (vec) {
+        uint4* p4 = reinterpret_cast<uint4*>(hist + lo);
+        const int n4 = (hi - lo) / 4;
+        for (int k = 0; k < n4; k += 8) {
+            uint4 t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = k + u < n4 ? p4[k + u] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                uint4 o;
+                o.x = run; run += t[u].x;
+                o.y = run; run += t[u].y;
+                o.z = run; run += t[u].z;
+                o.w = run; run += t[u].w;
+                if (k + u < n4) p4[k + u] = o;
+            }
+        }
+    } else {
+        for (int k = lo; k < hi; ++k) {
+            const uint32_t t = hist[k];
+            hist[k] = run;
+            run += t;
+        }
     }
 }
 
+// Stable scatter of one chunk by the current digit.  The chunk is cut into groups of 64 consecutive keys (one wave
+// handles a group at a time): digit counts per group (LDS integer counters), an exclusive scan over the groups per
+// digit on top of the chunk's global base, and inside a group the rank of a key among the keys of equal digit at lower
+// positions, from eight ballots.
 __global__ __launch_bounds__(256) void sort_scatter(const uint32_t* __restrict__ keys,
                                                     const uint32_t* __restrict__ vals, int N, int shift,
                                                     const uint32_t* __restrict__ base, int nchunks,
                                                     uint32_t* __restrict__ keys_out, uint32_t* __restrict__ vals_out) {
-    __shared__ uint32_t dig[SORT_CHUNK];
-    __shared__ uint32_t dst[SORT_CHUNK];
+    constexpr int NG = SORT_CHUNK / 64;  // groups per chunk
+    __shared__ uint32_t gcnt[NG][256];
     const int c = blockIdx.x;
     const int n0 = c * SORT_CHUNK;
     const int valid = N - n0 < SORT_CHUNK ? N - n0 : SORT_CHUNK;
-    for (int k = threadIdx.x; k < valid; k += 256) dig[k] = (keys[n0 + k] >> shift) & 255u;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int e = threadIdx.x; e < NG * 256; e += 256) (&gcnt[0][0])[e] = 0;
     __syncthreads();
-    const uint32_t b = threadIdx.x;
-    uint32_t pos = base[(size_t)b * nchunks + c];
-    for (int k = 0; k < valid; ++k)
-        if (dig[k] == b) dst[k] = pos++;  // stable: ascending position inside the chunk
+    uint32_t key[NG / 4], val[NG / 4];
+#pragma unroll
+    for (int q = 0; q < NG / 4; ++q) {
+        const int g = wave + 4 * q, k = g * 64 + lane;
+        key[q] = val[q] = 0;
+        if (k < valid) {
+            key[q] = keys[n0 + k];
+            val[q] = vals[n0 + k];
+            atomicAdd(&gcnt[g][(key[q] >> shift) & 255u], 1u);
+        }
+    }
     __syncthreads();
-    for (int k = threadIdx.x; k < valid; k += 256) {
-        const uint32_t o = dst[k];
-        keys_out[o] = keys[n0 + k];
-        vals_out[o] = vals[n0 + k];
+    {
+        const uint32_t b = threadIdx.x;
+        uint32_t run = base[(size_t)b * nchunks + c];
+#pragma unroll
+        for (int g = 0; g < NG; ++g) {
+            const uint32_t t = gcnt[g][b];
+            gcnt[g][b] = run;
+            run += t;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < NG / 4; ++q) {
+        const int g = wave + 4 * q, k = g * 64 + lane;
+        const bool ok = k < valid;
+        const uint32_t dgt = (key[q] >> shift) & 255u;
+        unsigned long long same = __ballot(ok);
+#pragma unroll
+        for (int bit = 0; bit < 8; ++bit) {
+            const bool one = (dgt >> bit) & 1u;
+            const unsigned long long bal = __ballot(ok && one);
+            same &= one ? bal : ~bal;
+        }
+        if (ok) {
+            const uint32_t rank = (uint32_t)__popcll(same & ((1ull << lane) - 1ull));
+            const uint32_t o = gcnt[g][dgt] + rank;
+            keys_out[o] = key[q];
+            vals_out[o] = val[q];
+        }
     }
 }
 
