@@ -16,7 +16,8 @@
  * then pass 2 (dp_clip_accumulate_* over every layer, "+=" into the fp32 sum buffers), and after the
  * last micro-batch one dp_noise_adamw over the flat parameter space.
  *
- * Per-example gradients are never materialised.  For a dense layer y = xW + b with inputs A_i [T, d_in]
+ * Per-example gradients of the weight tensors are never materialised (the one exception is optional and small:
+ * dp_sqnorms_layernorm_keep writes the 2 d numbers of a LayerNorm per example).  For a dense layer y = xW + b with inputs A_i [T, d_in]
  * and output gradients G_i [T, d_out] of example i (the outer-product form of the fully connected
  * layer's gradient, Section 4.3) the example's weight gradient is A_i^T G_i and its bias gradient is
  * sum_t G_i[t, :].
