@@ -604,6 +604,24 @@ def test_zero_and_empty_calls(dp):
     assert lib.dp_clip_accumulate_layernorm(dp.handle, n.data_ptr(), n.data_ptr(), 1, 4, 0, 8, 1.0, n.data_ptr(), n.data_ptr(), n.data_ptr()) == 0
     dp.sync()
     assert host(n).tolist() == [1, 1, 1, 1]
+    # kept LayerNorm gradients: no examples is a no-op; no tokens means zero gradients, written as such
+    import ctypes
+    d = 8
+    keep = torch.full((4, 2, d), 3.0, dtype=torch.float32, device=DEV)
+    x = torch.ones(4, 1, d, dtype=torch.float32, device=DEV)
+    one = lambda t: (ctypes.c_void_p * 1)(t.data_ptr())
+    assert lib.dp_sqnorms_layernorm_keep(dp.handle, 1, one(x), one(x), 0, 0, 1, d, n.data_ptr(), one(keep)) == 0
+    dp.sync()
+    assert float(host(keep).min()) == 3.0
+    assert lib.dp_sqnorms_layernorm_keep(dp.handle, 1, one(x), one(x), 0, 4, 0, d, n.data_ptr(), one(keep)) == 0
+    dp.sync()
+    assert not host(keep).any() and host(n).tolist() == [1, 1, 1, 1]
+    sg = torch.full((d,), 2.0, dtype=torch.float32, device=DEV)
+    sb = torch.full((d,), 2.0, dtype=torch.float32, device=DEV)
+    assert lib.dp_clip_accumulate_layernorm_kept(dp.handle, 1, one(keep), 0, d, 1.0, n.data_ptr(), one(sg), one(sb)) == 0
+    assert lib.dp_clip_accumulate_layernorm_kept(dp.handle, 1, one(keep), 4, 6, 1.0, n.data_ptr(), one(sg), one(sb)) == -2  # d % 4
+    dp.sync()
+    assert host(sg).tolist() == [2.0] * d and host(sb).tolist() == [2.0] * d
 
 
 @pytest.mark.parametrize("dtype,B,T,d,V", [("bf16", 9, 128, 64, 512), ("bf16", 3, 7, 8, 16), ("f32", 5, 33, 20, 40),
