@@ -49,8 +49,10 @@ struct WgemmArgs {
     int tiles_m, tiles_n, nsplit;
     float* out;          // EPI_STORE: [nsplit][d_in][d_out]; EPI_ADD: [d_in][d_out]; EPI_SQNORM: [nsplit][ntiles]
     int xcd_map;         // 0: plain; 1: split index interleaved over the 8 XCDs; 2: each XCD owns one split and a
-                         // rect_m x rect_n-th sub-rectangle of the tile grid
-    int rect_m, rect_n;  // mode 2: the tile grid is cut into rect_m x rect_n rectangles, 8 / nsplit per split
+                         // rect_m x rect_n-th sub-rectangle of the tile grid; 3 (direct-to-LDS kernel only): the
+                         // (unit, tile) sequence cut into 8 equal runs
+    int rect_m, rect_n;  // mode 2: the tile grid is cut into rect_m x rect_n rectangles, 8 / nsplit per split;
+                         // modes 1 and 3: a unit's tiles are walked in rectangles of this size
 };
 
 // Several layers of one shape in one launch (direct-to-LDS kernel): the unit of work distribution is the pair
@@ -462,8 +464,16 @@ __global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmBatchArgs b) {
         unit = xcd / nrect;
         tile = ((rect / a.rect_n) * tm + slot / tn) * a.tiles_n + (rect % a.rect_n) * tn + slot % tn;
     } else {
-        tile = blockIdx.x % ntiles;
-        unit = blockIdx.x / ntiles;
+        // mode 3: the (unit, tile) pairs in unit-major order, cut into 8 equal runs, one per XCD: balanced for any
+        // unit and tile count; at most 7 units have their tiles on two XCDs
+        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        const int total = nunits * ntiles, per_xcd = (total + 7) >> 3;
+        const int w = xcd * per_xcd + slot;
+        if (slot >= per_xcd || w >= total) return;
+        unit = w / ntiles;
+        const int t = w - unit * ntiles, per = a.rect_m * a.rect_n, rect = t / per, r = t % per;
+        const int rpr = a.tiles_n / a.rect_n;
+        tile = ((rect / rpr) * a.rect_m + r / a.rect_n) * a.tiles_n + (rect % rpr) * a.rect_n + r % a.rect_n;
     }
     const int layer = unit / a.nsplit, split = unit % a.nsplit;
     const uint16_t* Aptr = b.L[layer].A;
@@ -823,20 +833,63 @@ static inline bool range_ok(long rows, int d_in, int d_out) {
     return (rows + 4 * BK) * w * 2 < (1l << 31);
 }
 
-// Row-split count for `total_tiles` tiles: about 256 workgroups (one per CU); counts below 8 are powers of two
-// and larger ones multiples of 8 so that units map onto the 8 XCDs; each split keeps at least 256 rows.
-static long choose_nsplit(long total_tiles, long ksteps) {
-    long nsplit = 1;
-    if (total_tiles < 256) {
-        nsplit = (256 + total_tiles - 1) / total_tiles;
-        const long max_split = (ksteps + 7) / 8;
-        if (nsplit >= 8) nsplit = (nsplit / 8) * 8;
-        else if (nsplit > 4) nsplit = max_split >= 8 ? 8 : 4;
-        else if (nsplit == 3) nsplit = 4;
-        if (nsplit > max_split) nsplit = max_split < 1 ? 1 : max_split;
-        if (nsplit < 1) nsplit = 1;
+namespace {
+// The row splits' partial sums of all layers of a launch, added in one launch: blockIdx.y = layer,
+// out_l[j] += sum_{r<R} part_l[r*n4 + j] with r ascending (a fixed order).
+struct ReduceBatch {
+    const float4* part[MAX_BATCH];
+    float4* out[MAX_BATCH];
+};
+__global__ __launch_bounds__(256) void reduce_layers_kernel(ReduceBatch rb, int R, size_t n4) {
+    const size_t j = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= n4) return;
+    const float4* __restrict__ part = rb.part[blockIdx.y];
+    float4* __restrict__ out = rb.out[blockIdx.y];
+    float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+    int r = 0;
+    for (; r + 4 <= R; r += 4) {  // four independent 16-byte loads in flight; additions stay in order
+        float4 p[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) p[u] = part[(size_t)(r + u) * n4 + j];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            t.x += p[u].x; t.y += p[u].y; t.z += p[u].z; t.w += p[u].w;
+        }
     }
-    return nsplit;
+    for (; r < R; ++r) {
+        const float4 p = part[(size_t)r * n4 + j];
+        t.x += p.x; t.y += p.y; t.z += p.z; t.w += p.w;
+    }
+    float4 o = out[j];
+    o.x += t.x; o.y += t.y; o.z += t.z; o.w += t.w;
+    out[j] = o;
+}
+}  // namespace
+
+// Row-split count of one launch of the direct-to-LDS kernel over `nl` layers of `ntiles` tiles: the count with the
+// smallest modelled time.  An XCD runs 32 workgroups at a time and gets an eighth of the launch's workgroups, so
+// the launch takes ceil(workgroups / 8 / 32) rounds of one workgroup's time (2 us per 64-row stage at the rate
+// the kernel sustains, plus its prologue and epilogue); more than one split sends partial sums through memory
+// (written once, read once, about 4 TB/s) and costs one reduction launch.  `spe`: stages per example
+// (splits start on examples).
+static long choose_nsplit_dma(int nl, int ntiles, long ksteps, long spe, int d_in, int d_out) {
+    const long max_split = ksteps / 8 < 1 ? 1 : ksteps / 8;
+    long best = 1;
+    double best_t = 0.0;
+    for (long s = 1; s <= max_split && s <= 64; ++s) {
+        const long steps_per = ((ksteps + s - 1) / s + spe - 1) / spe * spe;
+        const long se = (ksteps + steps_per - 1) / steps_per;  // the splits that are not empty
+        if (se != s && s > 1) continue;                        // the same plan as a smaller s
+        const long per_xcd = ((long)nl * se * ntiles + 7) / 8;
+        const long rounds = (per_xcd + 31) / 32;
+        double t = (double)rounds * (2.0 * (double)steps_per + 8.0);
+        if (se > 1) t += (double)nl * (double)(se + 2) * d_in * d_out * 4.0 / 4.0e6 + 6.0;
+        if (s == 1 || t < best_t) {
+            best = se;
+            best_t = t;
+        }
+    }
+    return best;
 }
 
 // Clip-weighted sums of n same-shaped dense layers.  Layers that the direct-to-LDS kernel can take (bf16, both
@@ -877,7 +930,8 @@ dp_status dpk_weighted_gemm_batched(dp_ctx* ctx, int n, const void* const* A, co
         a.tiles_m = (d_in + 255) / 256;
         a.tiles_n = (d_out + 255) / 256;
         const int ntiles = a.tiles_m * a.tiles_n;
-        long nsplit = choose_nsplit((long)nl * ntiles, ksteps);
+        const long spe = T / BK;  // row splits begin on examples: the kernel rescales across example boundaries only
+        long nsplit = choose_nsplit_dma(nl, ntiles, ksteps, spe, d_in, d_out);
         while (!range_ok((ksteps + nsplit - 1) / nsplit * BK, d_in, d_out)) nsplit *= 2;
         dp_ws_alloc ws(ctx);
         float* part = nullptr;
@@ -887,7 +941,6 @@ dp_status dpk_weighted_gemm_batched(dp_ctx* ctx, int n, const void* const* A, co
             if (part) break;
             nsplit = nsplit > 8 ? nsplit - 8 : nsplit / 2;  // shrink to what the workspace holds
         }
-        const long spe = T / BK;  // row splits begin on examples: the kernel rescales across example boundaries only
         const long steps_per = ((ksteps + nsplit - 1) / nsplit + spe - 1) / spe * spe;
         a.rows_per_split = steps_per * BK;
         if (!range_ok(a.rows_per_split, d_in, d_out)) {
@@ -897,7 +950,8 @@ dp_status dpk_weighted_gemm_batched(dp_ctx* ctx, int n, const void* const* A, co
         nsplit = (ksteps + steps_per - 1) / steps_per;
         a.nsplit = (int)nsplit;
         const long nunits = (long)nl * nsplit;
-        a.xcd_map = nunits >= 8 ? 1 : 0;
+        // whole units dealt to the XCDs when that is balanced; otherwise equal runs of the (unit, tile) sequence
+        a.xcd_map = nunits % 8 == 0 ? 1 : 3;
         a.rect_m = a.rect_n = 1;
         if (nunits < 8 && 8 % nunits == 0) {
             // 8 / nunits rectangles per unit: the cut with the smallest half-perimeter (operand bytes per XCD)
@@ -916,7 +970,7 @@ dp_status dpk_weighted_gemm_batched(dp_ctx* ctx, int n, const void* const* A, co
             }
             if (best >= 0) a.xcd_map = 2;
         }
-        if (a.xcd_map == 1 && ntiles > 32) {
+        if (a.xcd_map != 2 && ntiles > 32) {
             // rectangle of about 32 tiles (one XCD's worth of workgroups) with the smallest half-perimeter
             int best = -1;
             for (int tm = 1; tm <= a.tiles_m && tm <= 32; ++tm) {
@@ -932,7 +986,7 @@ dp_status dpk_weighted_gemm_batched(dp_ctx* ctx, int n, const void* const* A, co
                 }
             }
         }
-        const long nwg = a.xcd_map == 1 ? ((nunits + 7) / 8) * 8 * ntiles : nunits * ntiles;
+        const long nwg = a.xcd_map == 3 ? (nunits * ntiles + 7) / 8 * 8 : nunits * ntiles;
         if (nwg > 0x7FFFFFFFl) {
             DP_SET_ERR(ctx, "dp_clip_accumulate_dense: too many tiles");
             return DP_ERR_SHAPE;
@@ -965,11 +1019,15 @@ dp_status dpk_weighted_gemm_batched(dp_ctx* ctx, int n, const void* const* A, co
         }
         DP_LAUNCH_CHECK(ctx, "wgemm_dma");
         if (nsplit > 1) {
-            for (int l = 0; l < nl; ++l) {
-                dp_status st = dpk_reduce_partials(ctx, b.L[l].out, (int)nsplit, (size_t)d_in * d_out,
-                                                   (size_t)d_in * d_out, sum_W[l0 + l]);
-                if (st != DP_OK) return st;
+            ReduceBatch rb;
+            for (int l = 0; l < MAX_BATCH; ++l) {
+                rb.part[l] = reinterpret_cast<const float4*>(b.L[l < nl ? l : 0].out);
+                rb.out[l] = reinterpret_cast<float4*>(sum_W[l0 + (l < nl ? l : 0)]);
             }
+            const size_t n4 = (size_t)d_in * d_out / 4;  // d_out is a multiple of 8
+            hipLaunchKernelGGL(reduce_layers_kernel, dim3((unsigned)((n4 + 255) / 256), nl), dim3(256), 0, ctx->stream,
+                               rb, (int)nsplit, n4);
+            DP_LAUNCH_CHECK(ctx, "reduce_layers");
         }
         if (any_bias) {
             hipLaunchKernelGGL(bias_finish_kernel, dim3(nl, (d_out + 255) / 256), dim3(256), 0, ctx->stream, b, nb);

@@ -710,7 +710,10 @@ def test_tied_embedding_out_of_range_id_is_reported(dp):
 # several same-shaped dense layers in one call
 # ------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("n,B,T,d_in,d_out", [(3, 8, 128, 256, 384), (18, 2, 32, 256, 256), (5, 16, 128, 512, 256),
-                                              (2, 3, 50, 512, 264), (3, 4, 64, 72, 136)])
+                                              (2, 3, 50, 512, 264), (3, 4, 64, 72, 136),
+                                              # 9 and 36 tiles per layer: workgroup counts that are no multiple of 8
+                                              # (the balanced XCD mapping, with and without the rectangle walk)
+                                              (5, 12, 128, 768, 768), (3, 4, 128, 768, 3072)])
 def test_clip_accumulate_dense_batched(dp, n, B, T, d_in, d_out):
     C = 1.0
     sq = syn.synthetic_sqnorms(B, C, 300)
