@@ -868,8 +868,8 @@ __global__ __launch_bounds__(256) void reduce_layers_kernel(ReduceBatch rb, int 
 
 // Row-split count of one launch of the direct-to-LDS kernel over `nl` layers of `ntiles` tiles: the count with the
 // smallest modelled time.  An XCD runs 32 workgroups at a time and gets an eighth of the launch's workgroups, so
-// the launch takes ceil(workgroups / 8 / 32) rounds of one workgroup's time (2 us per 64-row stage at the rate
-// the kernel sustains, plus its prologue and epilogue); more than one split sends partial sums through memory
+// the launch takes ceil(workgroups / 8 / 32) rounds of one workgroup's time (1 us per step of BK rows at the rate
+// the kernel sustains, plus 8 us of prologue and epilogue); more than one split sends partial sums through memory
 // (written once, read once, about 4 TB/s) and costs one reduction launch.  `spe`: stages per example
 // (splits start on examples).
 static long choose_nsplit_dma(int nl, int ntiles, long ksteps, long spe, int d_in, int d_out) {
@@ -882,7 +882,7 @@ static long choose_nsplit_dma(int nl, int ntiles, long ksteps, long spe, int d_i
         if (se != s && s > 1) continue;                        // the same plan as a smaller s
         const long per_xcd = ((long)nl * se * ntiles + 7) / 8;
         const long rounds = (per_xcd + 31) / 32;
-        double t = (double)rounds * (2.0 * (double)steps_per + 8.0);
+        double t = (double)rounds * ((double)steps_per + 8.0);
         if (se > 1) t += (double)nl * (double)(se + 2) * d_in * d_out * 4.0 / 4.0e6 + 6.0;
         if (s == 1 || t < best_t) {
             best = se;
@@ -933,13 +933,24 @@ dp_status dpk_weighted_gemm_batched(dp_ctx* ctx, int n, const void* const* A, co
         const long spe = T / BK;  // row splits begin on examples: the kernel rescales across example boundaries only
         long nsplit = choose_nsplit_dma(nl, ntiles, ksteps, spe, d_in, d_out);
         while (!range_ok((ksteps + nsplit - 1) / nsplit * BK, d_in, d_out)) nsplit *= 2;
+        bool any_bias = false;
+        for (int l = 0; l < nl; ++l)
+            if (sum_b && sum_b[l0 + l]) any_bias = true;
+        // partial sums [nl][nsplit][d_in][d_out] and bias partials (one row per unit, tile row and wave row):
+        // fewer splits until the workspace holds both
         dp_ws_alloc ws(ctx);
         float* part = nullptr;
-        while (nsplit > 1) {
-            ws.off = 0;
-            part = ws.get<float>((size_t)nl * nsplit * d_in * d_out);
-            if (part) break;
-            nsplit = nsplit > 8 ? nsplit - 8 : nsplit / 2;  // shrink to what the workspace holds
+        float* bias_part = nullptr;
+        for (;;) {
+            ws.off = ctx->ws_base;
+            part = nsplit > 1 ? ws.get<float>((size_t)nl * nsplit * d_in * d_out) : nullptr;
+            bias_part = any_bias ? ws.get<float>((size_t)nl * nsplit * a.tiles_m * 2 * d_out) : nullptr;
+            if ((nsplit == 1 || part) && (!any_bias || bias_part)) break;
+            if (nsplit == 1) {
+                DP_SET_ERR(ctx, "workspace too small for the bias partials");
+                return DP_ERR_WORKSPACE;
+            }
+            nsplit = nsplit > 8 ? nsplit - 8 : nsplit / 2;
         }
         const long steps_per = ((ksteps + nsplit - 1) / nsplit + spe - 1) / spe * spe;
         a.rows_per_split = steps_per * BK;
@@ -992,25 +1003,15 @@ dp_status dpk_weighted_gemm_batched(dp_ctx* ctx, int n, const void* const* A, co
             return DP_ERR_SHAPE;
         }
         b.n_layers = nl;
-        bool any_bias = false;
         for (int l = 0; l < MAX_BATCH; ++l) {
             const int src = l0 + (l < nl ? l : 0);
             b.L[l].A = (const uint16_t*)A[src];
             b.L[l].G = (const uint16_t*)G[src];
             b.L[l].out = nsplit == 1 ? sum_W[src] : part + (size_t)l * nsplit * d_in * d_out;
             b.L[l].sum_b = sum_b ? sum_b[src] : nullptr;
-            if (l < nl && b.L[l].sum_b) any_bias = true;
         }
-        // bias partials: one row per (unit, tile row, wave row)
-        const int nb = (int)nsplit * a.tiles_m * 2;
-        a.bias_part = nullptr;
-        if (any_bias) {
-            a.bias_part = ws.get<float>((size_t)nl * nb * d_out);
-            if (!a.bias_part) {
-                DP_SET_ERR(ctx, "workspace too small for the bias partials");
-                return DP_ERR_WORKSPACE;
-            }
-        }
+        const int nb = (int)nsplit * a.tiles_m * 2;  // bias partial rows per layer
+        a.bias_part = bias_part;
         {
             dp_prof_scope prof(ctx, DP_PROF_WGEMM, 2.0 * (double)K * d_in * d_out * nl);
             const dim3 grid((unsigned)nwg), block(512);
@@ -1090,13 +1091,20 @@ dp_status dpk_weighted_gemm(dp_ctx* ctx, const void* A, const void* G, dp_dtype 
         if (nsplit < 1) nsplit = 1;
     }
     while (!range_ok((ksteps + nsplit - 1) / nsplit * BK, d_in, d_out)) nsplit *= 2;
+    // partial sums [nsplit][d_in][d_out] and bias partials [nsplit][d_out]: fewer splits until the workspace holds both
     dp_ws_alloc ws(ctx);
     float* part = nullptr;
-    while (nsplit > 1) {
-        ws.off = 0;
-        part = ws.get<float>((size_t)nsplit * d_in * d_out);
-        if (part) break;
-        nsplit = nsplit > 8 ? nsplit - 8 : nsplit / 2;  // shrink to what the workspace holds
+    float* bias_part = nullptr;
+    for (;;) {
+        ws.off = ctx->ws_base;
+        part = nsplit > 1 ? ws.get<float>((size_t)nsplit * d_in * d_out) : nullptr;
+        bias_part = sum_b ? ws.get<float>((size_t)nsplit * d_out) : nullptr;
+        if ((nsplit == 1 || part) && (!sum_b || bias_part)) break;
+        if (nsplit == 1) {
+            DP_SET_ERR(ctx, "workspace too small for the bias partials");
+            return DP_ERR_WORKSPACE;
+        }
+        nsplit = nsplit > 8 ? nsplit - 8 : nsplit / 2;
     }
     const long steps_per = (ksteps + nsplit - 1) / nsplit;
     a.rows_per_split = steps_per * BK;
@@ -1125,14 +1133,7 @@ dp_status dpk_weighted_gemm(dp_ctx* ctx, const void* A, const void* G, dp_dtype 
         }
         if (best >= 0) a.xcd_map = 2;
     }
-    a.bias_part = nullptr;
-    if (sum_b) {
-        a.bias_part = ws.get<float>((size_t)nsplit * d_out);
-        if (!a.bias_part) {
-            DP_SET_ERR(ctx, "workspace too small for the bias partials");
-            return DP_ERR_WORKSPACE;
-        }
-    }
+    a.bias_part = bias_part;
     const long nwg = a.xcd_map == 1 ? ((nsplit + 7) / 8) * 8 * ntiles : nsplit * ntiles;
     if (nwg > 0x7FFFFFFFl) {
         DP_SET_ERR(ctx, "dp_clip_accumulate_dense: too many tiles");

@@ -589,6 +589,45 @@ def test_argument_errors(dp):
     assert not host(x).any()
 
 
+def test_small_workspace(dp):
+    """A context with a 2 MiB workspace: the GEMM takes fewer row splits than it would like and still gives the
+    oracle's sums; a call whose buffers cannot fit returns DP_ERR_WORKSPACE and leaves the context usable."""
+    import paper_2108_01624_amd as pkg
+
+    B, T, d_in, d_out, C = 64, 128, 512, 512, 1.0
+    A, G = gen((B, T, d_in), 1.0, 900, "bf16"), gen((B, T, d_out), 0.1, 901, "bf16")
+    sq = syn.synthetic_sqnorms(B, C, 902)
+    W_ref, b_ref = orc.clip_accumulate_dense(A, G, orc.clip_factors(sq.astype(np.float64), C), True)
+    big = torch.zeros(d_in, d_out, dtype=torch.float32, device=DEV)
+    dp.clip_accumulate_dense(to_dev(A), to_dev(G), C, f32_dev(sq), big, None)
+    dp.sync()
+    with pkg.Context(workspace_bytes=2 << 20) as small:
+        S = torch.zeros(d_in, d_out, dtype=torch.float32, device=DEV)
+        Sb = torch.zeros(d_out, dtype=torch.float32, device=DEV)
+        small.clip_accumulate_dense(to_dev(A), to_dev(G), C, f32_dev(sq), S, Sb)
+        small.sync()
+        assert_sums_close(host(S), W_ref, TOL_BF16, "sum_W, small workspace")
+        assert_sums_close(host(S), host(big).astype(np.float64), 1e-5, "small against default workspace")
+        assert_sums_close(host(Sb), b_ref, 1e-3, "sum_b, small workspace")
+        # the embedding sums sort 8,192 tokens and keep two partial rows per 32-token chunk: 2 x 256 x 1024 floats
+        V, d = 1000, 1024
+        ids = to_dev(syn.zipf_ids(B, T, V, 1.1, 903))
+        Ge = to_dev(gen((B, T, d), 0.1, 904, "bf16"))
+        SE = torch.zeros(V, d, dtype=torch.float32, device=DEV)
+        with pytest.raises(pkg.DpError) as e:
+            small.clip_accumulate_embedding(ids, Ge, V, C, f32_dev(sq), SE)
+        assert e.value.status == -7
+        small.sync()
+        assert not host(SE).any()
+        n = torch.zeros(B, dtype=torch.float32, device=DEV)
+        small.sqnorms_dense(to_dev(A), to_dev(G), True, pkg.DP_PATH_AUTO, n)   # still usable
+        small.sync()
+        n_ref = torch.zeros(B, dtype=torch.float32, device=DEV)
+        dp.sqnorms_dense(to_dev(A), to_dev(G), True, pkg.DP_PATH_AUTO, n_ref)
+        dp.sync()
+        np.testing.assert_array_equal(host(n), host(n_ref))
+
+
 def test_zero_and_empty_calls(dp):
     import paper_2108_01624_amd as pkg
 
@@ -667,7 +706,10 @@ def _tied_case(dtype, B, T, M, d, V, seed):
 
 @pytest.mark.parametrize("dtype,B,T,M,d,V", [("bf16", 6, 128, 20, 128, 1024), ("bf16", 3, 40, 5, 72, 200), ("bf16", 2, 160, 80, 64, 512),
                                              ("bf16", 4, 33, 33, 8, 64), ("f32", 5, 19, 7, 20, 50), ("f32", 2, 70, 3, 130, 33),
-                                             ("bf16", 3, 16, 0, 64, 64), ("bf16", 16, 24, 20, 256, 520)])
+                                             ("bf16", 3, 16, 0, 64, 64), ("bf16", 16, 24, 20, 256, 520),
+                                             # enough rows that the projection's GEMM splits them: partial sums next to
+                                             # the pre-scaled H that the caller holds in the same workspace
+                                             ("bf16", 64, 24, 20, 256, 520)])
 def test_tied_embedding_norms_and_sums(dp, dtype, B, T, M, d, V):
     ids, dY, H, dL = _tied_case(dtype, B, T, M, d, V, 800)
     n0 = np.linspace(0.5, 1.5, B).astype(np.float32)     # the entry point adds to what is there
