@@ -628,6 +628,67 @@ def test_small_workspace(dp):
         np.testing.assert_array_equal(host(n), host(n_ref))
 
 
+def test_tiny_workspace_every_entry_point_works_or_reports(dp):
+    """4 KiB of workspace: every call either needs none of it and gives the default context's result, or returns
+    DP_ERR_WORKSPACE without touching its outputs."""
+    import paper_2108_01624_amd as pkg
+
+    B, T, d, V, C = 48, 128, 256, 300, 1.0
+    A, G = to_dev(gen((B, T, d), 1.0, 910, "bf16")), to_dev(gen((B, T, d), 0.1, 911, "bf16"))
+    A3, G3 = to_dev(gen((B, 50, 72), 1.0, 912, "bf16")), to_dev(gen((B, 50, 136), 0.1, 913, "bf16"))
+    ids = to_dev(syn.zipf_ids(B, T, V, 1.1, 914))
+    sq = f32_dev(syn.synthetic_sqnorms(B, C, 915))
+    zeros = lambda *shape: torch.zeros(*shape, dtype=torch.float32, device=DEV)
+    kw = dict(sigma=0.5, C=C, seed=3, step=1, batch_size=B, lr=1e-3, beta1=0.9, beta2=0.999, weight_decay=0.1)
+    n_par = 100003
+    S0 = syn.normal_f32((n_par,), 1.0, 916)
+
+    def calls(ctx):
+        """(name, outputs, thunk) for one context"""
+        out = []
+        for name, path in (("gram", pkg.DP_PATH_GRAM), ("materialise", pkg.DP_PATH_MATERIALISE)):
+            n = zeros(B)
+            out.append((f"sqnorms_dense {name}", [n], lambda n=n, path=path: ctx.sqnorms_dense(A, G, True, path, n)))
+        n = zeros(B)
+        out.append(("sqnorms_dense ragged", [n], lambda n=n: ctx.sqnorms_dense(A3, G3, True, pkg.DP_PATH_AUTO, n)))
+        n = zeros(B)
+        out.append(("sqnorms_layernorm", [n], lambda n=n: ctx.sqnorms_layernorm(A, G, n)))
+        n = zeros(B)
+        out.append(("sqnorms_embedding", [n], lambda n=n: ctx.sqnorms_embedding(ids, G, V, False, n)))
+        W, b = zeros(d, d), zeros(d)
+        out.append(("clip_accumulate_dense", [W, b], lambda W=W, b=b: ctx.clip_accumulate_dense(A, G, C, sq, W, b)))
+        W, b = zeros(72, 136), zeros(136)
+        out.append(("clip_accumulate_dense ragged", [W, b], lambda W=W, b=b: ctx.clip_accumulate_dense(A3, G3, C, sq, W, b)))
+        g, be = zeros(d), zeros(d)
+        out.append(("clip_accumulate_layernorm", [g, be], lambda g=g, be=be: ctx.clip_accumulate_layernorm(A, G, C, sq, g, be)))
+        E = zeros(V, d)
+        out.append(("clip_accumulate_embedding", [E], lambda E=E: ctx.clip_accumulate_embedding(ids, G, V, C, sq, E)))
+        th, m, v, S, snr = zeros(n_par), zeros(n_par), zeros(n_par), f32_dev(S0), zeros(2)
+        out.append(("noise_adamw_snr", [th, snr], lambda th=th, m=m, v=v, S=S, snr=snr: ctx.noise_adamw_snr(th, m, v, S, snr, **kw)))
+        return out
+
+    ref = calls(dp)
+    for _, _, thunk in ref:
+        thunk()
+    dp.sync()
+    reported = []
+    with pkg.Context(workspace_bytes=4096) as tiny:
+        for (name, outs, thunk), (_, ref_outs, _) in zip(calls(tiny), ref):
+            try:
+                thunk()
+                tiny.sync()
+            except pkg.DpError as e:
+                assert e.status == -7, (name, e)
+                tiny.sync()
+                reported.append(name)
+                for o in outs:
+                    assert not host(o).any(), f"{name}: output touched although the call reported an error"
+                continue
+            for o, r in zip(outs, ref_outs):
+                assert_sums_close(host(o), host(r).astype(np.float64), 1e-5, name)
+    assert "clip_accumulate_embedding" in reported, reported   # the sort buffers of 6,144 tokens cannot fit in 4 KiB
+
+
 def test_zero_and_empty_calls(dp):
     import paper_2108_01624_amd as pkg
 
