@@ -217,6 +217,17 @@ def main():
                       "noise_adamw": phase_ms[2] / args.steps, "input_gen_s": t_gen} if n_micro == 1 else
                      {"whole_step": phase_ms[2] / args.steps, "input_gen_s": t_gen}),
     }
+    if n_micro == 1:
+        # whole-phase rates against the same peaks: pass 1 moves every input byte once, pass 2 is priced at the
+        # dense layers' 2*B*T*d_in*d_out flops only, the update at 28 bytes per parameter
+        p1, p2, p3 = (phase_ms[j] / args.steps * 1e-3 for j in range(3))
+        dense_flops = sum(2.0 * B * T * sp.d_in * sp.d_out for sp in manifest if sp.kind == "dense")
+        out["phase_rates"] = {"pass1_GBps": in_bytes / p1 / 1e9, "pass1_frac_of_hbm_peak": in_bytes / p1 / 1e9 / PEAK_HBM_GBS,
+                              "pass2_TFLOPs": dense_flops / p2 / 1e12,
+                              "pass2_frac_of_mfma_peak": dense_flops / p2 / 1e12 / PEAK_BF16_TFLOPS,
+                              "noise_adamw_GBps_at_28B_per_param": 28.0 * run.P / p3 / 1e9,
+                              "noise_adamw_note": "the update also clears the sum buffer for the next step (32 B per "
+                                                  "parameter moved: kernels.noise_adamw counts those)"}
     if not args.no_cpu_baseline:
         # ~155 GFLOP of fp64 work per BERT-Large example at T=128: a few dozen examples are 10-30 s of host time
         n_ex = args.cpu_examples or max(1, min(B, 32 * 128 // T))
