@@ -287,11 +287,19 @@ dp_status dp_lr_schedule(uint64_t step, double peak, uint64_t warmup_steps, uint
  * dp_rdp_epsilon: a run of n_phases phases, phase p = steps[p] steps at rate q[p], is
  * (alpha, sum_p steps[p] * eps_p(alpha))-RDP; returns the smallest eps = RDP(alpha) + ln(1/delta) / (alpha - 1)
  * over alpha = 2 .. max_alpha and (if best_alpha is not NULL) the order that gives it.
+ * dp_rdp_noise_multiplier: the noise multiplier of Algorithm 1 for a privacy target (Section 3: the accountant is what
+ * gives sigma) - the smallest sigma, to a relative rel_tol in (0,1), for which dp_rdp_epsilon of the same run is at most
+ * eps_target.  The guarantee decreases in sigma: the target is bracketed from sigma = 1 by doubling and halving and the
+ * bracket bisected; the end that meets the target is returned in *sigma (a HOST pointer, like every pointer of these
+ * three functions).  A run that needs no noise (no steps, q = 0) returns a value below 2^-9.  DP_ERR_VALUE if
+ * eps_target <= 0 or no sigma up to 2^20 meets it (eps_target below ln(1/delta) / (max_alpha - 1)).
  * DP_ERR_VALUE for q outside [0,1], sigma <= 0, alpha < 2, delta outside (0,1).
  * ------------------------------------------------------------------------------------------------- */
 dp_status dp_rdp_sampled_gaussian(double q, double sigma, int alpha, double* out);
 dp_status dp_rdp_epsilon(const double* q, const uint64_t* steps, int n_phases, double sigma, double delta, int max_alpha,
                          double* eps, int* best_alpha);
+dp_status dp_rdp_noise_multiplier(const double* q, const uint64_t* steps, int n_phases, double eps_target, double delta,
+                                  int max_alpha, double rel_tol, double* sigma);
 
 /* ---------------------------------------------------------------------------------------------------
  * Kernel timing (for benchmarks): while enabled, the library brackets each launch of its three main

@@ -27,7 +27,9 @@ gradient formulas, norms, clip factors and sums (a second tiny model, with its o
 to the lookup table, for tied_embedding_example_grad); closed forms (T = 1, rank one); clip
 invariant and clip no-op against a flat GEMM / bincount / index_add; torch.optim.AdamW and a
 hand-worked element for the update; statistical moments and exact-uniform checks for the
-normals.  Philox known-answer vectors are NOT in this repository: its raw stream is
+normals; for the privacy accounting, quadrature of the Renyi divergence's definition, closed forms, and
+for the noise-multiplier search the unsampled Gaussian mechanism (whose guarantee the test types out) plus
+minimality of the result.  Philox known-answer vectors are NOT in this repository: its raw stream is
 "parity unpinned" on the CPU beyond an independent big-integer implementation, the
 inverse-round bijection check and avalanche statistics.  The gpu-marked test
 test_philox_matches_rocrand_host_generator pins the words bit for bit against rocRAND's host
@@ -483,7 +485,10 @@ def rdp_sampled_gaussian(q: float, sigma: float, alpha: int) -> float:
 
     if not (0.0 <= q <= 1.0) or sigma <= 0 or alpha < 2:
         raise ValueError("bad accounting arguments")
-    getcontext().prec = 60
+    from decimal import MAX_EMAX, MIN_EMIN
+
+    ctx = getcontext()
+    ctx.prec, ctx.Emax, ctx.Emin = 60, MAX_EMAX, MIN_EMIN   # exp((k^2-k)/(2 sigma^2)) leaves the default exponent range for small sigma
     qd, sd = Decimal(q), Decimal(sigma)
     total = Decimal(0)
     power = lambda x, n: Decimal(1) if n == 0 else x ** n   # 0^0 = 1 (the decimal module refuses it)
@@ -509,3 +514,32 @@ def rdp_epsilon(q, steps, sigma: float, delta: float, max_alpha: int = 256):
         if eps < best[0]:
             best = (eps, alpha)
     return best
+
+
+def rdp_noise_multiplier(q, steps, eps_target: float, delta: float, max_alpha: int = 256, rel_tol: float = 1e-6) -> float:
+    """The noise multiplier of Algorithm 1 for a privacy target (Section 3: the accountant is used to compute it):
+    the smallest sigma, to a relative rel_tol, for which the run's guarantee as rdp_epsilon computes it is at most
+    eps_target.  The guarantee shrinks as sigma grows, so: from sigma = 1, double until the target is met and halve
+    until it is missed (a bracket lo < hi with eps(lo) > target >= eps(hi)), bisect until hi - lo <= rel_tol * hi, and
+    return hi, the end that meets the target.  ValueError if even sigma = 2^20 misses it (the conversion term
+    ln(1/delta) / (max_alpha - 1) alone is above the target)."""
+    if not eps_target > 0.0 or not 0.0 < rel_tol < 1.0:
+        raise ValueError("bad accounting arguments")
+    eps_of = lambda sigma: rdp_epsilon(q, steps, sigma, delta, max_alpha)[0]
+    hi = 1.0
+    while eps_of(hi) > eps_target:
+        hi *= 2.0
+        if hi > 2.0 ** 20:
+            raise ValueError("the target cannot be met with orders up to max_alpha")
+    lo = hi / 2.0
+    while eps_of(lo) <= eps_target:
+        hi, lo = lo, lo / 2.0
+        if lo < 2.0 ** -10:
+            return hi   # no noise to speak of is needed (no steps, or nothing is ever sampled)
+    while hi - lo > rel_tol * hi:
+        mid = 0.5 * (lo + hi)
+        if eps_of(mid) <= eps_target:
+            hi = mid
+        else:
+            lo = mid
+    return hi

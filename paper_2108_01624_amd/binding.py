@@ -62,6 +62,8 @@ SIGNATURES = {
     "dp_rdp_sampled_gaussian": [ctypes.c_double, ctypes.c_double, c_int, ctypes.POINTER(ctypes.c_double)],
     "dp_rdp_epsilon": [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_uint64), c_int, ctypes.c_double, ctypes.c_double,
                        c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_int)],
+    "dp_rdp_noise_multiplier": [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_uint64), c_int, ctypes.c_double, ctypes.c_double,
+                                c_int, ctypes.c_double, ctypes.POINTER(ctypes.c_double)],
     "dp_profile_enable": [c_void_p, c_int],
     "dp_profile_read": [c_void_p, c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_uint64),
                         ctypes.POINTER(ctypes.c_double)],
@@ -414,6 +416,19 @@ def dp_rdp_epsilon(q, steps, sigma, delta, max_alpha=256):
     if st != DP_OK:
         raise DpError(st, "dp_rdp_epsilon")
     return eps.value, arg.value
+
+
+def dp_rdp_noise_multiplier(q, steps, eps_target, delta, max_alpha=256, rel_tol=1e-6) -> float:
+    """Smallest noise multiplier (to rel_tol) whose (eps, delta) guarantee over the run is at most eps_target."""
+    n = len(q)
+    if len(steps) != n:
+        raise ValueError("q and steps must be equally long")
+    out = ctypes.c_double()
+    st = load_library().dp_rdp_noise_multiplier((ctypes.c_double * n)(*q), (c_uint64 * n)(*steps), n, eps_target, delta,
+                                                max_alpha, rel_tol, ctypes.byref(out))
+    if st != DP_OK:
+        raise DpError(st, "dp_rdp_noise_multiplier")
+    return out.value
 
 
 def dp_choose_path(T, d_in, d_out, dtype=DP_BF16) -> int:

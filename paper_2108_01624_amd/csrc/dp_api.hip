@@ -263,6 +263,42 @@ dp_status dp_rdp_epsilon(const double* q, const uint64_t* steps, int n_phases, d
     return DP_OK;
 }
 
+dp_status dp_rdp_noise_multiplier(const double* q, const uint64_t* steps, int n_phases, double eps_target, double delta,
+                                  int max_alpha, double rel_tol, double* sigma) {
+    if (!sigma) return DP_ERR_NULL;
+    if (!(eps_target > 0.0) || !(rel_tol > 0.0 && rel_tol < 1.0)) return DP_ERR_VALUE;
+    // the guarantee shrinks as sigma grows: bracket the target from sigma = 1 by doubling / halving, then bisect
+    double e, hi = 1.0;
+    for (;;) {
+        const dp_status st = dp_rdp_epsilon(q, steps, n_phases, hi, delta, max_alpha, &e, nullptr);
+        if (st != DP_OK) return st;
+        if (e <= eps_target) break;
+        hi *= 2.0;
+        if (hi > 1048576.0) return DP_ERR_VALUE;  // the conversion term of the largest order alone is above the target
+    }
+    double lo = hi / 2.0;
+    for (;;) {
+        const dp_status st = dp_rdp_epsilon(q, steps, n_phases, lo, delta, max_alpha, &e, nullptr);
+        if (st != DP_OK) return st;
+        if (e > eps_target) break;
+        hi = lo;
+        lo = lo / 2.0;
+        if (lo < 1.0 / 1024.0) {  // no noise to speak of is needed (no steps, or nothing is ever sampled)
+            *sigma = hi;
+            return DP_OK;
+        }
+    }
+    while (hi - lo > rel_tol * hi) {
+        const double mid = 0.5 * (lo + hi);
+        const dp_status st = dp_rdp_epsilon(q, steps, n_phases, mid, delta, max_alpha, &e, nullptr);
+        if (st != DP_OK) return st;
+        if (e <= eps_target) hi = mid;
+        else lo = mid;
+    }
+    *sigma = hi;
+    return DP_OK;
+}
+
 dp_status dp_sqnorms_dense(dp_ctx* ctx, const void* A, const void* G, dp_dtype dtype, int B, int T, int d_in,
                            int d_out, int has_bias, dp_path path, float* sqnorms) {
     REQUIRE_CTX(ctx);

@@ -127,3 +127,16 @@ def test_privacy_accounting_matches_the_oracle(lib):
             pkg.dp_rdp_sampled_gaussian(*bad)
     with pytest.raises(pkg.DpError):
         pkg.dp_rdp_epsilon([0.1], [1], 1.0, 0.0, 8)
+    # the noise multiplier for a target: the same search as the oracle's, so the two ends agree to the search tolerance;
+    # the result meets the target by the library's own accounting and nothing three tolerances smaller does
+    tol = 1e-5
+    for target in (2.0, 5.36):
+        got = pkg.dp_rdp_noise_multiplier(q, steps, target, 2.89e-9, 32, tol)
+        ref = orc.rdp_noise_multiplier(q, steps, target, 2.89e-9, 32, tol)
+        assert abs(got - ref) <= 2 * tol * ref, (target, got, ref)
+        assert pkg.dp_rdp_epsilon(q, steps, got, 2.89e-9, 32)[0] <= target
+        assert pkg.dp_rdp_epsilon(q, steps, got * (1 - 3 * tol), 2.89e-9, 32)[0] > target
+    assert pkg.dp_rdp_noise_multiplier([0.1], [0], 1.0, 1e-5, 32, tol) <= 2.0 ** -9      # nothing to protect
+    for bad in ((0.0, tol), (1.0, 0.0), (1.0, 1.0), (0.9 * math.log(1 / 2.89e-9) / 31, tol)):    # last: below the conversion term
+        with pytest.raises(pkg.DpError):
+            pkg.dp_rdp_noise_multiplier(q, steps, bad[0], 2.89e-9, 32, bad[1])

@@ -128,6 +128,12 @@ MUTANTS = [
      "test_rdp_epsilon_composition_over_a_batch_size_schedule"),
     ("rdp_composition_ignores_step_counts", [("rdp = sum(n * rdp_sampled_gaussian(qq, sigma, alpha) for qq, n in zip(q, steps))", "rdp = sum(rdp_sampled_gaussian(qq, sigma, alpha) for qq, n in zip(q, steps))", None)],
      "test_rdp_epsilon_composition_over_a_batch_size_schedule"),
+    ("sigma_search_returns_the_end_that_misses", [("        else:\n            lo = mid\n    return hi", "        else:\n            lo = mid\n    return lo", None)],
+     "test_rdp_noise_multiplier_inverts_the_guarantee"),
+    ("sigma_search_bisects_the_wrong_way", [("        if eps_of(mid) <= eps_target:\n            hi = mid", "        if eps_of(mid) > eps_target:\n            hi = mid", None)],
+     "test_rdp_noise_multiplier_inverts_the_guarantee"),
+    ("sigma_search_stops_at_the_first_bracket", [("    while hi - lo > rel_tol * hi:", "    while hi - lo > 0.25 * hi:", None)],
+     "test_rdp_noise_multiplier_inverts_the_guarantee"),
     ("rdp_takes_the_worst_order", [("        if eps < best[0]:\n            best = (eps, alpha)", "        if eps > best[0] or best[1] == 0:\n            best = (eps, alpha)", None)],
      "test_rdp_epsilon_composition_over_a_batch_size_schedule"),
     ("bf16_widening_shift", [("<< np.uint32(16)", "<< np.uint32(15)", None)], "test_bf16_widening_matches_torch"),

@@ -805,6 +805,42 @@ def test_rdp_epsilon_composition_over_a_batch_size_schedule():
     assert math.isclose(e1, ref, rel_tol=1e-12) and abs(a1 - (1 + math.sqrt(32 * math.log(1e5)))) <= 1
 
 
+def test_rdp_noise_multiplier_inverts_the_guarantee():
+    """The search for sigma against what fixes it: the unsampled Gaussian mechanism, whose guarantee is typed out here
+    (n alpha / (2 sigma^2) + ln(1/delta) / (alpha - 1), best integer order) and strictly decreases in sigma, so the
+    smallest sigma that meets eps(sigma0) is sigma0 itself; then, on the paper's batch-size schedule, that the result
+    meets the target, that nothing 3 tolerances smaller does, and the directions in which it must move."""
+    def eps_plain(sigma, n, delta, max_alpha):
+        return min(n * a / (2 * sigma * sigma) + math.log(1 / delta) / (a - 1) for a in range(2, max_alpha + 1))
+
+    for sigma0, n, delta in [(4.0, 1, 1e-5), (30.0, 100, 1e-6), (0.9, 1, 1e-3), (1.0, 1, 1e-5), (2.0, 7, 1e-4)]:
+        target = eps_plain(sigma0, n, delta, 64)
+        got = orc.rdp_noise_multiplier([1.0], [n], target, delta, 64, 1e-7)
+        assert sigma0 * (1 - 1e-9) <= got <= sigma0 * (1 + 2e-7), (sigma0, got)
+        assert eps_plain(got, n, delta, 64) <= target * (1 + 1e-12)
+
+    n = _schedule_numbers()
+    N, delta = 346_000_000, 2.89e-9
+    sizes = [orc.batch_size_schedule(k * 1875 + 1, n["b_start"], n["b_end"], n["ramp_steps"], n["parts"]) for k in range(5)]
+    q = [b / N for b in sizes]
+    steps = [1875, 1875, 1875, 1875, n["total_steps"] - n["ramp_steps"]]
+    tol = 1e-4
+    sig = {t: orc.rdp_noise_multiplier(q, steps, t, delta, 32, tol) for t in (2.0, 5.36, 10.6)}
+    for t, s in sig.items():
+        assert orc.rdp_epsilon(q, steps, s, delta, 32)[0] <= t                       # meets the target
+        assert orc.rdp_epsilon(q, steps, s * (1 - 3 * tol), delta, 32)[0] > t        # and is the smallest that does
+    assert sig[2.0] > sig[5.36] > sig[10.6]                                          # a tighter target needs more noise
+    longer = orc.rdp_noise_multiplier(q, [2 * k for k in steps], 5.36, delta, 32, tol)
+    assert longer > sig[5.36]                                                        # and so do more steps
+    # below the conversion term of the largest order no sigma helps; with no steps any sigma does
+    with pytest.raises(ValueError):
+        orc.rdp_noise_multiplier(q, steps, 0.9 * math.log(1 / delta) / 31, delta, 32, tol)
+    assert orc.rdp_noise_multiplier([0.1], [0], 1.0, 1e-5, 32, tol) <= 2.0 ** -9
+    for bad in ((0.0, 1e-4), (1.0, 0.0), (1.0, 1.0)):
+        with pytest.raises(ValueError):
+            orc.rdp_noise_multiplier(q, steps, bad[0], delta, 32, bad[1])
+
+
 # ----------------------------------------------------------------------------------------------
 # stored reference (written by tests/golden/make_oracle_reference.py from the oracle alone): drift guard
 # ----------------------------------------------------------------------------------------------
