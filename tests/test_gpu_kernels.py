@@ -816,7 +816,9 @@ def test_tied_embedding_out_of_range_id_is_reported(dp):
                                               (2, 3, 50, 512, 264), (3, 4, 64, 72, 136),
                                               # 9 and 36 tiles per layer: workgroup counts that are no multiple of 8
                                               # (the balanced XCD mapping, with and without the rectangle walk)
-                                              (5, 12, 128, 768, 768), (3, 4, 128, 768, 3072)])
+                                              (5, 12, 128, 768, 768), (3, 4, 128, 768, 3072),
+                                              # widths that end inside a 256-column tile, odd layer counts, T = one and three stages of 64 rows
+                                              (7, 6, 64, 264, 520), (2, 20, 192, 1000, 256)])
 def test_clip_accumulate_dense_batched(dp, n, B, T, d_in, d_out):
     C = 1.0
     sq = syn.synthetic_sqnorms(B, C, 300)
