@@ -723,6 +723,305 @@ __global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmBatchArgs b) {
     }
 }
 
+// The same kernel on the 16x16x32 MFMA.  Per flop it moves as many fragment bytes through LDS, but the matrix pipe draws
+// less power: a loop of nothing but MFMAs on random operands sustains 2.1 PFLOP/s with this shape against 1.4 with
+// 32x32x16 (the chip holds 2.07 against 1.7 GHz; on zeros 2.47 against 1.63 PFLOP/s), and this kernel lives under the
+// power limit.  Wave tile 128 x 64 = 8 x 4 tiles of 16 x 16; a stage (32 rows) is one MFMA step per tile, worked on in
+// two halves of 16 MFMAs (tile rows 0..3, then 4..7) so that the fragments of the next half arrive while this one
+// multiplies: 12 fragments in flight in 48 registers, as before.  Rows r and r + 8 of a stage are read by lanes of the
+// same pass now, so the chunk swizzle also takes bit 3 of the row.
+__device__ __forceinline__ int swz16(int row) { return ((row & 3) << 2) | (((row >> 3) & 1) << 1); }
+
+template <int EPI>
+__global__ __launch_bounds__(512) void wgemm_dma16_kernel(WgemmBatchArgs b) {
+    constexpr int MI = 8, NI = 4, MH = 4, WVN = 4, NT = 512;  // 16 x 16 tiles per wave: MI x NI, worked on in two halves of MH tile rows
+    constexpr int WM = 128, WN = 64, BM = 256, BN = 256;
+    constexpr int LPS = 4;  // LDS-filling loads per wave per stage (2 for A, 2 for G)
+    __shared__ __attribute__((aligned(16))) uint16_t As[DMA_NS][BK * BM];
+    __shared__ __attribute__((aligned(16))) uint16_t Gs[DMA_NS][BK * BN];
+    const WgemmArgs& a = b.base;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: everything derived from it stays in SGPRs
+    const int wr = wave / WVN, wc = wave % WVN;
+    const int ntiles = a.tiles_m * a.tiles_n;
+    const int nunits = b.n_layers * a.nsplit;  // unit = layer * nsplit + split
+    // Workgroup ids are dealt to the 8 XCDs round-robin: an XCD gets whole units (mode 1) or one rectangle of
+    // one unit's tile grid (mode 2), so that its L2 sees each operand row and column about once.
+    int tile, unit;
+    if (a.xcd_map == 1) {
+        const int g = blockIdx.x, slot = g >> 3;
+        unit = (slot / ntiles) * 8 + (g & 7);
+        if (unit >= nunits) return;
+        // An XCD runs about 32 workgroups at a time: walk the unit's tile grid in rect_m x rect_n rectangles so
+        // that those 32 share as many operand columns as possible (rect 1 x 1 = plain row-major order).
+        const int t = slot % ntiles, per = a.rect_m * a.rect_n, rect = t / per, w = t % per;
+        const int rpr = a.tiles_n / a.rect_n;
+        tile = ((rect / rpr) * a.rect_m + w / a.rect_n) * a.tiles_n + (rect % rpr) * a.rect_n + w % a.rect_n;
+    } else if (a.xcd_map == 2) {
+        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        const int nrect = a.rect_m * a.rect_n;
+        const int rect = xcd % nrect;
+        const int tm = a.tiles_m / a.rect_m, tn = a.tiles_n / a.rect_n;
+        unit = xcd / nrect;
+        tile = ((rect / a.rect_n) * tm + slot / tn) * a.tiles_n + (rect % a.rect_n) * tn + slot % tn;
+    } else {
+        // mode 3: the (unit, tile) pairs in unit-major order, cut into 8 equal runs, one per XCD: balanced for any
+        // unit and tile count; at most 7 units have their tiles on two XCDs
+        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+        const int total = nunits * ntiles, per_xcd = (total + 7) >> 3;
+        const int w = xcd * per_xcd + slot;
+        if (slot >= per_xcd || w >= total) return;
+        unit = w / ntiles;
+        const int t = w - unit * ntiles, per = a.rect_m * a.rect_n, rect = t / per, r = t % per;
+        const int rpr = a.tiles_n / a.rect_n;
+        tile = ((rect / rpr) * a.rect_m + r / a.rect_n) * a.tiles_n + (rect % rpr) * a.rect_n + r % a.rect_n;
+    }
+    const int layer = unit / a.nsplit, split = unit % a.nsplit;
+    const uint16_t* Aptr = b.L[layer].A;
+    const uint16_t* Gptr = b.L[layer].G;
+    const int pm = tile / a.tiles_n, qn = tile % a.tiles_n;
+    const int p0 = pm * BM, q0 = qn * BN;
+    const long k_lo = (long)split * a.rows_per_split;
+    const long k_hi = k_lo + a.rows_per_split < a.K ? k_lo + a.rows_per_split : a.K;
+    const int nrows = k_hi > k_lo ? (int)(k_hi - k_lo) : 0;
+    const int nsteps = (nrows + BK - 1) / BK;
+
+    const i32x4_t rA = make_rsrc(Aptr + (size_t)k_lo * a.d_in, (uint32_t)((size_t)nrows * a.d_in * 2));
+    const i32x4_t rG = make_rsrc(Gptr + (size_t)k_lo * a.d_out, (uint32_t)((size_t)nrows * a.d_out * 2));
+
+    // Load j (0, 1) of this wave fills tile rows 4*wave + 2*j and + 1: lane l -> row + l/32, LDS chunk l%32,
+    // which holds global chunk (l%32) ^ swz16(row).
+    int voffA[2], voffG[2];
+    uint32_t ldsA[2], ldsG[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int row0 = 4 * wave + 2 * j, row = row0 + (lane >> 5);
+        const int cg = (lane & 31) ^ swz16(row);
+        voffA[j] = (row * a.d_in + p0 + cg * 8) * 2;
+        voffG[j] = (row * a.d_out + q0 + cg * 8) * 2;
+        ldsA[j] = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)&As[0][row0 * BM];
+        ldsG[j] = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)&Gs[0][row0 * BN];
+    }
+    auto issue = [&](int st, int buf) {
+        // stages past the range load the last stage again (never multiplied): the stage offset is not part of the
+        // buffer bounds check, so it must not run past the rows
+        const int stc = st < nsteps ? st : (nsteps > 0 ? nsteps - 1 : 0);
+        const int soffA = __builtin_amdgcn_readfirstlane(stc * BK * a.d_in * 2);
+        const int soffG = __builtin_amdgcn_readfirstlane(stc * BK * a.d_out * 2);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            dma_load16(rA, __builtin_amdgcn_readfirstlane(ldsA[j] + buf * (BK * BM * 2)), voffA[j], soffA);
+            dma_load16(rG, __builtin_amdgcn_readfirstlane(ldsG[j] + buf * (BK * BN * 2)), voffG[j], soffG);
+        }
+    };
+    // Operand of the 16x16x32 MFMA: lane l holds the 8 consecutive k = 8*(l/16) .. +7 of column l%16 of its tile.  The
+    // transposing read hands lane i of a 16-lane group column i of the 4 rows x 16 columns that the group addresses
+    // (lane i: row i/4, columns 4*(i%4) .. +3): two reads, rows frow and frow + 4 (same swizzle: bits 0, 1, 3 agree).
+    const int frow = 8 * (lane >> 4) + ((lane & 15) >> 2);
+    const int fsw = swz16(frow);
+    int foffA[MI], foffG[NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+        const int col = wr * WM + 16 * i + 4 * (lane & 3);
+        foffA[i] = frow * BM + (((col >> 3) ^ fsw) << 3) + (col & 7);
+    }
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int col = wc * WN + 16 * i + 4 * (lane & 3);
+        foffG[i] = frow * BN + (((col >> 3) ^ fsw) << 3) + (col & 7);
+    }
+    auto load_fa = [&](int buf, int half, bf16x8_t* fa) {
+#pragma unroll
+        for (int i = 0; i < MH; ++i) fa[i] = read_frag(&As[buf][foffA[half * MH + i]], BM);
+    };
+
+    f32x4_t acc[MI][NI], bacc[NI];
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) bacc[j][r] = 0.f;
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
+    }
+    const bool want_bias = b.L[layer].sum_b != nullptr;
+    const int duty_mod = 2 * a.tiles_m, duty = 2 * pm + wr;
+    const uint32_t one2 = 0x3F803F80u;  // two bf16 ones
+    const bf16x8_t ones = __builtin_bit_cast(bf16x8_t, u32x4_t{one2, one2, one2, one2});
+    auto mma_bias = [&](const bf16x8_t* fg) {
+#pragma unroll
+        for (int j = 0; j < NI; ++j) bacc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, fg[j], bacc[j], 0, 0, 0);
+    };
+    // fragments of one stage: tile rows 0..3 (lo), 4..7 (hi) of A and the four tile columns of G
+    bf16x8_t fa_lo[MH], fa_hi[MH], fg[NI];
+    float c_cur = 1.f;  // clip factor of the example being accumulated (set by the example's first stage)
+
+    // prologue: DMA_NS - 1 stages in flight; publish stage 0
+    constexpr int AHEAD = DMA_NS - 1;  // the newest stage in flight is AHEAD stages past the one being multiplied
+#pragma unroll
+    for (int st = 0; st < AHEAD; ++st) issue(st, st);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((AHEAD - 1) * LPS) : "memory");  // stage 0 has landed
+    __syncthreads();
+    int buf = 0;      // ring slot of the stage being multiplied
+    int ibuf = AHEAD; // ring slot the next load fills
+    load_fa(buf, 0, fa_lo);
+#pragma unroll
+    for (int j = 0; j < NI; ++j) fg[j] = read_frag(&Gs[buf][foffG[j]], BN);
+
+    // One loop iteration = one stage = one barrier.
+    int my = 0;      // the stage being multiplied; stages >= nsteps hold zeros
+    int duty_ctr = 0;  // my % duty_mod
+    const int spe = a.T / BK;                                  // stages per example (>= 2)
+    int ex_run = (int)((uint32_t)k_lo / (uint32_t)a.T);        // the next example to start (row splits begin on examples)
+    const int nex = (int)(a.K / a.T);
+    // lane l: clip factor c_e of example e = (ex & ~63) + l and the rescaling ratio c_{e-1} / c_e that applies when
+    // example e starts.  Two plain loads per 64 examples; the compiler's wait for them also waits for the
+    // LDS-filling loads in flight, a bubble once per 256 or more stages.
+    float cvec = 1.f, rvec = 1.f;
+    auto load_factors = [&](int ex) {
+        const int e = (ex & ~63) + lane;
+        const float n_e = e < nex ? a.sqnorms[e] : 1.f;
+        const float n_p = (e >= 1 && e - 1 < nex) ? a.sqnorms[e - 1] : n_e;
+        cvec = dp_clip_factor(n_e, a.C);
+        rvec = dp_clip_factor(n_p, a.C) / cvec;
+    };
+    if (nsteps > 0) load_factors(ex_run);
+    int s_issue = AHEAD;
+    // Rescaling at an example boundary (every accumulator register times c_prev / c_next) is spread over the two halves
+    // around it: in the second half of the example's last stage (PRE) a tile of the first half is multiplied in every
+    // MFMA slot and a tile of the second half two MFMAs after its own MFMA; the last two tiles directly before their
+    // MFMAs in the second half of the next example's first stage (POST).  Every stage kind is a straight-line body.
+    constexpr int PLAIN = 0, POST = 1, PRE = 2;
+    float ratio = 1.f;  // c_prev / c_next of the boundary being worked on (set in PRE, used up in POST)
+    auto scale_tile = [&](int i, int j) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[i][j][r] *= ratio;
+    };
+    auto body = [&](auto kind_tag) {
+        constexpr int KIND = decltype(kind_tag)::value;
+        const int buf1 = buf + 1 == DMA_NS ? 0 : buf + 1;
+        const bool bias_now = want_bias && duty_ctr == duty;
+        duty_ctr = duty_ctr + 1 == duty_mod ? 0 : duty_ctr + 1;
+        load_fa(buf, 1, fa_hi);  // needed by the second half
+        // of the two waves that share a SIMD, the one inside an MFMA run goes first
+        __builtin_amdgcn_s_setprio(1);
+        if (KIND == POST) {
+            // first stage of example ex_run: take over the example's factor
+            const int el = __builtin_amdgcn_readfirstlane(ex_run & 63);
+            c_cur = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cvec), el));
+            ++ex_run;
+        }
+        // first half: tile rows 0..3, tile column by tile column
+#pragma unroll
+        for (int t = 0; t < MH * NI; ++t) {
+            const int i = t % MH, j = t / MH;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa_lo[i], fg[j], acc[i][j], 0, 0, 0);
+        }
+        if (KIND == POST) {
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) bacc[j][r] *= ratio;
+        }
+        if (bias_now) mma_bias(fg);
+        __builtin_amdgcn_s_setprio(0);
+        // my loads of the next stage have landed (later stages may still be in flight); after the barrier every
+        // wave's have, and every wave has finished reading the stage whose ring slot the newest stage now overwrites
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((AHEAD - 2) * LPS) : "memory");
+        __syncthreads();
+        load_fa(buf1, 0, fa_lo);  // the next stage's first half
+        if (KIND == PRE) {
+            // last stage of example ex_run - 1; the factors of 64 examples sit in registers (lane = example mod 64)
+            if ((ex_run & 63) == 0) load_factors(ex_run);
+            const int el = __builtin_amdgcn_readfirstlane(ex_run & 63);
+            ratio = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, rvec), el));
+        }
+        // second half: tile rows 4..7.  When a tile column is done its G fragment makes room for the next stage's,
+        // and one of the four LDS-filling loads of the newest stage goes out (spread, not back to back: issued
+        // together by all eight waves they queue up in the address unit).
+        {
+            __builtin_amdgcn_s_setprio(1);
+            const int stc = s_issue < nsteps ? s_issue : (nsteps > 0 ? nsteps - 1 : 0);
+            const int soffA = __builtin_amdgcn_readfirstlane(stc * BK * a.d_in * 2);
+            const int soffG = __builtin_amdgcn_readfirstlane(stc * BK * a.d_out * 2);
+#pragma unroll
+            for (int t = 0; t < MH * NI; ++t) {
+                const int i = MH + t % MH, j = t / MH;
+                if (KIND == POST && t >= MH * NI - 2) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    scale_tile(i, j);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa_hi[t % MH], fg[j], acc[i][j], 0, 0, 0);
+                if (t % MH == MH - 1) {
+                    const int jj = j >> 1;
+                    __builtin_amdgcn_sched_barrier(0);
+                    fg[j] = read_frag(&Gs[buf1][foffG[j]], BN);
+                    if ((j & 1) == 0)
+                        dma_load16(rA, __builtin_amdgcn_readfirstlane(ldsA[jj] + ibuf * (BK * BM * 2)), voffA[jj], soffA);
+                    else
+                        dma_load16(rG, __builtin_amdgcn_readfirstlane(ldsG[jj] + ibuf * (BK * BN * 2)), voffG[jj], soffG);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if (KIND == PRE) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    scale_tile(t % MH, t / MH);
+                    if (t >= 2) scale_tile(MH + (t - 2) % MH, (t - 2) / MH);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+        __builtin_amdgcn_s_setprio(0);
+        ++s_issue;
+        ibuf = ibuf + 1 == DMA_NS ? 0 : ibuf + 1;
+        buf = buf1;
+        ++my;
+    };
+    // The unit's rows are whole examples (the host aligns row splits to examples), at least two stages each.
+    const int n_ex_unit = nsteps / spe;
+    for (int e = 0; e + 1 < n_ex_unit; ++e) {
+        body(std::integral_constant<int, POST>{});
+        for (int q = 0; q < spe - 2; ++q) body(std::integral_constant<int, PLAIN>{});
+        body(std::integral_constant<int, PRE>{});
+    }
+    if (n_ex_unit > 0) {
+        body(std::integral_constant<int, POST>{});
+        for (int q = 0; q < spe - 1; ++q) body(std::integral_constant<int, PLAIN>{});
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing may still be writing LDS when the workgroup ends
+
+    // MFMA tile (i, j): accumulator register r of lane l holds row 4*(l/16) + r, column l%16.
+    float* base = b.L[layer].out + (EPI == EPI_STORE ? (size_t)split * a.d_in * a.d_out : (size_t)0);
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int p = p0 + wr * WM + 16 * i + 4 * (lane >> 4) + r;
+            if (p < a.d_in) {
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    const int q = q0 + wc * WN + 16 * j + (lane & 15);
+                    if (q < a.d_out) {
+                        float* dst = base + (size_t)p * a.d_out + q;
+                        if (EPI == EPI_ADD) *dst += acc[i][j][r] * c_cur;
+                        else *dst = acc[i][j][r] * c_cur;
+                    }
+                }
+            }
+        }
+    if (want_bias && lane < 16) {
+        // every row of the ones-product equals the column sums; row 0 sits in register 0 of lanes 0..15
+        float* bp = a.bias_part + ((size_t)(unit * a.tiles_m + pm) * 2 + wr) * a.d_out;
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int q = q0 + wc * WN + 16 * j + lane;
+            if (q < a.d_out) bp[q] = bacc[j][0] * c_cur;
+        }
+    }
+}
+
 // sum_b[layer][q] += sum over the layer's nb partial rows, in row order (fixed order).  grid (n_layers, d_out/256).
 __global__ __launch_bounds__(256) void bias_finish_kernel(WgemmBatchArgs b, int nb) {
     const int layer = blockIdx.x;
@@ -825,6 +1124,16 @@ static inline int tile_cfg(int d_in, int d_out) {
         big_cfg = (e && e[0] == '4') ? 1 : 2;
     }
     return big_tile(d_in, d_out) ? big_cfg : 0;
+}
+
+// MFMA shape of the direct-to-LDS kernel: 16 (16x16x32, the default) or 32 (32x32x16; DPCLIP_GEMM_MFMA=32, tuning aid).
+static inline int dma_mfma_shape() {
+    static int shape = -1;
+    if (shape < 0) {
+        const char* e = getenv("DPCLIP_GEMM_MFMA");
+        shape = (e && e[0] == '3') ? 32 : 16;
+    }
+    return shape;
 }
 
 // A split's rows of one operand must stay below 2^31 bytes (32-bit buffer offsets).
@@ -1015,8 +1324,13 @@ dp_status dpk_weighted_gemm_batched(dp_ctx* ctx, int n, const void* const* A, co
         {
             dp_prof_scope prof(ctx, DP_PROF_WGEMM, 2.0 * (double)K * d_in * d_out * nl);
             const dim3 grid((unsigned)nwg), block(512);
-            if (nsplit == 1) hipLaunchKernelGGL((wgemm_dma_kernel<EPI_ADD>), grid, block, 0, ctx->stream, b);
-            else hipLaunchKernelGGL((wgemm_dma_kernel<EPI_STORE>), grid, block, 0, ctx->stream, b);
+            if (dma_mfma_shape() == 16) {
+                if (nsplit == 1) hipLaunchKernelGGL((wgemm_dma16_kernel<EPI_ADD>), grid, block, 0, ctx->stream, b);
+                else hipLaunchKernelGGL((wgemm_dma16_kernel<EPI_STORE>), grid, block, 0, ctx->stream, b);
+            } else {
+                if (nsplit == 1) hipLaunchKernelGGL((wgemm_dma_kernel<EPI_ADD>), grid, block, 0, ctx->stream, b);
+                else hipLaunchKernelGGL((wgemm_dma_kernel<EPI_STORE>), grid, block, 0, ctx->stream, b);
+            }
         }
         DP_LAUNCH_CHECK(ctx, "wgemm_dma");
         if (nsplit > 1) {

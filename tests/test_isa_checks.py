@@ -46,7 +46,7 @@ def _kernels(text):
 
 
 @pytest.mark.parametrize("src,hot", [("dp_gram.hip", ("gram_dma_kernel", "gram_pairs_dma_kernel", "gram_small_dma_kernel")),
-                                     ("dp_wgemm.hip", ("wgemm_dma_kernel",))])
+                                     ("dp_wgemm.hip", ("wgemm_dma_kernel", "wgemm_dma16_kernel"))])
 def test_lds_filling_kernels_keep_descriptors_scalar_and_use_no_scratch(src, hot, tmp_path):
     kernels = _kernels(_isa(src, tmp_path))
     seen = 0
