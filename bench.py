@@ -175,7 +175,7 @@ def main():
     tpath = os.path.join(ROOT, "profiles", f"bench_{args.workload.lower()}_hbm_traffic.json")
     if not args.batch and os.path.exists(tpath):
         try:
-            k = json.load(open(tpath))["kernels"]["wgemm_dma_kernel"]
+            k = json.load(open(tpath))["kernels"]["wgemm_dma16_kernel"]
             traffic = k["hbm_read_bytes_per_launch"] + k["hbm_write_bytes_per_launch"]
         except Exception:
             traffic = None
@@ -203,7 +203,7 @@ def main():
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
                      "traffic_unit": "HBM bytes per launch (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, profiles/)",
-                     "kernel": "wgemm_dma_kernel (clip-weighted A^T diag(c) G, up to 32 same-shaped layers per launch)",
+                     "kernel": "wgemm_dma16_kernel (clip-weighted A^T diag(c) G, up to 32 same-shaped layers per launch)",
                      "avg_launch_ms": g_ms / max(1, g_n), "launches": int(g_n)},
         "kernels": {
             "gram_sqnorms": {"bound": "hbm", "achieved_GBps": n_bytes / (n_ms * 1e-3) / 1e9 if n_ms else 0.0,
