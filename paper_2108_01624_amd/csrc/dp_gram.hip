@@ -424,25 +424,27 @@ __device__ __forceinline__ float gram_pair_ring(const uint16_t* __restrict__ A, 
         else run(rG, voffG);
         ibuf = ibuf + 1 == GP_NS ? 0 : ibuf + 1;
     };
-    int fr[2], fc[2];
+    // operand of the 16x16x32 MFMA (less power per flop than 32x32x16): lane l holds k = 8*(l/16) .. +7 of row l%16 of
+    // its 16-row tile, i.e. 16-byte chunk 4*kk + l/16 of that row; a wave's 64 x 64 quadrant is 4 x 4 such tiles
+    int fr[4], fc[4];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-        const int r = wr * 64 + u * 32 + (lane & 31), c = wc * 64 + u * 32 + (lane & 31);
-        fr[u] = r * GP_K + (((lane >> 5) ^ swz(r)) << 3);
-        fc[u] = c * GP_K + (((lane >> 5) ^ swz(c)) << 3) + (OFFDIAG ? PANEL : 0);
+    for (int u = 0; u < 4; ++u) {
+        const int r = wr * 64 + u * 16 + (lane & 15), c = wc * 64 + u * 16 + (lane & 15);
+        fr[u] = r * GP_K + (((lane >> 4) ^ swz(r)) << 3);
+        fc[u] = c * GP_K + (((lane >> 4) ^ swz(c)) << 3) + (OFFDIAG ? PANEL : 0);
     }
-    f32x16_t accA[2][2], accG[2][2];
+    f32x4_t accA[4][4], accG[4][4];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < 4; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < 4; ++b)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) accA[a][b][r] = accG[a][b][r] = 0.f;
+            for (int r = 0; r < 4; ++r) accA[a][b][r] = accG[a][b][r] = 0.f;
 
 #pragma unroll
     for (int st = 0; st < GP_NS - 1; ++st) issue(st);
     int cbuf = 0, s_next = GP_NS - 1;
-    auto stage = [&](f32x16_t (&acc)[2][2]) {
+    auto stage = [&](f32x4_t (&acc)[4][4]) {
         // my loads of this chunk have landed (up to three later chunks may be in flight); after the barrier everyone's
         // have, and everyone is done reading the previous chunk, whose slot the newest chunk overwrites
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"((GP_NS - 2) * LPS) : "memory");
@@ -451,20 +453,20 @@ __device__ __forceinline__ float gram_pair_ring(const uint16_t* __restrict__ A, 
         if (active) {
             const uint16_t* st = ring[cbuf];
 #pragma unroll
-            for (int kk = 0; kk < GP_K / 16; ++kk) {
-                bf16x8_t a0[2], b0[2];
+            for (int kk = 0; kk < GP_K / 32; ++kk) {
+                bf16x8_t a0[4], b0[4];
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const int xr = fr[u] ^ ((2 * kk) << 3), xc = fc[u] ^ ((2 * kk) << 3);
+                for (int u = 0; u < 4; ++u) {
+                    const int xr = fr[u] ^ ((4 * kk) << 3), xc = fc[u] ^ ((4 * kk) << 3);
                     a0[u] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(st + xr));
                     b0[u] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(st + xc));
                 }
 #pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
+                for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-                    for (int nt = 0; nt < 2; ++nt)
-                        if (!(mt == 1 && nt == 0 && diagw))
-                            acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0[mt], b0[nt], acc[mt][nt], 0, 0, 0);
+                    for (int nt = 0; nt < 4; ++nt)
+                        if (!(mt > nt && diagw))
+                            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[mt], b0[nt], acc[mt][nt], 0, 0, 0);
             }
         }
         cbuf = cbuf + 1 == GP_NS ? 0 : cbuf + 1;
@@ -474,12 +476,12 @@ __device__ __forceinline__ float gram_pair_ring(const uint16_t* __restrict__ A, 
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing may still be writing LDS past this point
     float sum = 0.f;
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < 4; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < 4; ++b)
 #pragma unroll
-            for (int r = 0; r < 16; ++r)
-                sum += (a == 0 && b == 1 && diagw ? 2.f : 1.f) * ((accA[a][b][r] + bias_term) * accG[a][b][r]);  // skipped tiles hold zeros
+            for (int r = 0; r < 4; ++r)
+                sum += (a < b && diagw ? 2.f : 1.f) * ((accA[a][b][r] + bias_term) * accG[a][b][r]);  // skipped tiles hold zeros
     return sum * (OFFDIAG ? 2.f : (wr == wc ? 1.f : (wr < wc ? 2.f : 0.f)));
 }
 
