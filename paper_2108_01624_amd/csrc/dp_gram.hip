@@ -372,8 +372,8 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gram_dma_kernel(GramBatch gb,
 // fed like the kernel above: the two row panels of a 64-wide contraction chunk (32 KiB; 16 KiB on the diagonal,
 // where they coincide) go straight into an LDS ring, no staging registers and no LDS store instructions.  At this
 // size the contraction, not HBM, is the bound (T flop per byte against ~310 at the machine balance), and within the
-// contraction the LDS reads: with 64 x 64 wave tiles every 32x32x16 MFMA needs one 16-byte-per-lane fragment read,
-// which by itself keeps the CU's LDS port busy.  Two stages and two workgroups per CU measured best (22.9 ms for
+// contraction the LDS reads: with 64 x 64 wave tiles a k step of 32 needs eight 16-byte-per-lane fragment reads for
+// sixteen 16x16x32 MFMAs (1 KiB per 32 matrix-pipe cycles and SIMD), which by itself keeps the CU's LDS port busy.  Two stages and two workgroups per CU measured best (22.9 ms for
 // pass 1 of the T = 512 workload against 27.7 ms for the register-staged kernel); a deeper ring with one workgroup
 // per CU (one wave per SIMD) was slower (31 ms).  The block pairs of an example share an XCD (workgroup id % 8), so
 // each panel comes from HBM once and from L2 for its other uses.
