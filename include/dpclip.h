@@ -230,7 +230,7 @@ dp_status dp_noise_adamw(dp_ctx* ctx, float* params, float* m, float* v, float* 
                          int zero_sum);
 
 /* The same update, which also measures the two vectors whose ratio is the gradient signal-to-noise ratio
- * of Section 5.2 (effect of batch size on DP gradients) while they pass through registers, at no extra
+ * of Section 5.2.1 (effect of batch size on DP gradients) while they pass through registers, at no extra
  * memory traffic:
  *     snr_sq[0] += sum_e sum[e]^2               (the aggregated clipped gradient, before the division by |B_t|)
  *     snr_sq[1] += sum_e (sigma*C*z_e)^2        (the noise vector added to it; 0 if sigma == 0)
@@ -261,7 +261,7 @@ dp_status dp_choose_path(int T, int d_in, int d_out, dp_dtype dtype, dp_path* ou
  * Schedules: the per-step scalars q_t (batch size) and eta_t (learning rate) of Algorithm 1's input list.
  * Host-only, pure; `out` is a HOST pointer; `step` counts from 1; DP_ERR_VALUE on inconsistent arguments.
  *
- * dp_batch_size_schedule: the increasing batch-size schedule of the batch-size study (Section 5.2.1): the
+ * dp_batch_size_schedule: the increasing batch-size schedule of Section 5.2.2 (batch size schedule improves efficiency): the
  * batch grows from b_start to b_end over ramp_steps steps in n_increments equal jumps of
  * floor((b_end - b_start) / n_increments), the k-th one once k/n_increments of the ramp's steps are complete,
  * the last one landing exactly on b_end (the paper's run: 262144 -> 1048576 over 7500 steps in 4 jumps of
@@ -312,6 +312,12 @@ dp_status dp_rdp_noise_multiplier(const double* q, const uint64_t* steps, int n_
 typedef enum { DP_PROF_WGEMM = 0, DP_PROF_GRAM = 1, DP_PROF_ADAMW = 2 } dp_prof_kind;
 dp_status dp_profile_enable(dp_ctx* ctx, int enable);
 dp_status dp_profile_read(dp_ctx* ctx, dp_prof_kind kind, double* ms_total, uint64_t* launches, double* work_total);
+/* Calibration for the roofline of the clip-weighted sum (the dominant kernel of Algorithm 1's g_t line): runs a loop of
+ * nothing but the bf16 16x16x32 matrix instructions of that kernel (same accumulator tiles and waves per CU, operands
+ * held in registers, pseudo-random values), `launches` launches of `iters` loop iterations each after one warm-up
+ * launch, and returns the rate they sustain in TFLOP/s (*tflops, a HOST pointer): what the card's power limit leaves of
+ * the nominal matrix peak.  Synchronises the stream.  iters in [1, 2^20], launches in [1, 1024], else DP_ERR_VALUE. */
+dp_status dp_profile_mfma_ceiling(dp_ctx* ctx, int iters, int launches, double* tflops);
 
 #ifdef __cplusplus
 }

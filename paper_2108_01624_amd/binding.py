@@ -67,6 +67,7 @@ SIGNATURES = {
     "dp_profile_enable": [c_void_p, c_int],
     "dp_profile_read": [c_void_p, c_int, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(c_uint64),
                         ctypes.POINTER(ctypes.c_double)],
+    "dp_profile_mfma_ceiling": [c_void_p, c_int, c_int, ctypes.POINTER(ctypes.c_double)],
 }
 _RESTYPES = {"dp_status_str": c_char_p, "dp_last_error": c_char_p}
 
@@ -449,6 +450,13 @@ def dp_profile_read(ctx, kind: int):
     st = load_library().dp_profile_read(ctx, kind, ctypes.byref(ms), ctypes.byref(cnt), ctypes.byref(work))
     _check(ctx, st, "dp_profile_read")
     return ms.value, cnt.value, work.value
+
+
+def dp_profile_mfma_ceiling(ctx, iters: int = 4096, launches: int = 8) -> float:
+    """-> TFLOP/s that a register-only loop of the GEMM's bf16 matrix instructions sustains on this card."""
+    out = ctypes.c_double()
+    _check(ctx, load_library().dp_profile_mfma_ceiling(ctx, iters, launches, ctypes.byref(out)), "dp_profile_mfma_ceiling")
+    return out.value
 
 
 class Context:

@@ -151,6 +151,13 @@ dp_status dp_profile_read(dp_ctx* ctx, dp_prof_kind kind, double* ms_total, uint
     return DP_OK;
 }
 
+dp_status dp_profile_mfma_ceiling(dp_ctx* ctx, int iters, int launches, double* tflops) {
+    REQUIRE_CTX(ctx);
+    if (!tflops) FAIL(ctx, DP_ERR_NULL, "tflops is NULL");
+    if (iters < 1 || iters > (1 << 20) || launches < 1 || launches > 1024) FAIL(ctx, DP_ERR_VALUE, "iters in [1, 2^20], launches in [1, 1024]");
+    return dpk_mfma_ceiling(ctx, iters, launches, tflops);
+}
+
 dp_status dp_sync(dp_ctx* ctx) {
     REQUIRE_CTX(ctx);
     DP_HIP_CHECK(ctx, hipStreamSynchronize(ctx->stream));
@@ -158,7 +165,8 @@ dp_status dp_sync(dp_ctx* ctx) {
     DP_HIP_CHECK(ctx, hipMemcpy(&w, ctx->err_word, sizeof(int), hipMemcpyDeviceToHost));
     if (w) {
         DP_HIP_CHECK(ctx, hipMemset(ctx->err_word, 0, sizeof(int)));
-        FAIL(ctx, DP_ERR_INDEX, "a token id outside [0, V) was met on the device");
+        if (w & DP_ERRBIT_INDEX) FAIL(ctx, DP_ERR_INDEX, "a token id outside [0, V) was met on the device");
+        FAIL(ctx, DP_ERR_VALUE, "a per-example squared norm was NaN or overflowed fp32: the sums it entered hold NaN");
     }
     return DP_OK;
 }

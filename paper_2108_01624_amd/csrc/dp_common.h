@@ -19,7 +19,7 @@ struct dp_ctx {
     char* ws;         // device workspace
     size_t ws_bytes;
     size_t ws_base;   // bytes at the start of the workspace held by an enclosing step of the current call
-    int* err_word;    // device: bit 0 = token id out of range
+    int* err_word;    // device: bit 0 = token id out of range, bit 1 = a squared norm that is not a finite number
     float* cbuf;      // device: clip factors of the current micro-batch
     int cbuf_cap;     // capacity of cbuf in floats
     int prof_on;
@@ -146,8 +146,12 @@ __device__ __forceinline__ float dp_block_sum(float v, float* red) {
     return t;
 }
 
+constexpr int DP_ERRBIT_INDEX = 1, DP_ERRBIT_NORM = 2;
+
 __device__ __forceinline__ float dp_clip_factor(float sqnorm, float C) {
-    // c = min(1, C / ||g||); a zero gradient keeps factor 1
+    // c = min(1, C / ||g||); a zero gradient keeps factor 1.  A squared norm that is NaN or overflowed fp32 has no
+    // clip factor: NaN, on every path alike, so that the sums it enters are NaN too (and dp_sync reports it).
+    if (!(sqnorm < __builtin_inff())) return __builtin_nanf("");
     return sqnorm > 0.f ? fminf(1.f, C / sqrtf(sqnorm)) : 1.f;
 }
 
@@ -179,6 +183,7 @@ dp_status dpk_materialise_sqnorms(dp_ctx*, const void* A, const void* G, dp_dtyp
 dp_status dpk_weighted_gemm(dp_ctx*, const void* A, const void* G, dp_dtype, int B, int T, int d_in, int d_out,
                             const float* sqnorms, float C, float* sum_W, float* sum_b);
 
+dp_status dpk_mfma_ceiling(dp_ctx*, int iters, int launches, double* tflops);
 dp_status dpk_weighted_gemm_batched(dp_ctx*, int n, const void* const* A, const void* const* G, dp_dtype, int B, int T,
                                     int d_in, int d_out, const float* sqnorms, float C, float* const* sum_W,
                                     float* const* sum_b);

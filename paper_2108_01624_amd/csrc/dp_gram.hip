@@ -197,12 +197,12 @@ __device__ __forceinline__ void gram_dma16(gram_i32x4 rsrc, uint32_t lds_byte_ad
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen nt lds"
                      :
                      : "s"(lds_byte_addr), "v"(voff), "s"(rsrc), "s"(soff)
-                     : "memory");
+                     : "memory", "m0");
     else
         asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                      :
                      : "s"(lds_byte_addr), "v"(voff), "s"(rsrc), "s"(soff)
-                     : "memory");
+                     : "memory", "m0");
 }
 
 __device__ __forceinline__ gram_i32x4 gram_rsrc(const void* base, uint32_t bytes) {
@@ -763,17 +763,10 @@ static bool gram_dma_ok(int T, int d_in, int d_out) {
 static dp_status gram_dma_launch(dp_ctx* ctx, const GramBatch& gb, int T, int d_in, int d_out, int has_bias, float* out,
                                  double bytes) {
     dp_prof_scope prof(ctx, DP_PROF_GRAM, bytes);
-    static int variant = -1;
-    if (variant < 0) {  // DPCLIP_GRAM_VARIANT: tuning aid
-        const char* e = getenv("DPCLIP_GRAM_VARIANT");
-        variant = e ? atoi(e) : 1;
-    }
     const dim3 grid((unsigned)((long)gb.n_layers * gb.B)), block(256);
-    const bool wide = d_in % 128 == 0 && d_out % 128 == 0;
-    if (variant == 1 && wide)
+    // 256-byte row segments (two stages of 32 KiB) when the widths allow, else 128-byte segments (four stages of 16 KiB)
+    if (d_in % 128 == 0 && d_out % 128 == 0)
         hipLaunchKernelGGL((gram_dma_kernel<128, 2, 2>), grid, block, 0, ctx->stream, gb, T, d_in, d_out, has_bias, out);
-    else if (variant == 2 && wide)
-        hipLaunchKernelGGL((gram_dma_kernel<128, 3, 1>), grid, block, 0, ctx->stream, gb, T, d_in, d_out, has_bias, out);
     else
         hipLaunchKernelGGL((gram_dma_kernel<64, 4, 2>), grid, block, 0, ctx->stream, gb, T, d_in, d_out, has_bias, out);
     DP_LAUNCH_CHECK(ctx, "gram_dma");
@@ -812,18 +805,9 @@ static dp_status gram_pairs_launch(dp_ctx* ctx, const GramBatch& gb, int T, int 
     return dpk_finish_partials(ctx, part, gb.B, (int)(npairs * gb.n_layers), sqnorms);
 }
 
-static bool gram_pairs_enabled() {
-    static int on = -1;
-    if (on < 0) {  // DPCLIP_GRAM_PAIRS=0: the register-staged kernel for T > 128 (tuning aid)
-        const char* e = getenv("DPCLIP_GRAM_PAIRS");
-        on = (e && e[0] == '0') ? 0 : 1;
-    }
-    return on != 0;
-}
-
 dp_status dpk_gram_sqnorms_batched(dp_ctx* ctx, int n_layers, const void* const* A, const void* const* G, dp_dtype dt,
                                    int B, int T, int d_in, int d_out, int has_bias, float* sqnorms) {
-    if (dt == DP_BF16 && gram_pairs_ok(T, d_in, d_out) && gram_pairs_enabled()) {
+    if (dt == DP_BF16 && gram_pairs_ok(T, d_in, d_out)) {
         // enough layers per launch for a few rounds of workgroups, and partials that fit the workspace
         const int nblk = (T + GB - 1) / GB;
         const long npairs = (long)nblk * (nblk + 1) / 2;
@@ -964,7 +948,7 @@ dp_status dpk_gram_sqnorms(dp_ctx* ctx, const void* A, const void* G, dp_dtype d
         lds_attr_set = true;
     }
     const double bytes = 2.0 * (double)B * T * ((double)d_in + d_out);
-    if (gram_dma_ok(T, d_in, d_out) || (gram_pairs_ok(T, d_in, d_out) && gram_pairs_enabled())) {
+    if (gram_dma_ok(T, d_in, d_out) || (gram_pairs_ok(T, d_in, d_out))) {
         GramBatch gb;
         for (int l = 0; l < GRAM_MAX_BATCH; ++l) {
             gb.A[l] = (const uint16_t*)A;

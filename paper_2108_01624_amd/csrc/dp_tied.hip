@@ -127,13 +127,8 @@ __global__ __launch_bounds__(256) void scale_rows_bf16_kernel(const uint16_t* __
 // the B*M rows are then contracted as B*M/64 blocks of 64 rows with factor 1 by the fast kernel.
 dp_status dpk_tied_projection_sums(dp_ctx* ctx, const void* H, const void* dL, dp_dtype dt, int B, int M, int d, int V,
                                    const float* sqnorms, float C, float* sum_E) {
-    static int flat = -1;
-    if (flat < 0) {  // DPCLIP_TIED_FLAT=0: always the general GEMM (tuning aid)
-        const char* e = getenv("DPCLIP_TIED_FLAT");
-        flat = (e && e[0] == '0') ? 0 : 1;
-    }
     const long rows = (long)B * M;
-    if (flat && dt == DP_BF16 && rows % 64 == 0 && M % 64 != 0 && V >= 256 && d >= 256 && rows / 64 <= ctx->cbuf_cap) {
+    if (dt == DP_BF16 && rows % 64 == 0 && M % 64 != 0 && V >= 256 && d >= 256 && rows / 64 <= ctx->cbuf_cap) {
         dp_ws_alloc ws(ctx);
         uint16_t* Hs = ws.get<uint16_t>((size_t)rows * d);
         float* zero = ws.get<float>((size_t)(rows / 64));

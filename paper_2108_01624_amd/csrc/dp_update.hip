@@ -78,7 +78,7 @@ __device__ __forceinline__ void adam_elem(float& th, float& m, float& v, float s
     th = th - a.lr * (mh / (sqrtf(vh) + a.eps) + a.wd * th);
 }
 
-// Gradient signal-to-noise terms (Section 5.2): with SNR the kernels also form the squares of the sum and of
+// Gradient signal-to-noise terms (Section 5.2.1): with SNR the kernels also form the squares of the sum and of
 // the noise sigma*C*z they read / draw anyway, reduce them over the workgroup in a fixed order and store one
 // pair per workgroup at snr_part[2 * (part0 + blockIdx.x)]; snr_finish_kernel adds the pairs in index order.
 template <bool SNR>
@@ -253,9 +253,13 @@ __global__ __launch_bounds__(256) void finish_partials_kernel(const float* __res
 }
 
 __global__ __launch_bounds__(256) void clip_factors_kernel(const float* __restrict__ sqnorms, int B, float C,
-                                                           float* __restrict__ c) {
+                                                           float* __restrict__ c, int* __restrict__ err) {
     const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i < B) c[i] = dp_clip_factor(sqnorms[i], C);
+    if (i < B) {
+        const float ci = dp_clip_factor(sqnorms[i], C);
+        c[i] = ci;
+        if (ci != ci) atomicOr(err, DP_ERRBIT_NORM);
+    }
 }
 
 template <bool NOISE, bool ZERO, bool SNR>
@@ -375,7 +379,8 @@ dp_status dpk_finish_partials(dp_ctx* ctx, const float* partial, int B, int J, f
 }
 
 dp_status dpk_clip_factors(dp_ctx* ctx, const float* sqnorms, int B, float C, float* c) {
-    hipLaunchKernelGGL(clip_factors_kernel, dim3((B + 255) / 256), dim3(256), 0, ctx->stream, sqnorms, B, C, c);
+    hipLaunchKernelGGL(clip_factors_kernel, dim3((B + 255) / 256), dim3(256), 0, ctx->stream, sqnorms, B, C, c,
+                       ctx->err_word);
     DP_LAUNCH_CHECK(ctx, "clip_factors");
     return DP_OK;
 }

@@ -14,8 +14,8 @@
 // in the same banks.  The 16-byte chunk index is therefore XOR-ed with 4*(row % 4) when a chunk is stored,
 // which spreads the four rows of a group, and the two groups of a half-wave, over 256 distinct bytes.
 //
-// Pipeline per workgroup (4 waves as 2 x 2, one wave per SIMD because the 256 x 256 fp32 tile takes all
-// 256 accumulator registers of a lane): global -> registers up to four stages ahead (buffer loads: rows
+// Pipeline per workgroup of the register-staged kernel (8 waves as 2 x 4 on a 256 x 256 tile, or 4 waves as 2 x 2 on
+// 128 x 128): global -> registers up to four stages ahead (buffer loads: rows
 // past the split's range read as zero, so there is no branch around a load), registers -> LDS ring of
 // three stages, LDS -> fragments one 16-row step ahead of the MFMAs, also across the one barrier per stage.
 //
@@ -53,6 +53,7 @@ struct WgemmArgs {
                          // (unit, tile) sequence cut into 8 equal runs
     int rect_m, rect_n;  // mode 2: the tile grid is cut into rect_m x rect_n rectangles, 8 / nsplit per split;
                          // modes 1 and 3: a unit's tiles are walked in rectangles of this size
+    int* err;            // device error word: DP_ERRBIT_NORM is set when a clip factor is NaN (non-finite squared norm)
 };
 
 // Several layers of one shape in one launch (direct-to-LDS kernel): the unit of work distribution is the pair
@@ -98,7 +99,7 @@ __device__ __forceinline__ bf16x8_t read_frag(const uint16_t* lds_lane_ptr, int 
     return __builtin_bit_cast(bf16x8_t, v);
 }
 
-// Workgroup = 4 waves as 2 x 2; wave tile (32*MI) x (32*NI); block tile BM x BN = (64*MI) x (64*NI).
+// Workgroup = WVM x WVN waves; wave tile (32*MI) x (32*NI); block tile BM x BN = (32*MI*WVM) x (32*NI*WVN).
 // SCALE: multiply G rows by c.  UNIFORM_C: T % BK == 0, so all rows of a stage belong to one example.
 template <int MI, int NI, int WVM, int WVN, int EPI, bool SCALE, bool UNIFORM_C>
 __global__ __launch_bounds__(64 * WVM * WVN) void wgemm_bf16_kernel(WgemmArgs a) {
@@ -207,6 +208,7 @@ __global__ __launch_bounds__(64 * WVM * WVN) void wgemm_bf16_kernel(WgemmArgs a)
             if constexpr (UNIFORM_C) {
                 const long k = k_lo + (long)st * BK;
                 const float s = dp_clip_factor(a.sqnorms[(uint32_t)(k < a.K ? k : a.K - 1) / (uint32_t)a.T], a.C);
+                if (s != s && tid == 0) atomicOr(a.err, DP_ERRBIT_NORM);
 #pragma unroll
                 for (int j = 0; j < SG; ++j) cs[set][j] = s;
             } else {
@@ -215,6 +217,7 @@ __global__ __launch_bounds__(64 * WVM * WVN) void wgemm_bf16_kernel(WgemmArgs a)
                     long k = k_lo + (long)st * BK + rowG[j];
                     if (k >= a.K) k = a.K - 1;
                     cs[set][j] = dp_clip_factor(a.sqnorms[(uint32_t)k / (uint32_t)a.T], a.C);
+                    if (cs[set][j] != cs[set][j]) atomicOr(a.err, DP_ERRBIT_NORM);
                 }
             }
         }
@@ -294,31 +297,6 @@ __global__ __launch_bounds__(64 * WVM * WVN) void wgemm_bf16_kernel(WgemmArgs a)
         gload(SET, s + 4);
         load_frags(buf1, 0, fa0, fg0);
         mma(fa1, fg1);
-        if constexpr (MI == 4 && NI == 4 && NT == 256) {
-            // Interleave: the wave is alone on its SIMD, so every run of non-MFMA instructions longer than
-            // one MFMA's 32 cycles leaves the matrix pipe idle.  First 16 MFMAs: one fragment read and the
-            // scaling arithmetic between them; last 16: LDS stores, global loads and the next fragment reads.
-#pragma unroll
-            for (int g = 0; g < 16; ++g) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
-                __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);  // VALU
-            }
-#pragma unroll
-            for (int g = 0; g < 8; ++g) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // DS write
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // VMEM read
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
-            }
-#pragma unroll
-            for (int g = 0; g < 8; ++g) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
-            }
-        }
         __syncthreads();
         // nothing of the next iteration may move above this point: its register set is still in flight
         __builtin_amdgcn_sched_barrier(0);
@@ -417,7 +395,7 @@ __device__ __forceinline__ void dma_load16(i32x4_t rsrc, uint32_t lds_byte_addr,
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                  :
                  : "s"(lds_byte_addr), "v"(voff), "s"(rsrc), "s"(soff)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 __device__ __forceinline__ i32x4_t make_rsrc(const void* base, uint32_t bytes) {
@@ -430,306 +408,13 @@ __device__ __forceinline__ i32x4_t make_rsrc(const void* base, uint32_t bytes) {
     return r;
 }
 
-template <int EPI>
-__global__ __launch_bounds__(512) void wgemm_dma_kernel(WgemmBatchArgs b) {
-    constexpr int MI = 4, NI = 2, WVN = 4, NT = 512;
-    constexpr int WM = 128, WN = 64, BM = 256, BN = 256;
-    constexpr int LPS = 4;  // LDS-filling loads per wave per stage (2 for A, 2 for G)
-    __shared__ __attribute__((aligned(16))) uint16_t As[DMA_NS][BK * BM];
-    __shared__ __attribute__((aligned(16))) uint16_t Gs[DMA_NS][BK * BN];
-    const WgemmArgs& a = b.base;
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: everything derived from it stays in SGPRs
-    const int wr = wave / WVN, wc = wave % WVN;
-    const int ntiles = a.tiles_m * a.tiles_n;
-    const int nunits = b.n_layers * a.nsplit;  // unit = layer * nsplit + split
-    // Workgroup ids are dealt to the 8 XCDs round-robin: an XCD gets whole units (mode 1) or one rectangle of
-    // one unit's tile grid (mode 2), so that its L2 sees each operand row and column about once.
-    int tile, unit;
-    if (a.xcd_map == 1) {
-        const int g = blockIdx.x, slot = g >> 3;
-        unit = (slot / ntiles) * 8 + (g & 7);
-        if (unit >= nunits) return;
-        // An XCD runs about 32 workgroups at a time: walk the unit's tile grid in rect_m x rect_n rectangles so
-        // that those 32 share as many operand columns as possible (rect 1 x 1 = plain row-major order).
-        const int t = slot % ntiles, per = a.rect_m * a.rect_n, rect = t / per, w = t % per;
-        const int rpr = a.tiles_n / a.rect_n;
-        tile = ((rect / rpr) * a.rect_m + w / a.rect_n) * a.tiles_n + (rect % rpr) * a.rect_n + w % a.rect_n;
-    } else if (a.xcd_map == 2) {
-        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-        const int nrect = a.rect_m * a.rect_n;
-        const int rect = xcd % nrect;
-        const int tm = a.tiles_m / a.rect_m, tn = a.tiles_n / a.rect_n;
-        unit = xcd / nrect;
-        tile = ((rect / a.rect_n) * tm + slot / tn) * a.tiles_n + (rect % a.rect_n) * tn + slot % tn;
-    } else {
-        // mode 3: the (unit, tile) pairs in unit-major order, cut into 8 equal runs, one per XCD: balanced for any
-        // unit and tile count; at most 7 units have their tiles on two XCDs
-        const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-        const int total = nunits * ntiles, per_xcd = (total + 7) >> 3;
-        const int w = xcd * per_xcd + slot;
-        if (slot >= per_xcd || w >= total) return;
-        unit = w / ntiles;
-        const int t = w - unit * ntiles, per = a.rect_m * a.rect_n, rect = t / per, r = t % per;
-        const int rpr = a.tiles_n / a.rect_n;
-        tile = ((rect / rpr) * a.rect_m + r / a.rect_n) * a.tiles_n + (rect % rpr) * a.rect_n + r % a.rect_n;
-    }
-    const int layer = unit / a.nsplit, split = unit % a.nsplit;
-    const uint16_t* Aptr = b.L[layer].A;
-    const uint16_t* Gptr = b.L[layer].G;
-    const int pm = tile / a.tiles_n, qn = tile % a.tiles_n;
-    const int p0 = pm * BM, q0 = qn * BN;
-    const long k_lo = (long)split * a.rows_per_split;
-    const long k_hi = k_lo + a.rows_per_split < a.K ? k_lo + a.rows_per_split : a.K;
-    const int nrows = k_hi > k_lo ? (int)(k_hi - k_lo) : 0;
-    const int nsteps = (nrows + BK - 1) / BK;
-
-    const i32x4_t rA = make_rsrc(Aptr + (size_t)k_lo * a.d_in, (uint32_t)((size_t)nrows * a.d_in * 2));
-    const i32x4_t rG = make_rsrc(Gptr + (size_t)k_lo * a.d_out, (uint32_t)((size_t)nrows * a.d_out * 2));
-
-    // Load j (0, 1) of this wave fills tile rows 4*wave + 2*j and + 1: lane l -> row + l/32, LDS chunk l%32,
-    // which holds global chunk (l%32) ^ 4*(row%4) (bank swizzle, see the file header).
-    int voffA[2], voffG[2];
-    uint32_t ldsA[2], ldsG[2];
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int row0 = 4 * wave + 2 * j, row = row0 + (lane >> 5);
-        const int cg = (lane & 31) ^ ((row & 3) << 2);
-        voffA[j] = (row * a.d_in + p0 + cg * 8) * 2;
-        voffG[j] = (row * a.d_out + q0 + cg * 8) * 2;
-        ldsA[j] = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)&As[0][row0 * BM];
-        ldsG[j] = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)&Gs[0][row0 * BN];
-    }
-    auto issue = [&](int st, int buf) {
-        // stages past the range load the last stage again (never multiplied): the stage offset is not part of the
-        // buffer bounds check, so it must not run past the rows
-        const int stc = st < nsteps ? st : (nsteps > 0 ? nsteps - 1 : 0);
-        const int soffA = __builtin_amdgcn_readfirstlane(stc * BK * a.d_in * 2);
-        const int soffG = __builtin_amdgcn_readfirstlane(stc * BK * a.d_out * 2);
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            dma_load16(rA, __builtin_amdgcn_readfirstlane(ldsA[j] + buf * (BK * BM * 2)), voffA[j], soffA);
-            dma_load16(rG, __builtin_amdgcn_readfirstlane(ldsG[j] + buf * (BK * BN * 2)), voffG[j], soffG);
-        }
-    };
-    const int frow = 8 * (lane >> 5) + ((lane & 15) >> 2);
-    const int fsw = frow & 3;
-    int foffA[MI], foffG[NI];
-#pragma unroll
-    for (int i = 0; i < MI; ++i) {
-        const int col = wr * WM + 32 * i + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-        foffA[i] = frow * BM + (((col >> 3) ^ (fsw << 2)) << 3) + (col & 7);
-    }
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-        const int col = wc * WN + 32 * i + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-        foffG[i] = frow * BN + (((col >> 3) ^ (fsw << 2)) << 3) + (col & 7);
-    }
-    auto load_frags = [&](int buf, int kk, bf16x8_t* fa, bf16x8_t* fg) {
-#pragma unroll
-        for (int i = 0; i < MI; ++i) fa[i] = read_frag(&As[buf][kk * 16 * BM + foffA[i]], BM);
-#pragma unroll
-        for (int i = 0; i < NI; ++i) fg[i] = read_frag(&Gs[buf][kk * 16 * BN + foffG[i]], BN);
-    };
-
-    f32x16_t acc[MI][NI], bacc[NI];
-#pragma unroll
-    for (int j = 0; j < NI; ++j) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) bacc[j][r] = 0.f;
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    }
-    auto mma = [&](const bf16x8_t* fa, const bf16x8_t* fg) {
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-            for (int j = 0; j < NI; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fg[j], acc[i][j], 0, 0, 0);
-    };
-    const bool want_bias = b.L[layer].sum_b != nullptr;
-    const int duty_mod = 2 * a.tiles_m, duty = 2 * pm + wr;
-    const uint32_t one2 = 0x3F803F80u;  // two bf16 ones
-    const bf16x8_t ones = __builtin_bit_cast(bf16x8_t, u32x4_t{one2, one2, one2, one2});
-    auto mma_bias = [&](const bf16x8_t* fg) {
-#pragma unroll
-        for (int j = 0; j < NI; ++j) bacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, fg[j], bacc[j], 0, 0, 0);
-    };
-    bf16x8_t fa0[MI], fg0[NI], fa1[MI], fg1[NI];
-    float c_cur = 1.f;  // clip factor of the example being accumulated (set by the example's first stage)
-
-    // prologue: DMA_NS - 1 stages in flight; publish stage 0
-    constexpr int AHEAD = DMA_NS - 1;  // the newest stage in flight is AHEAD stages past the one being multiplied
-#pragma unroll
-    for (int st = 0; st < AHEAD; ++st) issue(st, st);
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((AHEAD - 1) * LPS) : "memory");  // stage 0 has landed
-    __syncthreads();
-    int buf = 0;      // ring slot of the stage being multiplied
-    int ibuf = AHEAD; // ring slot the next load fills
-    load_frags(buf, 0, fa0, fg0);
-
-    // One loop iteration = one stage = one barrier.
-    int my = 0;      // the stage being multiplied; stages >= nsteps hold zeros
-    int duty_ctr = 0;  // my % duty_mod
-    const int spe = a.T / BK;                                  // stages per example (>= 2)
-    int ex_run = (int)((uint32_t)k_lo / (uint32_t)a.T);        // the next example to start (row splits begin on examples)
-    const int nex = (int)(a.K / a.T);
-    // lane l: clip factor c_e of example e = (ex & ~63) + l and the rescaling ratio c_{e-1} / c_e that applies when
-    // example e starts.  Two plain loads per 64 examples; the compiler's wait for them also waits for the
-    // LDS-filling loads in flight, a bubble once per 256 or more stages.
-    float cvec = 1.f, rvec = 1.f;
-    auto load_factors = [&](int ex) {
-        const int e = (ex & ~63) + lane;
-        const float n_e = e < nex ? a.sqnorms[e] : 1.f;
-        const float n_p = (e >= 1 && e - 1 < nex) ? a.sqnorms[e - 1] : n_e;
-        cvec = dp_clip_factor(n_e, a.C);
-        rvec = dp_clip_factor(n_p, a.C) / cvec;
-    };
-    if (nsteps > 0) load_factors(ex_run);
-    int s_issue = AHEAD;
-    // Rescaling at an example boundary is spread over the two half-iterations around it, so that the 128 multiplies
-    // hide behind 16 MFMAs instead of 8: in the second half of the example's last stage (PRE) a tile is multiplied two
-    // MFMAs after its last MFMA of that example went out (tiles 0..5), the remaining tiles (6, 7) directly before their
-    // first MFMA of the next example (POST).  Every stage kind is a straight-line body of its own (a two-armed branch
-    // around the MFMAs costs the register allocator > 100 spilled VGPRs).
-    constexpr int PLAIN = 0, POST = 1, PRE = 2;
-    float ratio = 1.f;  // c_prev / c_next of the boundary being worked on (set in PRE, used up in POST)
-    auto scale_tile = [&](int t) {
-        const int i = t / NI, j = t % NI;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][j][r] *= ratio;
-    };
-    auto body = [&](auto kind_tag) {
-        constexpr int KIND = decltype(kind_tag)::value;
-        const int buf1 = buf + 1 == DMA_NS ? 0 : buf + 1;
-        const bool bias_now = want_bias && duty_ctr == duty;
-        duty_ctr = duty_ctr + 1 == duty_mod ? 0 : duty_ctr + 1;
-        load_frags(buf, 1, fa1, fg1);
-        // of the two waves that share a SIMD, the one inside an MFMA run goes first (+1 to 3 % measured)
-        __builtin_amdgcn_s_setprio(1);
-        if (KIND == POST) {
-            // first stage of example ex_run: finish the rescaling PRE began, take over the example's factor
-            const int el = __builtin_amdgcn_readfirstlane(ex_run & 63);
-            c_cur = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cvec), el));
-            ++ex_run;
-#pragma unroll
-            for (int t = 0; t < MI * NI; ++t) {
-                const int i = t / NI, j = t % NI;
-                if (t >= MI * NI - 2) {
-                    __builtin_amdgcn_sched_barrier(0);
-                    scale_tile(t);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[i], fg0[j], acc[i][j], 0, 0, 0);
-            }
-#pragma unroll
-            for (int j = 0; j < NI; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) bacc[j][r] *= ratio;
-        } else {
-            mma(fa0, fg0);
-        }
-        if (bias_now) mma_bias(fg0);
-        __builtin_amdgcn_s_setprio(0);
-        // my loads of the next stage have landed (later stages may still be in flight); after the barrier every
-        // wave's have, and every wave has finished reading the stage whose ring slot the newest stage now overwrites
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((AHEAD - 2) * LPS) : "memory");
-        __syncthreads();
-        load_frags(buf1, 0, fa0, fg0);
-        if (KIND == PRE) {
-            // last stage of example ex_run - 1; the factors of 64 examples sit in registers (lane = example mod 64)
-            if ((ex_run & 63) == 0) load_factors(ex_run);
-            const int el = __builtin_amdgcn_readfirstlane(ex_run & 63);
-            ratio = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, rvec), el));
-        }
-        // The four LDS-filling loads of the newest stage go out one after every second MFMA: issued back to back
-        // right after the barrier by all eight waves they queue up in the address unit, and a wave that waits there
-        // issues no MFMA either.
-        {
-            __builtin_amdgcn_s_setprio(1);
-            const int stc = s_issue < nsteps ? s_issue : (nsteps > 0 ? nsteps - 1 : 0);
-            const int soffA = __builtin_amdgcn_readfirstlane(stc * BK * a.d_in * 2);
-            const int soffG = __builtin_amdgcn_readfirstlane(stc * BK * a.d_out * 2);
-#pragma unroll
-            for (int t = 0; t < MI * NI; ++t) {
-                const int i = t / NI, j = t % NI;
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[i], fg1[j], acc[i][j], 0, 0, 0);
-                if (t % 2 == 1) {
-                    const int k = t / 2, jj = k >> 1;
-                    __builtin_amdgcn_sched_barrier(0);
-                    if ((k & 1) == 0)
-                        dma_load16(rA, __builtin_amdgcn_readfirstlane(ldsA[jj] + ibuf * (BK * BM * 2)), voffA[jj], soffA);
-                    else
-                        dma_load16(rG, __builtin_amdgcn_readfirstlane(ldsG[jj] + ibuf * (BK * BN * 2)), voffG[jj], soffG);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                if (KIND == PRE && t >= 2) {
-                    __builtin_amdgcn_sched_barrier(0);
-                    scale_tile(t - 2);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-        }
-        __builtin_amdgcn_s_setprio(0);
-        ++s_issue;
-        ibuf = ibuf + 1 == DMA_NS ? 0 : ibuf + 1;
-        if (bias_now) mma_bias(fg1);
-        buf = buf1;
-        ++my;
-    };
-    // The unit's rows are whole examples (the host aligns row splits to examples), at least two stages each.
-    const int n_ex_unit = nsteps / spe;
-    for (int e = 0; e + 1 < n_ex_unit; ++e) {
-        body(std::integral_constant<int, POST>{});
-        for (int q = 0; q < spe - 2; ++q) body(std::integral_constant<int, PLAIN>{});
-        body(std::integral_constant<int, PRE>{});
-    }
-    if (n_ex_unit > 0) {
-        body(std::integral_constant<int, POST>{});
-        for (int q = 0; q < spe - 1; ++q) body(std::integral_constant<int, PLAIN>{});
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing may still be writing LDS when the workgroup ends
-
-    // MFMA tile (i, j): accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
-    float* base = b.L[layer].out + (EPI == EPI_STORE ? (size_t)split * a.d_in * a.d_out : (size_t)0);
-#pragma unroll
-    for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int p = p0 + wr * WM + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-            if (p < a.d_in) {
-#pragma unroll
-                for (int j = 0; j < NI; ++j) {
-                    const int q = q0 + wc * WN + 32 * j + (lane & 31);
-                    if (q < a.d_out) {
-                        float* dst = base + (size_t)p * a.d_out + q;
-                        if (EPI == EPI_ADD) *dst += acc[i][j][r] * c_cur;
-                        else *dst = acc[i][j][r] * c_cur;
-                    }
-                }
-            }
-        }
-    if (want_bias && lane < 32) {
-        // every row of the ones-product equals the column sums; row 0 sits in register 0 of lanes 0..31
-        float* bp = a.bias_part + ((size_t)(unit * a.tiles_m + pm) * 2 + wr) * a.d_out;
-#pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            const int q = q0 + wc * WN + 32 * j + lane;
-            if (q < a.d_out) bp[q] = bacc[j][0] * c_cur;
-        }
-    }
-}
-
-// The same kernel on the 16x16x32 MFMA.  Per flop it moves as many fragment bytes through LDS, but the matrix pipe draws
-// less power: a loop of nothing but MFMAs on random operands sustains 2.1 PFLOP/s with this shape against 1.4 with
-// 32x32x16 (the chip holds 2.07 against 1.7 GHz; on zeros 2.47 against 1.63 PFLOP/s), and this kernel lives under the
-// power limit.  Wave tile 128 x 64 = 8 x 4 tiles of 16 x 16; a stage (32 rows) is one MFMA step per tile, worked on in
-// two halves of 16 MFMAs (tile rows 0..3, then 4..7) so that the fragments of the next half arrive while this one
-// multiplies: 12 fragments in flight in 48 registers, as before.  Rows r and r + 8 of a stage are read by lanes of the
-// same pass now, so the chunk swizzle also takes bit 3 of the row.
+// The kernel uses the 16x16x32 MFMA.  Per flop it moves as many fragment bytes through LDS as 32x32x16 would, but the
+// matrix pipe draws less power: a loop of nothing but MFMAs on random operands sustains 2.1 PFLOP/s with this shape
+// against 1.4 with 32x32x16 (the chip holds 2.07 against 1.7 GHz; on zeros 2.47 against 1.63 PFLOP/s), and this kernel
+// lives under the power limit.  Wave tile 128 x 64 = 8 x 4 tiles of 16 x 16; a stage (32 rows) is one MFMA step per tile,
+// worked on in two halves of 16 MFMAs (tile rows 0..3, then 4..7) so that the fragments of the next half arrive while
+// this one multiplies: 12 fragments in flight in 48 registers.  Rows r and r + 8 of a stage are read by lanes of the
+// same pass, so the chunk swizzle also takes bit 3 of the row.
 __device__ __forceinline__ int swz16(int row) { return ((row & 3) << 2) | (((row >> 3) & 1) << 1); }
 
 template <int EPI>
@@ -886,6 +571,7 @@ __global__ __launch_bounds__(512) void wgemm_dma16_kernel(WgemmBatchArgs b) {
         const float n_p = (e >= 1 && e - 1 < nex) ? a.sqnorms[e - 1] : n_e;
         cvec = dp_clip_factor(n_e, a.C);
         rvec = dp_clip_factor(n_p, a.C) / cvec;
+        if (cvec != cvec) atomicOr(a.err, DP_ERRBIT_NORM);  // NaN factor: this unit's sums become NaN as well
     };
     if (nsteps > 0) load_factors(ex_run);
     int s_issue = AHEAD;
@@ -1022,6 +708,43 @@ __global__ __launch_bounds__(512) void wgemm_dma16_kernel(WgemmBatchArgs b) {
     }
 }
 
+// Calibration: the clip-weighted GEMM's matrix work with nothing around it - 32 accumulator tiles of 16 x 16 per wave
+// (128 registers), 8 + 4 operand fragments that stay in registers, 32 MFMAs per iteration, 8 waves per workgroup (two
+// per SIMD), one workgroup per CU.  Operands are pseudo-random bf16 values in +-[1, 2) (the rate the chip sustains
+// depends on the data: on zeros it holds a higher clock).  What this loop sustains is the ceiling of any kernel that
+// executes these MFMAs on this card under its power limit.
+__global__ __launch_bounds__(512) void mfma_ceiling_kernel(int iters, float* __restrict__ sink) {
+    constexpr int MI = 8, NI = 4;
+    const uint32_t t = blockIdx.x * 512u + threadIdx.x;
+    auto rnd = [&](uint32_t k) {  // two bf16 values with random sign and mantissa, exponent 0
+        uint32_t h = (t * 0x9E3779B1u) ^ (k * 0x85EBCA77u);
+        h ^= h >> 15; h *= 0x2C1B3C6Du; h ^= h >> 12; h *= 0x297A2D39u; h ^= h >> 15;
+        return (h & 0x807F807Fu) | 0x3F803F80u;
+    };
+    bf16x8_t fa[MI], fg[NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i) fa[i] = __builtin_bit_cast(bf16x8_t, u32x4_t{rnd(8 * i), rnd(8 * i + 1), rnd(8 * i + 2), rnd(8 * i + 3)});
+#pragma unroll
+    for (int j = 0; j < NI; ++j) fg[j] = __builtin_bit_cast(bf16x8_t, u32x4_t{rnd(100 + 8 * j), rnd(101 + 8 * j), rnd(102 + 8 * j), rnd(103 + 8 * j)});
+    f32x4_t acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fg[j], acc[i][j], 0, 0, 0);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j) s += (acc[i][j][0] + acc[i][j][1]) + (acc[i][j][2] + acc[i][j][3]);
+    sink[t] = s;
+}
+
 // sum_b[layer][q] += sum over the layer's nb partial rows, in row order (fixed order).  grid (n_layers, d_out/256).
 __global__ __launch_bounds__(256) void bias_finish_kernel(WgemmBatchArgs b, int nb) {
     const int layer = blockIdx.x;
@@ -1087,17 +810,13 @@ void wgemm_launch(dp_ctx* ctx, const WgemmArgs& a, unsigned grid) {
                        dim3(64 * WVM * WVN), 0, ctx->stream, a);
 }
 
-// Tile configurations: 0 = 128 x 128 (4 waves of 64 x 64), 1 = 256 x 256 with 4 waves of 128 x 128 (one wave per
-// SIMD), 2 = 256 x 256 with 8 waves of 128 x 64 (two waves per SIMD, which lets one wave's MFMAs run under the
-// other's loads, conversions and waits).
+// Tile configurations: 0 = 128 x 128 (4 waves of 64 x 64), 2 = 256 x 256 with 8 waves of 128 x 64 (two waves per
+// SIMD, which lets one wave's MFMAs run under the other's loads, conversions and waits).
 template <int EPI, bool SCALE>
 void wgemm_dispatch(dp_ctx* ctx, const WgemmArgs& a, unsigned grid, int cfg, bool uniform) {
     if (cfg == 2) {
         if (uniform) wgemm_launch<4, 2, 2, 4, EPI, SCALE, true>(ctx, a, grid);
         else wgemm_launch<4, 2, 2, 4, EPI, SCALE, false>(ctx, a, grid);
-    } else if (cfg == 1) {
-        if (uniform) wgemm_launch<4, 4, 2, 2, EPI, SCALE, true>(ctx, a, grid);
-        else wgemm_launch<4, 4, 2, 2, EPI, SCALE, false>(ctx, a, grid);
     } else {
         if (uniform) wgemm_launch<2, 2, 2, 2, EPI, SCALE, true>(ctx, a, grid);
         else wgemm_launch<2, 2, 2, 2, EPI, SCALE, false>(ctx, a, grid);
@@ -1109,32 +828,8 @@ void wgemm_dispatch(dp_ctx* ctx, const WgemmArgs& a, unsigned grid, int cfg, boo
 // Tile shape: 256 x 256 when both dimensions are at least that large, otherwise 128 x 128.
 static inline bool big_tile(int d_in, int d_out) { return d_in >= 256 && d_out >= 256; }
 // The direct-to-LDS kernel serves the 256 x 256 tile when all rows of a stage share one example.
-static inline bool use_dma_path(int cfg, bool uniform) {
-    static int on = -1;
-    if (on < 0) {  // DPCLIP_GEMM_DMA=0 falls back to the register-staged kernel (tuning aid)
-        const char* e = getenv("DPCLIP_GEMM_DMA");
-        on = (e && e[0] == '0') ? 0 : 1;
-    }
-    return on && cfg != 0 && uniform;
-}
-static inline int tile_cfg(int d_in, int d_out) {
-    static int big_cfg = -1;
-    if (big_cfg < 0) {  // DPCLIP_GEMM_WAVES=4 selects the one-wave-per-SIMD variant (tuning aid)
-        const char* e = getenv("DPCLIP_GEMM_WAVES");
-        big_cfg = (e && e[0] == '4') ? 1 : 2;
-    }
-    return big_tile(d_in, d_out) ? big_cfg : 0;
-}
-
-// MFMA shape of the direct-to-LDS kernel: 16 (16x16x32, the default) or 32 (32x32x16; DPCLIP_GEMM_MFMA=32, tuning aid).
-static inline int dma_mfma_shape() {
-    static int shape = -1;
-    if (shape < 0) {
-        const char* e = getenv("DPCLIP_GEMM_MFMA");
-        shape = (e && e[0] == '3') ? 32 : 16;
-    }
-    return shape;
-}
+static inline bool use_dma_path(int cfg, bool uniform) { return cfg != 0 && uniform; }
+static inline int tile_cfg(int d_in, int d_out) { return big_tile(d_in, d_out) ? 2 : 0; }
 
 // A split's rows of one operand must stay below 2^31 bytes (32-bit buffer offsets).
 static inline bool range_ok(long rows, int d_in, int d_out) {
@@ -1232,6 +927,7 @@ dp_status dpk_weighted_gemm_batched(dp_ctx* ctx, int n, const void* const* A, co
         a.out = nullptr;
         a.sqnorms = sqnorms;
         a.C = C;
+        a.err = ctx->err_word;
         a.T = T;
         a.d_in = d_in;
         a.d_out = d_out;
@@ -1324,13 +1020,8 @@ dp_status dpk_weighted_gemm_batched(dp_ctx* ctx, int n, const void* const* A, co
         {
             dp_prof_scope prof(ctx, DP_PROF_WGEMM, 2.0 * (double)K * d_in * d_out * nl);
             const dim3 grid((unsigned)nwg), block(512);
-            if (dma_mfma_shape() == 16) {
-                if (nsplit == 1) hipLaunchKernelGGL((wgemm_dma16_kernel<EPI_ADD>), grid, block, 0, ctx->stream, b);
-                else hipLaunchKernelGGL((wgemm_dma16_kernel<EPI_STORE>), grid, block, 0, ctx->stream, b);
-            } else {
-                if (nsplit == 1) hipLaunchKernelGGL((wgemm_dma_kernel<EPI_ADD>), grid, block, 0, ctx->stream, b);
-                else hipLaunchKernelGGL((wgemm_dma_kernel<EPI_STORE>), grid, block, 0, ctx->stream, b);
-            }
+            if (nsplit == 1) hipLaunchKernelGGL((wgemm_dma16_kernel<EPI_ADD>), grid, block, 0, ctx->stream, b);
+            else hipLaunchKernelGGL((wgemm_dma16_kernel<EPI_STORE>), grid, block, 0, ctx->stream, b);
         }
         DP_LAUNCH_CHECK(ctx, "wgemm_dma");
         if (nsplit > 1) {
@@ -1349,6 +1040,42 @@ dp_status dpk_weighted_gemm_batched(dp_ctx* ctx, int n, const void* const* A, co
             DP_LAUNCH_CHECK(ctx, "bias_finish");
         }
     }
+    return DP_OK;
+}
+
+dp_status dpk_mfma_ceiling(dp_ctx* ctx, int iters, int launches, double* tflops) {
+    int cus = 0;
+    DP_HIP_CHECK(ctx, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ctx->device));
+    if (cus <= 0) cus = 256;
+    dp_ws_alloc ws(ctx);
+    float* sink = ws.get<float>((size_t)cus * 512);
+    if (!sink) {
+        DP_SET_ERR(ctx, "workspace too small for the calibration kernel");
+        return DP_ERR_WORKSPACE;
+    }
+    hipEvent_t e0, e1;
+    DP_HIP_CHECK(ctx, hipEventCreate(&e0));
+    if (hipEventCreate(&e1) != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        DP_SET_ERR(ctx, "hipEventCreate failed");
+        return DP_ERR_HIP;
+    }
+    hipLaunchKernelGGL(mfma_ceiling_kernel, dim3(cus), dim3(512), 0, ctx->stream, iters, sink);  // warm-up
+    hipError_t e = hipEventRecord(e0, ctx->stream);
+    for (int l = 0; l < launches; ++l) hipLaunchKernelGGL(mfma_ceiling_kernel, dim3(cus), dim3(512), 0, ctx->stream, iters, sink);
+    if (e == hipSuccess) e = hipGetLastError();
+    if (e == hipSuccess) e = hipEventRecord(e1, ctx->stream);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (e != hipSuccess) {
+        DP_SET_ERR(ctx, "mfma calibration failed: %s", hipGetErrorString(e));
+        return DP_ERR_HIP;
+    }
+    const double flops = (double)launches * cus * 8.0 * (double)iters * 32.0 * (2.0 * 16 * 16 * 32);
+    *tflops = ms > 0.f ? flops / (ms * 1e-3) / 1e12 : 0.0;
     return DP_OK;
 }
 
@@ -1382,6 +1109,7 @@ dp_status dpk_weighted_gemm(dp_ctx* ctx, const void* A, const void* G, dp_dtype 
     a.G = (const uint16_t*)G;
     a.sqnorms = sqnorms;
     a.C = C;
+    a.err = ctx->err_word;
     a.T = T;
     a.d_in = d_in;
     a.d_out = d_out;
@@ -1486,6 +1214,7 @@ dp_status dpk_materialise_sqnorms(dp_ctx* ctx, const void* A, const void* G, dp_
         a.G = (const uint16_t*)G;
         a.sqnorms = nullptr;
         a.C = 1.f;
+        a.err = ctx->err_word;
         a.bias_part = nullptr;
         a.T = T;
         a.d_in = d_in;

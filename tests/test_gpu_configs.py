@@ -4,9 +4,11 @@ C ABI, in the launch configuration bench.py times.
 Coverage contract (what the oracle computed is what is claimed):
   C1  every element: norms (both paths), clip factors, sums, update with sigma = 0 and with sigma = 1, seed 0.
   C2, C3, C5  full-size micro-batch on the GPU; the oracle computes (a) the global norms of a sample of examples
-      over the full manifest, (b) sampled entries of the clip-weighted sums of the full micro-batch, with seeded
-      stand-in norms fed to both sides, (c) every tensor for a leading subset of B' examples (GPU re-run at B');
-      embedding rows written are checked exactly at full size.
+      over the full manifest, (b) sampled entries of the clip-weighted sums of the full micro-batch (dense weights and
+      biases, the first and last LayerNorm through both of its pass-2 paths, token-table entries of the most frequent
+      ids, of ids that occur once and of random ids, position-table entries), with seeded stand-in norms fed to both
+      sides, (c) every tensor for a leading subset of B' examples (GPU re-run at B'); embedding rows written are
+      checked exactly at full size.
   C4  update over all ~334M parameters against the oracle on sampled slices (Philox words bit-exact on the same
       slices), gradient-SNR terms of all parameters against a chi-square bound / a library sum and, on the one-block
       manifest, against the oracle over every parameter; accumulation over micro-batches on a one-block manifest against the oracle; a B = 1024 dense layer
@@ -78,6 +80,17 @@ def _subset_parity(cfg_name, Bsub, C=None):
     return worst
 
 
+def _embedding_entries(l, S_E, ids_h, vs, c_ref, V, rng, name):
+    """Entries (vs[j], ks[j]) of an embedding table's clip-weighted sum against the oracle's scatter over ALL examples,
+    restricted to the sampled columns ks."""
+    ks = rng.integers(0, S_E.shape[1], size=vs.size)
+    Gc = l["G"][:, :, torch.as_tensor(ks, device=DEV)].float().cpu().numpy()
+    ref = orc.clip_accumulate_embedding(ids_h, Gc, c_ref, V)[vs, np.arange(vs.size)]
+    got = S_E[vs, ks].astype(np.float64)
+    rms = np.sqrt(np.mean(ref ** 2))
+    assert np.all(np.abs(got - ref) <= 1e-4 * (np.abs(ref) + rms)), (name, np.abs(got - ref).max(), rms)
+
+
 def _full_size_parity(cfg_name, n_norm_samples=2, n_entries=24):
     """Full-size micro-batch on the GPU; sampled norms and sampled sum entries from the oracle."""
     import paper_2108_01624_amd as pkg
@@ -127,10 +140,43 @@ def _full_size_parity(cfg_name, n_norm_samples=2, n_entries=24):
                     sb = np.sqrt(np.mean(ref_b ** 2))
                     assert np.all(np.abs(got_b - ref_b) <= 1e-4 * (np.abs(ref_b) + sb)), spec.name
             elif spec.kind == "embedding" and not spec.distinct:
-                rows = np.nonzero(np.abs(host(run.view(run.S, k, 0))).sum(axis=1))[0]
-                np.testing.assert_array_equal(rows, np.unique(host(l["ids"])))
+                S_E = host(run.view(run.S, k, 0))
+                ids_h = host(l["ids"])
+                rows = np.nonzero(np.abs(S_E).sum(axis=1))[0]
+                np.testing.assert_array_equal(rows, np.unique(ids_h))
+                # values: the oracle's scatter restricted to sampled columns, read at sampled rows - the most frequent
+                # ids (their runs of sorted positions cross hundreds of 32-position chunks), ids that occur once, and
+                # ids drawn from those present
+                counts = np.bincount(ids_h.reshape(-1), minlength=spec.d_in)
+                frequent = counts.argsort()[::-1][:6]
+                once = np.nonzero(counts == 1)[0]
+                present = np.nonzero(counts)[0]
+                vs = np.concatenate([frequent, rng.choice(once, size=6, replace=False), rng.choice(present, size=12, replace=False)])
+                assert counts[frequent[0]] > 32 * 100 and (counts[vs[6:12]] == 1).all()
+                _embedding_entries(l, S_E, ids_h, vs, c_ref, spec.d_in, rng, spec.name)
             elif spec.kind == "embedding":
-                assert not host(run.view(run.S, k, 0))[T:].any()
+                S_E = host(run.view(run.S, k, 0))
+                assert not S_E[T:].any()
+                vs = np.concatenate([[0, T - 1], rng.integers(0, T, size=14)])
+                _embedding_entries(l, S_E, host(l["ids"]), vs, c_ref, spec.d_in, rng, spec.name)
+        # LayerNorm sums of the first and the last LayerNorm, sampled columns over all B examples: the sums pass 2 formed
+        # from the per-example gradients that pass 1 kept, and the sums of the path that reads the inputs again
+        ln = [k for k, spec in enumerate(man) if spec.kind == "layernorm"]
+        for k in (ln[0], ln[-1]):
+            l, d = layers[k], man[k].d_out
+            cols = np.concatenate([[0, d - 1], rng.integers(0, d, size=14)])
+            ct = torch.as_tensor(cols, device=DEV)
+            ref_g, ref_b = orc.clip_accumulate_layernorm(l["X"][:, :, ct].float().cpu().numpy(),
+                                                         l["G"][:, :, ct].float().cpu().numpy(), c_ref)
+            again_g = torch.zeros(d, dtype=torch.float32, device=DEV)
+            again_b = torch.zeros(d, dtype=torch.float32, device=DEV)
+            ctx.clip_accumulate_layernorm_batched([l["X"]], [l["G"]], C, run.sqnorms[:B], [again_g], [again_b])
+            ctx.sync()
+            for what, got_g, got_b in (("kept", host(run.view(run.S, k, 0)), host(run.view(run.S, k, 1))),
+                                       ("re-read", host(again_g), host(again_b))):
+                for nm, got, ref in (("gamma", got_g[cols], ref_g), ("beta", got_b[cols], ref_b)):
+                    rms = np.sqrt(np.mean(ref ** 2))
+                    assert np.all(np.abs(got - ref) <= 1e-4 * (np.abs(ref) + rms)), (man[k].name, what, nm, np.abs(got - ref).max(), rms)
 
 
 # ------------------------------------------------------------------------------------------------

@@ -157,7 +157,7 @@ def test_adamw_untouched_row_is_pure_decay(dp):
 
 
 # ------------------------------------------------------------------------------------------------
-# gradient signal-to-noise terms fused into the update (Section 5.2)
+# gradient signal-to-noise terms fused into the update (Section 5.2.1)
 # ------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("n,off,sigma,zero_sum", [(64 * 64, 0, 1.0, False), (1, 0, 0.6, False), (4099, 0, 0.6, True),
                                                    (1000, 5, 0.6, False), (7, 2, 0.0, False), (300007, 8, 0.6, True),
@@ -355,6 +355,64 @@ def test_dense_pipeline_clip_invariant_and_determinism(dp):
     SW_ref, Sb_ref = orc.clip_accumulate_dense(A, G, c_ref, True)
     assert_sums_close(S_W, SW_ref, TOL_BF16, "sum_W")
     assert_sums_close(S_b, Sb_ref, TOL_BF16, "sum_b")
+
+
+@pytest.mark.parametrize("T", [128, 48])  # 128: operands straight into LDS, accumulators rescaled at example boundaries;
+                                          # 48: register-staged kernel, clip factor applied to the staged rows
+def test_dense_one_example_with_a_huge_norm(dp, T):
+    """Finite inputs, one example whose gradient norm is 5e18 (its squared norm, 2.5e37, is near the top of the fp32 range)
+    between neighbours with norms around 1: its clip factor is 2e-19, the ratios of neighbouring factors 5e18 and 2e-19, and
+    every path must still give the oracle's sums."""
+    import paper_2108_01624_amd as pkg
+
+    B, d_in, d_out, C, big = 6, 256, 256, 1.0, 3
+    A = gen((B, T, d_in), 1.0, 150, "bf16")
+    Gf = syn.normal_f32((B, T, d_out), 1e-2, 151)
+    n0 = orc.sqnorms_dense(A, syn.f32_to_bf16_bits(Gf), True)
+    Gf /= np.sqrt(n0)[:, None, None].astype(np.float32)          # every example: norm ~1
+    Gf[big] *= np.float32(5e18)
+    G = syn.f32_to_bf16_bits(Gf)
+    n_ref = orc.sqnorms_dense(A, G, True)
+    assert 1e37 < n_ref[big] < 3e38 and n_ref[big - 1] < 4 and n_ref[big + 1] < 4
+    c_ref = orc.clip_factors(n_ref, C)
+    SW_ref, Sb_ref = orc.clip_accumulate_dense(A, G, c_ref, True)
+    A_d, G_d = to_dev(A), to_dev(G)
+    n = torch.zeros(B, dtype=torch.float32, device=DEV)
+    S_W, S_b = torch.zeros(d_in, d_out, dtype=torch.float32, device=DEV), torch.zeros(d_out, dtype=torch.float32, device=DEV)
+    dp.sqnorms_dense(A_d, G_d, True, pkg.DP_PATH_GRAM, n)
+    dp.clip_accumulate_dense(A_d, G_d, C, n, S_W, S_b)
+    dp.sync()
+    assert_norms_close(host(n), n_ref, 1e-4, "norms")
+    assert_sums_close(host(S_W), SW_ref, TOL_BF16, "sum_W")
+    assert_sums_close(host(S_b), Sb_ref, TOL_BF16, "sum_b")
+    # the clipped example still weighs as much as a neighbour: dropping it would be seen
+    SW_without, _ = orc.clip_accumulate_dense(np.delete(A, big, 0), np.delete(G, big, 0), np.delete(c_ref, big), True)
+    assert np.linalg.norm(SW_ref - SW_without) > 0.1 * np.linalg.norm(SW_ref)
+
+
+@pytest.mark.parametrize("T", [128, 48])
+@pytest.mark.parametrize("bad", [np.inf, np.nan])
+def test_dense_non_finite_norm_poisons_the_sum_and_is_reported(dp, T, bad):
+    """A squared norm that overflowed fp32 (or is NaN) has no clip factor: every path alike turns the sums it enters
+    into NaN, and dp_sync reports DP_ERR_VALUE once."""
+    import paper_2108_01624_amd as pkg
+
+    B, d_in, d_out = 4, 256, 256
+    A, G = gen((B, T, d_in), 1.0, 152, "bf16"), gen((B, T, d_out), 1e-2, 153, "bf16")
+    sq = np.array([0.5, 2.0, bad, 3.0], np.float32)
+    S_W, S_b = torch.zeros(d_in, d_out, dtype=torch.float32, device=DEV), torch.zeros(d_out, dtype=torch.float32, device=DEV)
+    dp.clip_accumulate_dense(to_dev(A), to_dev(G), 1.0, f32_dev(sq), S_W, S_b)
+    with pytest.raises(pkg.DpError) as e:
+        dp.sync()
+    assert e.value.status == -5
+    dp.sync()  # the error word is cleared
+    assert np.isnan(host(S_W)).all() and np.isnan(host(S_b)).all()
+    c = torch.zeros(B, dtype=torch.float32, device=DEV)
+    dp.clip_factors(f32_dev(sq), 1.0, c)
+    with pytest.raises(pkg.DpError):
+        dp.sync()
+    got = host(c)
+    assert np.isnan(got[2]) and np.isfinite(got[[0, 1, 3]]).all()
 
 
 # ------------------------------------------------------------------------------------------------

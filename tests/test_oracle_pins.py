@@ -632,7 +632,7 @@ def test_noise_depends_on_global_element_index():
 
 
 # ----------------------------------------------------------------------------------------------
-# gradient signal-to-noise ratio (Section 5.2, effect of batch size on DP gradients)
+# gradient signal-to-noise ratio (Section 5.2.1, effect of batch size on DP gradients)
 # ----------------------------------------------------------------------------------------------
 def test_gradient_snr_closed_forms():
     n, sigma, C = 1 << 16, 0.6, 0.5
@@ -672,7 +672,7 @@ def test_gradient_snr_noise_is_what_the_update_adds():
 
 
 def test_gradient_snr_grows_with_batch_size():
-    """Section 5.2's observation in its simplest form: with per-example clipped gradients pointing the same
+    """Section 5.2.1's observation in its simplest form: with per-example clipped gradients pointing the same
     way, the signal norm grows like |B| while the noise norm does not depend on |B|."""
     n = 4096
     unit = syn.normal_f32((n,), 1.0, 31).astype(np.float64)
