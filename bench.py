@@ -41,7 +41,8 @@ def parse():
     ap.add_argument("--batch", type=int, default=0, help="override the micro-batch size (parity/debug only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-examples", type=int, default=0, help="examples in the oracle sample (0 = auto)")
-    XX
+    ap.add_argument("--cpu-update-elems", type=int, default=0,
+                    help="parameters in the oracle's update sample (0 = all of them: about 12 s on the GPU box's host)")
     ap.add_argument("--no-calibration", action="store_true",
                     help="skip the register-only MFMA loop and the separately timed 28 B/param update")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -284,7 +285,7 @@ def main():
     if not args.no_cpu_baseline:
         # ~155 GFLOP of fp64 work per BERT-Large example at T=128: a few dozen examples are 10-30 s of host time
         n_ex = args.cpu_examples or max(1, min(B, 32 * 128 // T))
-        base, _ = cpu_baseline(layers, cfg, n_ex, upd, min(args.cpu_update_elems, int(run.P)), int(run.P))
+        base, _ = cpu_baseline(layers, cfg, n_ex, upd, min(args.cpu_update_elems or int(run.P), int(run.P)), int(run.P))
         out["cpu_baseline"] = base
     ctx.close()
     print(json.dumps(out))
