@@ -245,6 +245,21 @@ dp_status dp_noise_adamw_snr(dp_ctx* ctx, float* params, float* m, float* v, flo
                              uint64_t batch_size, float lr, float beta1, float beta2, float eps, float weight_decay,
                              int zero_sum, float* snr_sq);
 
+/* dp_noise_adamw_snr for callers that cannot allocate device memory or hold a context whose creation does (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): no dp_ctx, the work is enqueued on
+ * `hip_stream` (a hipStream_t, borrowed; NULL = the null stream), whose device must be the current device, and the
+ * per-workgroup partial norms go to a fixed array in the library's device image (8 MiB per GPU, held until the process
+ * ends; its address on a device is looked up by the first call on that device or by dp_create) instead of a workspace.
+ * No hipMalloc / hipFree and no allocating library call.  Limit: n <= 2^30 elements per call, DP_ERR_WORKSPACE beyond
+ * (slice the update: snr_sq adds over slices).  Same arguments, argument checks, kernels and results, bit for bit, as
+ * dp_noise_adamw_snr; errors are returned as status codes only (there is no context to hold a message).  All calls on
+ * one GPU share that GPU's array: every call overwrites the part it uses, nothing needs clearing, but calls that overlap in
+ * time on one GPU (different streams or threads) race; calls on one stream are safe. */
+dp_status dp_noise_adamw_snr_static(void* hip_stream, float* params, float* m, float* v, float* sum, uint64_t n,
+                                    uint64_t elem_offset, float sigma, float C, uint64_t seed, uint64_t step,
+                                    uint64_t batch_size, float lr, float beta1, float beta2, float eps, float weight_decay,
+                                    int zero_sum, float* snr_sq);
+
 /* ---------------------------------------------------------------------------------------------------
  * Aids
  * ------------------------------------------------------------------------------------------------- */

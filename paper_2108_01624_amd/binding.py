@@ -53,6 +53,8 @@ SIGNATURES = {
                        c_uint64, c_uint64, c_float, c_float, c_float, c_float, c_float, c_int],
     "dp_noise_adamw_snr": [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_uint64, c_uint64, c_float, c_float, c_uint64,
                            c_uint64, c_uint64, c_float, c_float, c_float, c_float, c_float, c_int, c_void_p],
+    "dp_noise_adamw_snr_static": [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_uint64, c_uint64, c_float, c_float,
+                                  c_uint64, c_uint64, c_uint64, c_float, c_float, c_float, c_float, c_float, c_int, c_void_p],
     "dp_zero_f32": [c_void_p, c_void_p, c_uint64],
     "dp_philox_u32": [c_void_p, c_void_p, c_uint64, c_uint64, c_uint64, c_uint64],
     "dp_normal_f32": [c_void_p, c_void_p, c_uint64, c_uint64, c_uint64, c_uint64],
@@ -366,6 +368,19 @@ def dp_noise_adamw_snr(ctx, params, m, v, sum_, snr_sq, *, n=None, elem_offset=0
                                            seed, step, batch_size, lr, beta1, beta2, eps, weight_decay, int(zero_sum),
                                            _f32(snr_sq))
     _check(ctx, st, "dp_noise_adamw_snr")
+
+
+def dp_noise_adamw_snr_static(stream_handle, params, m, v, sum_, snr_sq, *, n=None, elem_offset=0, sigma, C, seed, step,
+                              batch_size, lr, beta1, beta2, eps=1e-11, weight_decay, zero_sum=False):
+    """dp_noise_adamw_snr without a context: `stream_handle` is the hipStream_t as an integer (0 = the null stream)."""
+    n = params.numel() if n is None else n
+    if snr_sq.numel() < 2:
+        raise ValueError("snr_sq needs two floats")
+    st = load_library().dp_noise_adamw_snr_static(stream_handle, _f32(params), _f32(m), _f32(v), _f32(sum_), n, elem_offset,
+                                                  sigma, C, seed, step, batch_size, lr, beta1, beta2, eps, weight_decay,
+                                                  int(zero_sum), _f32(snr_sq))
+    if st != DP_OK:
+        raise DpError(st, "dp_noise_adamw_snr_static")
 
 
 def dp_zero_f32(ctx, p, n=None):

@@ -77,6 +77,8 @@ dp_status dp_create(dp_ctx** out, void* hip_stream, size_t workspace_bytes) {
         return DP_ERR_HIP;
     }
     hipError_t e = hipGetDevice(&ctx->device);
+    float* static_scratch = nullptr;  // looked up here so that dp_noise_adamw_snr_static finds it ready on this device
+    if (e == hipSuccess && dpk_static_scratch(&static_scratch) != DP_OK) e = hipErrorInvalidSymbol;
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->ws, ctx->ws_bytes);
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->err_word, sizeof(int));
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->cbuf, (size_t)ctx->cbuf_cap * sizeof(float));
@@ -630,22 +632,37 @@ dp_status dp_clip_accumulate_tied_embedding(dp_ctx* ctx, const int32_t* ids, con
     return dpk_tied_projection_sums(ctx, H, dL, dtype, B, M, d, V, sqnorms, C, sum_E);
 }
 
+// Argument checks of the update; *why is set to a static text on failure.
+static dp_status check_update_args(const float* params, const float* m, const float* v, const float* sum, uint64_t n,
+                                   uint64_t elem_offset, float sigma, float C, uint64_t step, uint64_t batch_size, float lr,
+                                   float beta1, float beta2, float eps, float weight_decay, const char** why) {
+#define UPD_FAIL(code, text) \
+    do {                     \
+        *why = text;         \
+        return code;         \
+    } while (0)
+    if (!params || !m || !v || !sum) UPD_FAIL(DP_ERR_NULL, "params, m, v or sum is NULL");
+    if (((uintptr_t)params | (uintptr_t)m | (uintptr_t)v | (uintptr_t)sum) & 3) UPD_FAIL(DP_ERR_ALIGN, "params, m, v and sum must be 4-byte aligned");
+    if (!(sigma >= 0.f) || !isfinite(sigma)) UPD_FAIL(DP_ERR_VALUE, "sigma must be >= 0 and finite");
+    if (!(C > 0.f) || !isfinite(C)) UPD_FAIL(DP_ERR_VALUE, "clip norm C must be positive and finite");
+    if (batch_size == 0) UPD_FAIL(DP_ERR_VALUE, "batch_size must be positive");
+    if (step == 0) UPD_FAIL(DP_ERR_VALUE, "step counts from 1");
+    if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f)) UPD_FAIL(DP_ERR_VALUE, "beta outside [0, 1)");
+    if (!(eps >= 0.f) || !isfinite(eps)) UPD_FAIL(DP_ERR_VALUE, "eps must be >= 0 and finite");
+    if (!isfinite(lr) || !isfinite(weight_decay)) UPD_FAIL(DP_ERR_VALUE, "lr and weight_decay must be finite");
+    if (elem_offset + n < elem_offset) UPD_FAIL(DP_ERR_SHAPE, "elem_offset + n overflows");
+#undef UPD_FAIL
+    return DP_OK;
+}
+
 static dp_status noise_adamw_checked(dp_ctx* ctx, float* params, float* m, float* v, float* sum, uint64_t n,
                                      uint64_t elem_offset, float sigma, float C, uint64_t seed, uint64_t step,
                                      uint64_t batch_size, float lr, float beta1, float beta2, float eps,
                                      float weight_decay, int zero_sum, float* sq_out) {
-    TRY(check_f32(ctx, "params", params));
-    TRY(check_f32(ctx, "m", m));
-    TRY(check_f32(ctx, "v", v));
-    TRY(check_f32(ctx, "sum", sum));
-    if (!(sigma >= 0.f) || !isfinite(sigma)) FAIL(ctx, DP_ERR_VALUE, "sigma must be >= 0 and finite");
-    if (!(C > 0.f) || !isfinite(C)) FAIL(ctx, DP_ERR_VALUE, "clip norm C must be positive and finite");
-    if (batch_size == 0) FAIL(ctx, DP_ERR_VALUE, "batch_size must be positive");
-    if (step == 0) FAIL(ctx, DP_ERR_VALUE, "step counts from 1");
-    if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f)) FAIL(ctx, DP_ERR_VALUE, "beta outside [0, 1)");
-    if (!(eps >= 0.f) || !isfinite(eps)) FAIL(ctx, DP_ERR_VALUE, "eps must be >= 0 and finite");
-    if (!isfinite(lr) || !isfinite(weight_decay)) FAIL(ctx, DP_ERR_VALUE, "lr and weight_decay must be finite");
-    if (elem_offset + n < elem_offset) FAIL(ctx, DP_ERR_SHAPE, "elem_offset + n overflows");
+    const char* why = "";
+    const dp_status st = check_update_args(params, m, v, sum, n, elem_offset, sigma, C, step, batch_size, lr, beta1, beta2,
+                                           eps, weight_decay, &why);
+    if (st != DP_OK) FAIL(ctx, st, "%s", why);
     return dpk_noise_adamw(ctx, params, m, v, sum, n, elem_offset, sigma, C, seed, step, batch_size, lr, beta1, beta2,
                            eps, weight_decay, zero_sum, sq_out);
 }
@@ -668,6 +685,20 @@ dp_status dp_noise_adamw_snr(dp_ctx* ctx, float* params, float* m, float* v, flo
     if ((uintptr_t)snr_sq & 3) FAIL(ctx, DP_ERR_ALIGN, "snr_sq must be 4-byte aligned");
     return noise_adamw_checked(ctx, params, m, v, sum, n, elem_offset, sigma, C, seed, step, batch_size, lr, beta1,
                                beta2, eps, weight_decay, zero_sum, snr_sq);
+}
+
+dp_status dp_noise_adamw_snr_static(void* hip_stream, float* params, float* m, float* v, float* sum, uint64_t n,
+                                    uint64_t elem_offset, float sigma, float C, uint64_t seed, uint64_t step,
+                                    uint64_t batch_size, float lr, float beta1, float beta2, float eps, float weight_decay,
+                                    int zero_sum, float* snr_sq) {
+    if (!snr_sq) return DP_ERR_NULL;
+    if ((uintptr_t)snr_sq & 3) return DP_ERR_ALIGN;
+    const char* why = "";
+    const dp_status st = check_update_args(params, m, v, sum, n, elem_offset, sigma, C, step, batch_size, lr, beta1, beta2,
+                                           eps, weight_decay, &why);
+    if (st != DP_OK) return st;
+    return dpk_noise_adamw_snr_static((hipStream_t)hip_stream, params, m, v, sum, n, elem_offset, sigma, C, seed, step,
+                                      batch_size, lr, beta1, beta2, eps, weight_decay, zero_sum, snr_sq);
 }
 
 dp_status dp_zero_f32(dp_ctx* ctx, float* p, uint64_t n) {

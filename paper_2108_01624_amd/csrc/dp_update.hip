@@ -4,7 +4,17 @@
 // Roofline: HBM.  Per parameter the kernel reads theta, m, v, sum (16 B) and writes theta, m, v (12 B),
 // plus 4 B when it also clears the sum: 28 (32) algorithmic bytes.  One thread owns one Philox block,
 // i.e. four consecutive elements, so every access is a 16-byte vector and a wave covers 1 KiB per array.
+#include <mutex>
+
 #include "dp_common.h"
+
+// Scratch of dp_noise_adamw_snr_static (the entry point that allocates nothing): one pair of partial squared norms per
+// workgroup of the update, 2 floats per 1024 elements, for slices of up to DP_STATIC_MAX_ELEMS elements.  Every GPU
+// that loads the library holds its own copy (about 8 MiB) until the process ends.  In host code this name is only a
+// handle for hipGetSymbolAddress: kernels get the device address that call returns.
+constexpr uint64_t DP_STATIC_MAX_ELEMS = 1ull << 30;
+constexpr uint64_t DP_STATIC_MAX_PAIRS = DP_STATIC_MAX_ELEMS / 1024 + 2;
+static __device__ __align__(256) float dp_static_scratch[2 * DP_STATIC_MAX_PAIRS];
 
 namespace {
 
@@ -262,64 +272,61 @@ __global__ __launch_bounds__(256) void clip_factors_kernel(const float* __restri
     }
 }
 
-template <bool NOISE, bool ZERO, bool SNR>
-dp_status launch_adamw(dp_ctx* ctx, float* params, float* m, float* v, float* sum, uint64_t n, uint64_t off,
-                       uint64_t seed, uint64_t step, const AdamArgs& a, float* sq_out) {
+// How a slice [off, off + n) is cut into launches: the 16-byte-aligned body in blocks of four elements (vec4 kernel),
+// the rest (or everything, when the slice is not aligned) element by element; one partial pair per workgroup.
+struct AdamPlan {
+    uint64_t nb4, grid4, done, first, nblocks, grid1;
+    uint64_t pairs() const { return grid4 + grid1; }
+    bool fits() const { return grid4 <= 0x7FFFFFFFull && grid1 <= 0x7FFFFFFFull; }
+};
+AdamPlan plan_adamw(const float* params, const float* m, const float* v, const float* sum, uint64_t n, uint64_t off) {
+    AdamPlan p{};
     const bool aligned = (off % 4 == 0) && (((uintptr_t)params | (uintptr_t)m | (uintptr_t)v | (uintptr_t)sum) & 15) == 0;
-    const uint64_t nb4 = (aligned && n >= 4) ? n / 4 : 0;
-    const uint64_t grid4 = (nb4 + 255) / 256;
-    const uint64_t done = nb4 * 4;
-    uint64_t first = 0, nblocks = 0, grid1 = 0;
-    if (done < n) {
-        first = (off + done) / 4;
-        nblocks = (off + n - 1) / 4 - first + 1;
-        grid1 = (nblocks + 255) / 256;
+    p.nb4 = (aligned && n >= 4) ? n / 4 : 0;
+    p.grid4 = (p.nb4 + 255) / 256;
+    p.done = p.nb4 * 4;
+    if (p.done < n) {
+        p.first = (off + p.done) / 4;
+        p.nblocks = (off + n - 1) / 4 - p.first + 1;
+        p.grid1 = (p.nblocks + 255) / 256;
     }
-    if (grid4 > 0x7FFFFFFFull || grid1 > 0x7FFFFFFFull) {
-        DP_SET_ERR(ctx, "dp_noise_adamw: slice too large for one launch");
-        return DP_ERR_SHAPE;
+    return p;
+}
+
+// `part`: room for 2 * plan.pairs() floats when SNR (every pair is overwritten), else unused.  Returns the first
+// launch error.
+template <bool NOISE, bool ZERO, bool SNR>
+hipError_t launch_adamw(hipStream_t stream, const AdamPlan& pl, float* params, float* m, float* v, float* sum, uint64_t n,
+                        uint64_t off, uint64_t seed, uint64_t step, const AdamArgs& a, float* part, float* sq_out) {
+    hipError_t e = hipSuccess;
+    if (pl.grid4) {
+        hipLaunchKernelGGL((noise_adamw_vec4<NOISE, ZERO, SNR>), dim3((unsigned)pl.grid4), dim3(256), 0, stream, params, m,
+                           v, sum, pl.nb4, off / 4, seed, step, a, part);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
     }
-    float* part = nullptr;
-    if (SNR) {
-        dp_ws_alloc ws(ctx);
-        part = ws.get<float>(2 * (grid4 + grid1));
-        if (!part) {
-            DP_SET_ERR(ctx, "dp_noise_adamw_snr: workspace too small for the per-workgroup partial norms");
-            return DP_ERR_WORKSPACE;
-        }
-    }
-    if (grid4) {
-        hipLaunchKernelGGL((noise_adamw_vec4<NOISE, ZERO, SNR>), dim3((unsigned)grid4), dim3(256), 0, ctx->stream,
-                           params, m, v, sum, nb4, off / 4, seed, step, a, part);
-        DP_LAUNCH_CHECK(ctx, "noise_adamw_vec4");
-    }
-    if (grid1) {
-        hipLaunchKernelGGL((noise_adamw_scalar<NOISE, ZERO, SNR>), dim3((unsigned)grid1), dim3(256), 0, ctx->stream,
-                           params, m, v, sum, off, off + done, off + n, first, nblocks, seed, step, a, part, grid4);
-        DP_LAUNCH_CHECK(ctx, "noise_adamw_scalar");
+    if (pl.grid1) {
+        hipLaunchKernelGGL((noise_adamw_scalar<NOISE, ZERO, SNR>), dim3((unsigned)pl.grid1), dim3(256), 0, stream, params,
+                           m, v, sum, off, off + pl.done, off + n, pl.first, pl.nblocks, seed, step, a, part, pl.grid4);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     if (SNR) {
-        hipLaunchKernelGGL(snr_finish_kernel, dim3(1), dim3(1024), 0, ctx->stream, part, grid4 + grid1, sq_out);
-        DP_LAUNCH_CHECK(ctx, "snr_finish_kernel");
+        hipLaunchKernelGGL(snr_finish_kernel, dim3(1), dim3(1024), 0, stream, part, pl.pairs(), sq_out);
+        e = hipGetLastError();
     }
-    return DP_OK;
+    return e;
 }
 
 template <bool SNR>
-dp_status dispatch_adamw(dp_ctx* ctx, float* params, float* m, float* v, float* sum, uint64_t n, uint64_t off,
-                         uint64_t seed, uint64_t step, const AdamArgs& a, bool noise, int zero_sum, float* sq_out) {
-    if (noise && zero_sum) return launch_adamw<true, true, SNR>(ctx, params, m, v, sum, n, off, seed, step, a, sq_out);
-    if (noise) return launch_adamw<true, false, SNR>(ctx, params, m, v, sum, n, off, seed, step, a, sq_out);
-    if (zero_sum) return launch_adamw<false, true, SNR>(ctx, params, m, v, sum, n, off, seed, step, a, sq_out);
-    return launch_adamw<false, false, SNR>(ctx, params, m, v, sum, n, off, seed, step, a, sq_out);
+hipError_t dispatch_adamw(hipStream_t stream, const AdamPlan& pl, float* params, float* m, float* v, float* sum, uint64_t n,
+                          uint64_t off, uint64_t seed, uint64_t step, const AdamArgs& a, bool noise, int zero_sum,
+                          float* part, float* sq_out) {
+    if (noise && zero_sum) return launch_adamw<true, true, SNR>(stream, pl, params, m, v, sum, n, off, seed, step, a, part, sq_out);
+    if (noise) return launch_adamw<true, false, SNR>(stream, pl, params, m, v, sum, n, off, seed, step, a, part, sq_out);
+    if (zero_sum) return launch_adamw<false, true, SNR>(stream, pl, params, m, v, sum, n, off, seed, step, a, part, sq_out);
+    return launch_adamw<false, false, SNR>(stream, pl, params, m, v, sum, n, off, seed, step, a, part, sq_out);
 }
 
-}  // namespace
-
-dp_status dpk_noise_adamw(dp_ctx* ctx, float* params, float* m, float* v, float* sum, uint64_t n, uint64_t off,
-                          float sigma, float C, uint64_t seed, uint64_t step, uint64_t batch, float lr, float b1,
-                          float b2, float eps, float wd, int zero_sum, float* sq_out) {
-    if (n == 0) return DP_OK;
+AdamArgs adam_args(float sigma, float C, uint64_t step, uint64_t batch, float lr, float b1, float b2, float eps, float wd) {
     AdamArgs a;
     a.noise_scale = sigma * C;
     a.inv_batch = (float)(1.0 / (double)batch);
@@ -330,10 +337,73 @@ dp_status dpk_noise_adamw(dp_ctx* ctx, float* params, float* m, float* v, float*
     a.lr = lr;
     a.eps = eps;
     a.wd = wd;
+    return a;
+}
+
+}  // namespace
+
+// Device address of dp_static_scratch on the CURRENT device, looked up once per device.
+dp_status dpk_static_scratch(float** out) {
+    constexpr int MAX_DEV = 64;
+    static std::mutex mu;
+    static float* ptr[MAX_DEV] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEV) return DP_ERR_HIP;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(dp_static_scratch)) != hipSuccess || !p) return DP_ERR_HIP;
+        ptr[dev] = static_cast<float*>(p);
+    }
+    *out = ptr[dev];
+    return DP_OK;
+}
+
+// The update with the gradient-SNR terms on `stream`, partial pairs in the static scratch; arguments already checked.
+dp_status dpk_noise_adamw_snr_static(hipStream_t stream, float* params, float* m, float* v, float* sum, uint64_t n,
+                                     uint64_t off, float sigma, float C, uint64_t seed, uint64_t step, uint64_t batch,
+                                     float lr, float b1, float b2, float eps, float wd, int zero_sum, float* sq_out) {
+    if (n == 0) return DP_OK;
+    if (n > DP_STATIC_MAX_ELEMS) return DP_ERR_WORKSPACE;
+    const AdamPlan pl = plan_adamw(params, m, v, sum, n, off);
+    if (!pl.fits() || pl.pairs() > DP_STATIC_MAX_PAIRS) return DP_ERR_WORKSPACE;
+    float* part = nullptr;
+    const dp_status st = dpk_static_scratch(&part);
+    if (st != DP_OK) return st;
+    const AdamArgs a = adam_args(sigma, C, step, batch, lr, b1, b2, eps, wd);
+    const hipError_t e = dispatch_adamw<true>(stream, pl, params, m, v, sum, n, off, seed, step, a, sigma != 0.f, zero_sum,
+                                              part, sq_out);
+    return e == hipSuccess ? DP_OK : DP_ERR_HIP;
+}
+
+dp_status dpk_noise_adamw(dp_ctx* ctx, float* params, float* m, float* v, float* sum, uint64_t n, uint64_t off,
+                          float sigma, float C, uint64_t seed, uint64_t step, uint64_t batch, float lr, float b1,
+                          float b2, float eps, float wd, int zero_sum, float* sq_out) {
+    if (n == 0) return DP_OK;
+    const AdamArgs a = adam_args(sigma, C, step, batch, lr, b1, b2, eps, wd);
+    const AdamPlan pl = plan_adamw(params, m, v, sum, n, off);
+    if (!pl.fits()) {
+        DP_SET_ERR(ctx, "dp_noise_adamw: slice too large for one launch");
+        return DP_ERR_SHAPE;
+    }
+    float* part = nullptr;
+    if (sq_out) {
+        dp_ws_alloc ws(ctx);
+        part = ws.get<float>(2 * pl.pairs());
+        if (!part) {
+            DP_SET_ERR(ctx, "dp_noise_adamw_snr: workspace too small for the per-workgroup partial norms");
+            return DP_ERR_WORKSPACE;
+        }
+    }
     const bool noise = sigma != 0.f;
     dp_prof_scope prof(ctx, DP_PROF_ADAMW, (zero_sum ? 32.0 : 28.0) * (double)n);
-    if (sq_out) return dispatch_adamw<true>(ctx, params, m, v, sum, n, off, seed, step, a, noise, zero_sum, sq_out);
-    return dispatch_adamw<false>(ctx, params, m, v, sum, n, off, seed, step, a, noise, zero_sum, nullptr);
+    const hipError_t e = sq_out ? dispatch_adamw<true>(ctx->stream, pl, params, m, v, sum, n, off, seed, step, a, noise, zero_sum, part, sq_out)
+                                : dispatch_adamw<false>(ctx->stream, pl, params, m, v, sum, n, off, seed, step, a, noise, zero_sum, nullptr, nullptr);
+    if (e != hipSuccess) {
+        DP_SET_ERR(ctx, "launch of the noise + Adam update failed: %s", hipGetErrorString(e));
+        return DP_ERR_HIP;
+    }
+    return DP_OK;
 }
 
 template <int MODE>
