@@ -12,6 +12,7 @@ from .inputs import (  # noqa: F401
     normal_bf16_bits,
     zipf_ids,
     position_ids,
+    segment_ids,
     example_scales,
     synthetic_sqnorms,
 )

@@ -4,7 +4,7 @@ from __future__ import annotations
 
 import numpy as np
 
-from .inputs import position_ids, zipf_ids
+from .inputs import position_ids, segment_ids, zipf_ids
 
 
 def _randn(shape, std, gen, dtype, device):
@@ -35,12 +35,19 @@ def device_layer_inputs(manifest, B, T, *, dtype, act_std, grad_std, data_seed, 
     if example_scale is not None:
         sc = torch.from_numpy(np.asarray(example_scale, dtype=np.float32)).to(device)[:, None, None]
     layers = []
+    group_grads = {}
     for k, spec in enumerate(manifest):
         d = dict(kind=spec.kind, name=spec.name, spec=spec)
 
         def grad(width):
+            key = (spec.grad_group, width)
+            if spec.grad_group and key in group_grads:
+                return group_grads[key]   # the SAME tensor object: one upstream gradient for the whole group
             g = _randn((B, T, width), grad_std, gen, torch.float32 if sc is not None else tdtype, device)
-            return (g * sc).to(tdtype) if sc is not None else g
+            g = (g * sc).to(tdtype) if sc is not None else g
+            if spec.grad_group:
+                group_grads[key] = g
+            return g
 
         if spec.kind == "dense":
             d["A"] = _randn((B, T, spec.d_in), act_std, gen, tdtype, device)
@@ -70,7 +77,12 @@ def device_layer_inputs(manifest, B, T, *, dtype, act_std, grad_std, data_seed, 
                 dL *= sc
             d["dL"] = dL.to(tdtype)
         else:
-            ids = position_ids(B, T) if spec.distinct else zipf_ids(B, T, spec.d_in, zipf_s, int(data_seed) + 7919 * (k + 1))
+            if spec.distinct:
+                ids = position_ids(B, T)
+            elif spec.segment:
+                ids = segment_ids(B, T)
+            else:
+                ids = zipf_ids(B, T, spec.d_in, zipf_s, int(data_seed) + 7919 * (k + 1))
             d["ids"] = torch.from_numpy(ids).to(device)
             d["G"] = grad(spec.d_out)
             d["V"] = spec.d_in

@@ -50,6 +50,12 @@ def position_ids(B: int, T: int) -> np.ndarray:
     return np.broadcast_to(np.arange(T, dtype=np.int32), (B, T)).copy()
 
 
+def segment_ids(B: int, T: int) -> np.ndarray:
+    """Token-type ids of a sentence pair: 0 for the first half of the sequence, 1 for the second. int32 [B, T]."""
+    row = (np.arange(T, dtype=np.int32) >= (T + 1) // 2).astype(np.int32)
+    return np.broadcast_to(row, (B, T)).copy()
+
+
 def example_scales(B: int, lo: float, hi: float, seed: int) -> np.ndarray:
     """Per-example log-uniform scales in [lo, hi] (fp32): multiplying example i's output
     gradients by scale[i] makes the per-example norms straddle the clip norm."""

@@ -16,6 +16,9 @@ class LayerSpec:
     d_out: int = 0  # dense: output width; layernorm/embedding: width d
     has_bias: bool = False
     distinct: bool = False  # embedding: ids are distinct within an example (position ids)
+    segment: bool = False  # embedding: token-type ids (0 for the first half of the sequence, 1 for the second)
+    grad_group: str = ""  # layers with the same non-empty group receive ONE output-gradient tensor (the three
+                          # embedding tables are summed before their LayerNorm, so they share its input gradient)
     n_pred: int = 0  # tied_embedding: prediction slots M per example whose logits use the table as output projection
 
     def tensors(self) -> List[Tuple[str, Tuple[int, ...]]]:
@@ -44,17 +47,24 @@ def single_dense_manifest(d_in: int, d_out: int, has_bias: bool = False) -> List
     return [LayerSpec("dense0", "dense", d_in, d_out, has_bias)]
 
 
-def bert_manifest(n_layers: int, hidden: int, ffn: int, vocab: int = 0, max_pos: int = 0, tied_pred: int = 0) -> List[LayerSpec]:
+def bert_manifest(n_layers: int, hidden: int, ffn: int, vocab: int = 0, max_pos: int = 0, tied_pred: int = 0,
+                  type_vocab: int = 0) -> List[LayerSpec]:
     """Per block: Q, K, V, O dense hidden x hidden, LayerNorm, FFN hidden x ffn and ffn x hidden,
     LayerNorm; all dense layers carry biases. Optional token and position embeddings first.  With tied_pred = M
-    the token table is also the output projection of M prediction slots per example (one parameter, two uses)."""
+    the token table is also the output projection of M prediction slots per example (one parameter, two uses).
+    With type_vocab = 2 the embedding stage is the full one of Section 4.3: word-piece, positional and token-type
+    tables whose lookups are summed (one shared output gradient) and the LayerNorm that follows the sum."""
     m: List[LayerSpec] = []
+    grp = "emb" if type_vocab else ""
     if vocab and tied_pred:
-        m.append(LayerSpec("emb.tok", "tied_embedding", vocab, hidden, n_pred=tied_pred))
+        m.append(LayerSpec("emb.tok", "tied_embedding", vocab, hidden, n_pred=tied_pred, grad_group=grp))
     elif vocab:
-        m.append(LayerSpec("emb.tok", "embedding", vocab, hidden))
+        m.append(LayerSpec("emb.tok", "embedding", vocab, hidden, grad_group=grp))
     if max_pos:
-        m.append(LayerSpec("emb.pos", "embedding", max_pos, hidden, distinct=True))
+        m.append(LayerSpec("emb.pos", "embedding", max_pos, hidden, distinct=True, grad_group=grp))
+    if type_vocab:
+        m.append(LayerSpec("emb.type", "embedding", type_vocab, hidden, segment=True, grad_group=grp))
+        m.append(LayerSpec("emb.ln", "layernorm", 0, hidden))
     for l in range(n_layers):
         p = f"block{l}."
         for nm in ("q", "k", "v", "o"):

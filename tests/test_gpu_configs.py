@@ -11,8 +11,10 @@ Coverage contract (what the oracle computed is what is claimed):
       checked exactly at full size.
   C4  update over all ~334M parameters against the oracle on sampled slices (Philox words bit-exact on the same
       slices), gradient-SNR terms of all parameters against a chi-square bound / a library sum and, on the one-block
-      manifest, against the oracle over every parameter; accumulation over micro-batches on a one-block manifest against the oracle; a B = 1024 dense layer
-      with sampled entries; linearity of the accumulation on the GPU (an invariant, not oracle parity).
+      manifest, against the oracle over every parameter; accumulation over micro-batches on a one-block manifest against the oracle; the FULL count
+      (64 micro-batches of 1,024 examples, then the update with |B_t| = 65,536) on a width-reduced one-block manifest, every tensor and
+      every parameter against the oracle; a B = 1024 dense layer with sampled entries; linearity of the accumulation on the GPU (an
+      invariant, not oracle parity).
 """
 import numpy as np
 import pytest
@@ -269,6 +271,40 @@ def test_c3_mixed_clipping_both_branches():
         _compare_all_tensors(run, man, sums_ref, TOL_BF16)
 
 
+def test_c3_full_embedding_stage_all_tensors():
+    """The embedding stage as Section 4.3 names it: word-piece, positional and token-type (2 rows) tables whose lookups are
+    summed - one upstream gradient for all three - and the LayerNorm after the sum, in front of one BERT-Large block.
+    Every tensor of the clip-weighted sum against the oracle through the step driver, both clip branches."""
+    import paper_2108_01624_amd as pkg
+
+    Bsub = 6
+    man = syn.bert_manifest(1, 1024, 4096, 30522, 512, type_vocab=2)
+    assert [s.name for s in man[:4]] == ["emb.tok", "emb.pos", "emb.type", "emb.ln"]
+    assert syn.manifest_param_count(syn.bert_manifest(24, 1024, 4096, 30522, 512, type_vocab=2)) == 334_092_288
+    scale = syn.example_scales(Bsub, 1e-4, 1.0, 78)
+    cfg, man, layers = _layers("C3", B=Bsub, manifest=man, example_scale=scale)
+    assert layers[0]["G"] is layers[1]["G"] and layers[1]["G"] is layers[2]["G"]      # one upstream gradient
+    assert host(layers[2]["ids"])[0].tolist() == [0] * 64 + [1] * 64
+    with pkg.Context() as ctx:
+        run = pkg.StepRunner(ctx, man, Bsub, device=DEV)
+        n = run.pass1(layers)
+        ctx.sync()
+        hl = syn.host_layer_slice(layers, range(Bsub))
+        n_ref = orc.microbatch_sqnorms(hl)
+        C = float(np.sqrt(np.median(n_ref)))
+        run.pass2(layers, C)
+        ctx.sync()
+        sums_ref, _, c_ref = orc.microbatch_clip_sum(hl, C)
+        assert (c_ref == 1).any() and (c_ref < 1).any()
+        assert_norms_close(host(n), n_ref, 1e-4)
+        _compare_all_tensors(run, man, sums_ref, TOL_BF16)
+        # the token-type table: two rows, each the clip-weighted sum of its half of every sequence
+        S_type = host(run.view(run.S, 2, 0)).astype(np.float64)
+        assert S_type.shape == (2, 1024) and np.abs(S_type).min(axis=1).max() > 0
+        assert_sums_close(S_type, sums_ref[2][0], 1e-4, "token-type table")
+        assert_sums_close(host(run.view(run.S, 3, 0)), sums_ref[3][0], 1e-4, "embedding LayerNorm gain")
+
+
 def test_c5_long_sequence_subset_all_tensors():
     worst = _subset_parity("C5", 2)
     assert worst < 5e-3, worst
@@ -394,6 +430,59 @@ def test_c4_accumulation_over_micro_batches_one_block():
             np.testing.assert_allclose(host(run.m[o:o + L]), m_ref, rtol=1e-5, atol=1e-6 * np.abs(m_ref).max())
             assert np.all(np.abs(host(run.theta[o:o + L]) - th_ref) <= 1e-5 * np.abs(th_ref) + 1e-3 * cfg["lr"])
         assert not host(run.S).any()
+
+
+def test_c4_full_count_64_micro_batches_of_1024_reduced_width():
+    """The mega-batch at its FULL count - 64 micro-batches of 1,024 examples, 65,536 examples clip-accumulated into one sum
+    buffer, then one noise + Adam step with |B_t| = 65,536 (Section 5.3) - on a width-reduced one-block manifest (hidden 128,
+    FFN 512, T = 32, all three embedding tables and their LayerNorm) so that the oracle can materialise every one of the
+    65,536 per-example gradients (about half a minute of host time).  Every tensor of the sum, then every parameter."""
+    import paper_2108_01624_amd as pkg
+
+    cfg = syn.CONFIGS["C4"]
+    Bm, K, T = cfg["B"], cfg["micro_batches"], 32
+    assert (Bm, K) == (1024, 64)
+    man = syn.bert_manifest(1, 128, 512, vocab=512, max_pos=32, type_vocab=2)
+
+    def batch(k):
+        scale = syn.example_scales(Bm, 0.05, 20.0, 7000 + k)
+        return syn.device_layer_inputs(man, Bm, T, dtype="bf16", act_std=1.0, grad_std=1e-2, data_seed=7100 + k, device=DEV,
+                                       example_scale=scale)
+
+    with pkg.Context() as ctx:
+        run = pkg.StepRunner(ctx, man, Bm, device=DEV)
+        run.theta.copy_(f32_dev(syn.normal_f32((run.P,), 0.02, 7001)))
+        th0 = host(run.theta).astype(np.float64)
+        C = float(np.sqrt(np.median(orc.microbatch_sqnorms(syn.host_layer_slice(batch(0), range(Bm))))))
+        sums_ref, clipped, worst_norm = None, 0, 0.0
+        for k in range(K):
+            layers = batch(k)
+            n = run.pass1(layers)
+            run.pass2(layers, C)
+            ctx.sync()
+            sums_ref, n_ref, c_ref = orc.microbatch_clip_sum(syn.host_layer_slice(layers, range(Bm)), C, sums_ref)
+            worst_norm = max(worst_norm, assert_norms_close(host(n), n_ref, 1e-4, f"micro-batch {k}"))
+            clipped += int((c_ref < 1).sum())
+        assert 0.2 * Bm * K < clipped < 0.8 * Bm * K          # both branches of the clip, in bulk
+        _compare_all_tensors(run, man, sums_ref, TOL_BF16)
+        S_ref = np.concatenate([x.reshape(-1) for s_ in sums_ref for x in s_])
+        assert S_ref.shape[0] == run.P
+        rel = np.linalg.norm(host(run.S) - S_ref) / np.linalg.norm(S_ref)
+        assert rel < 5e-3, rel
+        kw = dict(sigma=cfg["sigma"], C=C, seed=cfg["noise_seed"], step=1, batch_size=Bm * K, lr=cfg["lr"], beta1=cfg["beta1"],
+                  beta2=cfg["beta2"], eps=1e-11, weight_decay=cfg["weight_decay"])
+        S_gpu = host(run.S).copy()
+        run.update(**kw)
+        ctx.sync()
+        # the update on the GPU's own sum (the sum itself was compared above): every parameter
+        th_ref, m_ref, v_ref, g_ref = orc.noise_adamw(th0, np.zeros(run.P), np.zeros(run.P), S_gpu, elem_offset=0, **kw)
+        np.testing.assert_allclose(host(run.m), m_ref, rtol=1e-5, atol=1e-6 * np.abs(m_ref).max())
+        np.testing.assert_allclose(host(run.v), v_ref, rtol=2e-5, atol=1e-6 * np.abs(v_ref).max())
+        assert np.all(np.abs(host(run.theta) - th_ref) <= 1e-5 * np.abs(th_ref) + 1e-3 * cfg["lr"])
+        assert not host(run.S).any()
+        # the noise is scaled by C / |B_t| on the mean gradient: per-coordinate std sigma * C / 65,536
+        z = (host(run.m).astype(np.float64) / (1 - float(np.float32(cfg["beta1"]))) * (Bm * K) - S_gpu) / (float(np.float32(cfg["sigma"])) * float(np.float32(C)))
+        assert abs(z.std() - 1) < 0.02 and abs(z.mean()) < 0.02
 
 
 def test_c4_micro_batch_of_1024_dense_layer_and_linearity():
