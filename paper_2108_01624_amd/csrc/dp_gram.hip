@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256, 2) void gram_bf16_kernel(const uint16_t* __res
 typedef int gram_i32x4 __attribute__((ext_vector_type(4)));
 
 // STREAM: non-temporal hint, for data that no other workgroup reads again (every byte of a T <= 128 example is read
-// once; +4 % there).  The block pairs of a longer example share their panels through L2 and must not use it.
+// once; +4 % there).  The units of a longer example share their panels through L2 and must not use it.
 template <bool STREAM>
 __device__ __forceinline__ void gram_dma16(gram_i32x4 rsrc, uint32_t lds_byte_addr, int voff, int soff) {
     if (STREAM)
@@ -368,70 +368,96 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gram_dma_kernel(GramBatch gb,
 }
 
 // ------------------------------------------------------------------------------------------------
-// T > 128, widths multiples of 64: one workgroup per 128 x 128 block pair (tb <= sb) of one example's T x T plane,
-// fed like the kernel above: the two row panels of a 64-wide contraction chunk (32 KiB; 16 KiB on the diagonal,
-// where they coincide) go straight into an LDS ring, no staging registers and no LDS store instructions.  At this
-// size the contraction, not HBM, is the bound (T flop per byte against ~310 at the machine balance), and within the
-// contraction the LDS reads: with 64 x 64 wave tiles a k step of 32 needs eight 16-byte-per-lane fragment reads for
-// sixteen 16x16x32 MFMAs (1 KiB per 32 matrix-pipe cycles and SIMD), which by itself keeps the CU's LDS port busy.  Two stages and two workgroups per CU measured best (22.9 ms for
-// pass 1 of the T = 512 workload against 27.7 ms for the register-staged kernel); a deeper ring with one workgroup
-// per CU (one wave per SIMD) was slower (31 ms).  The block pairs of an example share an XCD (workgroup id % 8), so
-// each panel comes from HBM once and from L2 for its other uses.
+// T > 128, widths multiples of 64: the panels of a 64-wide contraction chunk go straight into an LDS ring (no staging
+// registers, no LDS store instructions), as in the kernel above.  At this size the contraction, not HBM, is the bound
+// (T flop per byte against ~310 at the machine balance).  A workgroup of 8 waves (two per SIMD, one workgroup per CU) works on a
+// UNIT of two 128 x 128 cells of the example's T x T plane that share their row panel R: cells (R, C1) and (R, C2).  The
+// row panel is filled into LDS once for both cells, so a unit fills three panels where two block pairs fill four, and
+// with the leading cell on the diagonal (C1 == R) two; over the upper triangle of a 4 x 4 plane that is 11 panel fills
+// instead of 16.  The fills, not the matrix instructions, bound this kernel: the units of an example run on different
+// CUs at different times, most fills miss L2 and take microseconds, and a CU's LDS holds only a few stages ahead.  Fewer
+// bytes per unit and a ring that uses all of the LDS for stages in flight (three stages of 48 KiB, four of 32 KiB when
+// the leading cell is diagonal) are what this form is about.  Waves 0-3 own the 64 x 64 quadrants of the first cell, waves
+// 4-7 those of the second; cells below the diagonal never occur (the host pairs the upper triangle's cells into units;
+// by symmetry a cell (R, C) with C < R stands for (C, R)), and a diagonal cell skips its lower-left quadrant and the
+// mirrored tiles of its diagonal quadrants as before.
 // ------------------------------------------------------------------------------------------------
-constexpr int GP_K = 64;
+constexpr int GU_K = 64;         // contraction chunk per stage
+constexpr int GU_LDS = 3 * 3 * GB * GU_K;  // bf16 elements of the ring: 144 KiB
+// Ring stages by the number of panels a stage holds (48, 32 or 16 KiB a stage): what bounds this kernel is how many
+// bytes a CU keeps in flight (a fill that misses L2 takes a few microseconds), so a unit with fewer panels per stage
+// runs further ahead.
+__host__ __device__ constexpr int gu_stages(int npl) { return npl == 3 ? 3 : (npl == 2 ? 4 : 8); }
+constexpr int GU_MAX_BLK = 16;   // T <= 2048
+constexpr int GU_MAX_UNITS = GU_MAX_BLK * (GU_MAX_BLK + 1) / 4 + 1;
+struct GramUnits {
+    int n_units;
+    uint32_t rc[GU_MAX_UNITS];  // R | C1 << 8 | C2 << 16; C2 == 255: the unit has one cell only
+};
 
-template <bool OFFDIAG, int GP_NS>
-__device__ __forceinline__ float gram_pair_ring(const uint16_t* __restrict__ A, const uint16_t* __restrict__ G, int T,
-                                                int d_in, int d_out, int tb, int sb, float bias_term,
-                                                uint16_t (*ring)[2 * GB * GP_K]) {
-    constexpr int PANEL = GB * GP_K;        // bf16 elements of one panel of a stage
-    constexpr int LPP = 4;                  // loads per wave per panel: 8 rows of 8 chunks each
-    constexpr int LPS = OFFDIAG ? 2 * LPP : LPP;
+// NPL: panels filled per stage (1: a diagonal cell alone; 2: diagonal cell + one more, or one off-diagonal cell; 3: two
+// off-diagonal cells).
+template <int NPL>
+__device__ __forceinline__ float gram_unit_ring(const uint16_t* __restrict__ A, const uint16_t* __restrict__ G, int T, int d_in,
+                                                int d_out, int R, int C1, int C2, float bias_term, uint16_t* ring) {
+    constexpr int PANEL = GB * GU_K;   // bf16 elements of one panel of a stage
+    constexpr int STAGE = NPL * PANEL; // ... of one stage: its NPL panels side by side
+    constexpr int GU_NS = gu_stages(NPL);
+    static_assert(GU_NS * STAGE <= GU_LDS, "ring exceeds the LDS array");
+    constexpr int LPP = 2;             // loads per wave per panel: 8 rows of 8 chunks each, 16 loads a panel
+    constexpr int LPS = NPL * LPP;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wr = wave >> 1, wc = wave & 1;
-    const bool active = OFFDIAG || wr <= wc;
-    const bool diagw = !OFFDIAG && wr == wc;  // a diagonal quadrant of a diagonal block: its lower-left tile mirrors the upper-right one
-    const int nchA = d_in / GP_K, nch = nchA + d_out / GP_K;
+    const int cell = wave >> 2, wr = (wave >> 1) & 1, wc = wave & 1;
+    const bool diag0 = C1 == R, two = C2 != 255;
+    // panels of a stage, in this order: rows R; rows C1 when the first cell is off the diagonal; rows C2 when there is a second cell
+    const bool active = cell == 0 ? (!diag0 || wr <= wc) : two;
+    const bool diagw = cell == 0 && diag0 && wr == wc;  // a diagonal quadrant of a diagonal cell: tiles below its diagonal mirror those above
+    const int nchA = d_in / GU_K, nch = nchA + d_out / GU_K;
     auto swz = [](int r) { return (r >> 1) & 7; };
     // rows >= T lie outside the example's byte range and read as zero
     const gram_i32x4 rA = gram_rsrc(A, (uint32_t)((size_t)T * d_in * 2));
     const gram_i32x4 rG = gram_rsrc(G, (uint32_t)((size_t)T * d_out * 2));
-    int voffA[2][LPP], voffG[2][LPP];
-    uint32_t ldsoff[LPP];
+    // load j of this wave fills rows (LPP*wave + j)*8 .. +7 of a panel: lane l -> row + l/8, chunk position l%8
+    const int prow[3] = {R, diag0 ? C2 : C1, C2};  // the rows (in units of 128) of the p-th panel of a stage
+    int voffA[NPL][LPP], voffG[NPL][LPP];
+    uint32_t ldsoff[NPL][LPP];
 #pragma unroll
-    for (int j = 0; j < LPP; ++j) {
-        const int row0 = (LPP * wave + j) * 8, row = row0 + (lane >> 3);
-        const int cg = (lane & 7) ^ swz(row);
-        voffA[0][j] = ((tb * GB + row) * d_in + cg * 8) * 2;
-        voffG[0][j] = ((tb * GB + row) * d_out + cg * 8) * 2;
-        voffA[1][j] = ((sb * GB + row) * d_in + cg * 8) * 2;
-        voffG[1][j] = ((sb * GB + row) * d_out + cg * 8) * 2;
-        ldsoff[j] = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)&ring[0][row0 * GP_K];
-    }
+    for (int p = 0; p < NPL; ++p)
+#pragma unroll
+        for (int j = 0; j < LPP; ++j) {
+            const int row0 = (LPP * wave + j) * 8, row = row0 + (lane >> 3);
+            const int cg = (lane & 7) ^ swz(row);
+            voffA[p][j] = ((prow[p] * GB + row) * d_in + cg * 8) * 2;
+            voffG[p][j] = ((prow[p] * GB + row) * d_out + cg * 8) * 2;
+            ldsoff[p][j] = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)&ring[p * PANEL + row0 * GU_K];
+        }
     int ibuf = 0;
     auto issue = [&](int st) {
-        const bool isA = st < nchA;
-        // past the last chunk the loads still go out (the wait counts stay uniform) but read zeros
-        const int soff = __builtin_amdgcn_readfirstlane(st < nch ? (isA ? st : st - nchA) * GP_K * 2 : 0x7FFFFFF0);
-        auto run = [&](const gram_i32x4& rs, const int (&voff)[2][LPP]) {  // (the choice of the source stays outside the run of loads)
+        // past the last chunk the loads still go out (the wait counts stay uniform): they read the last chunk again, into
+        // a slot that nobody multiplies any more
+        const int stc = st < nch ? st : nch - 1;
+        const bool isA = stc < nchA;
+        const int soff = __builtin_amdgcn_readfirstlane((isA ? stc : stc - nchA) * GU_K * 2);
+        auto run = [&](const gram_i32x4& rs, const int (&voff)[NPL][LPP]) {  // (the choice of the source stays outside the run of loads)
 #pragma unroll
-            for (int pn = 0; pn < (OFFDIAG ? 2 : 1); ++pn)
+            for (int p = 0; p < NPL; ++p)
 #pragma unroll
                 for (int j = 0; j < LPP; ++j)
-                    gram_dma16<false>(rs, __builtin_amdgcn_readfirstlane(ldsoff[j] + (ibuf * 2 * PANEL + pn * PANEL) * 2), voff[pn][j], soff);
+                    gram_dma16<false>(rs, __builtin_amdgcn_readfirstlane(ldsoff[p][j] + ibuf * (STAGE * 2)), voff[p][j], soff);
         };
         if (isA) run(rA, voffA);
         else run(rG, voffG);
-        ibuf = ibuf + 1 == GP_NS ? 0 : ibuf + 1;
+        ibuf = ibuf + 1 == GU_NS ? 0 : ibuf + 1;
     };
-    // operand of the 16x16x32 MFMA (less power per flop than 32x32x16): lane l holds k = 8*(l/16) .. +7 of row l%16 of
-    // its 16-row tile, i.e. 16-byte chunk 4*kk + l/16 of that row; a wave's 64 x 64 quadrant is 4 x 4 such tiles
+    // operand of the 16x16x32 MFMA: lane l holds k = 8*(l/16) .. +7 of row l%16 of its 16-row tile, i.e. 16-byte chunk
+    // 4*kk + l/16 of that row; a wave's 64 x 64 quadrant is 4 x 4 such tiles
+    const int cslot = cell == 0 ? (diag0 ? 0 : 1) : NPL - 1;  // the panel this wave's column fragments come from
     int fr[4], fc[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int r = wr * 64 + u * 16 + (lane & 15), c = wc * 64 + u * 16 + (lane & 15);
-        fr[u] = r * GP_K + (((lane >> 4) ^ swz(r)) << 3);
-        fc[u] = c * GP_K + (((lane >> 4) ^ swz(c)) << 3) + (OFFDIAG ? PANEL : 0);
+        fr[u] = r * GU_K + (((lane >> 4) ^ swz(r)) << 3);
+        fc[u] = c * GU_K + (((lane >> 4) ^ swz(c)) << 3) + cslot * PANEL;
     }
     f32x4_t accA[4][4], accG[4][4];
 #pragma unroll
@@ -442,37 +468,67 @@ __device__ __forceinline__ float gram_pair_ring(const uint16_t* __restrict__ A, 
             for (int r = 0; r < 4; ++r) accA[a][b][r] = accG[a][b][r] = 0.f;
 
 #pragma unroll
-    for (int st = 0; st < GP_NS - 1; ++st) issue(st);
-    int cbuf = 0, s_next = GP_NS - 1;
-    auto stage = [&](f32x4_t (&acc)[4][4]) {
-        // my loads of this chunk have landed (up to three later chunks may be in flight); after the barrier everyone's
-        // have, and everyone is done reading the previous chunk, whose slot the newest chunk overwrites
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((GP_NS - 2) * LPS) : "memory");
-        __syncthreads();
-        issue(s_next++);
-        if (active) {
-            const uint16_t* st = ring[cbuf];
-#pragma unroll
-            for (int kk = 0; kk < GP_K / 32; ++kk) {
-                bf16x8_t a0[4], b0[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int xr = fr[u] ^ ((4 * kk) << 3), xc = fc[u] ^ ((4 * kk) << 3);
-                    a0[u] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(st + xr));
-                    b0[u] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(st + xc));
-                }
-#pragma unroll
-                for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-                    for (int nt = 0; nt < 4; ++nt)
-                        if (!(mt > nt && diagw))
-                            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[mt], b0[nt], acc[mt][nt], 0, 0, 0);
-            }
-        }
-        cbuf = cbuf + 1 == GP_NS ? 0 : cbuf + 1;
+    for (int st = 0; st < GU_NS - 1; ++st) issue(st);
+    int cbuf = 0, s_next = GU_NS - 1;
+    // A stage is two k steps of 32.  Fragment reads run half a stage ahead of the multiplies and across the barrier:
+    // behind the barrier that publishes stage s the wave first asks for the fragments of (s, k step 0), then multiplies
+    // those of (s-1, k step 1), which it already holds, asks for (s, k step 1) into the registers just freed, and
+    // multiplies (s, k step 0).  All eight waves come out of the barrier together; without the step held over, the
+    // matrix pipes would idle behind every barrier until the LDS has served the first reads of all of them.
+    struct Frags {
+        bf16x8_t a[4], b[4];
     };
-    for (int s = 0; s < nchA; ++s) stage(accA);
-    for (int s = nchA; s < nch; ++s) stage(accG);
+    auto read_frags = [&](Frags& f, int kk) {
+        const uint16_t* st = ring + cbuf * STAGE;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int xr = fr[u] ^ ((4 * kk) << 3), xc = fc[u] ^ ((4 * kk) << 3);
+            f.a[u] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(st + xr));
+            f.b[u] = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(st + xc));
+        }
+    };
+    // MODE 0: a wave with nothing to multiply (it still fills its share of every stage), 1: a full quadrant, 2: a diagonal
+    // quadrant (tiles below its diagonal mirror those above and are skipped).  The mode is fixed per wave, so the loops
+    // exist once per mode: a choice inside the loop body would merge the accumulators of its arms after every stage,
+    // which costs the register allocator more than it has.
+    auto all_stages = [&](auto mode_tag) {
+        constexpr int MODE = decltype(mode_tag)::value;
+        auto multiply = [&](f32x4_t (&acc)[4][4], const Frags& f) {
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt)
+                    if (!(MODE == 2 && mt > nt))
+                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.a[mt], f.b[nt], acc[mt][nt], 0, 0, 0);
+        };
+        Frags X, Y;
+        auto stage = [&](f32x4_t (&acc_prev)[4][4], f32x4_t (&acc_cur)[4][4], auto first_tag) {
+            // my loads of this chunk have landed (later chunks may be in flight); after the barrier everyone's have,
+            // and everyone is done reading the chunk before this one, whose slot the newest chunk overwrites
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((GU_NS - 2) * LPS) : "memory");
+            __syncthreads();
+            issue(s_next++);
+            if (MODE != 0) {
+                read_frags(X, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (!decltype(first_tag)::value) multiply(acc_prev, Y);
+                __builtin_amdgcn_sched_barrier(0);
+                read_frags(Y, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                multiply(acc_cur, X);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            cbuf = cbuf + 1 == GU_NS ? 0 : cbuf + 1;
+        };
+        stage(accA, accA, std::true_type{});
+        for (int s = 1; s < nchA; ++s) stage(accA, accA, std::false_type{});
+        stage(accA, accG, std::false_type{});  // the first chunk of G: the step held over still belongs to A
+        for (int s = nchA + 1; s < nch; ++s) stage(accG, accG, std::false_type{});
+        if (MODE != 0) multiply(accG, Y);
+    };
+    if (!active) all_stages(std::integral_constant<int, 0>{});
+    else if (diagw) all_stages(std::integral_constant<int, 2>{});
+    else all_stages(std::integral_constant<int, 1>{});
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing may still be writing LDS past this point
     float sum = 0.f;
 #pragma unroll
@@ -482,38 +538,34 @@ __device__ __forceinline__ float gram_pair_ring(const uint16_t* __restrict__ A, 
 #pragma unroll
             for (int r = 0; r < 4; ++r)
                 sum += (a < b && diagw ? 2.f : 1.f) * ((accA[a][b][r] + bias_term) * accG[a][b][r]);  // skipped tiles hold zeros
-    return sum * (OFFDIAG ? 2.f : (wr == wc ? 1.f : (wr < wc ? 2.f : 0.f)));
+    // a cell off the diagonal counts twice (its mirror image is never formed); in a diagonal cell so does the upper-right quadrant
+    const float weight = !active ? 0.f : ((cell == 0 && diag0) ? (wr == wc ? 1.f : 2.f) : 2.f);
+    return sum * weight;
 }
 
-// out: partials [B][n_layers * npairs], stored.  Workgroup id g -> XCD g % 8; unit (layer, example) u =
-// (g / 8 / npairs) * 8 + g % 8, pair = (g / 8) % npairs.
-template <int GP_NS, int WPC>
-__global__ __launch_bounds__(256, WPC) void gram_pairs_dma_kernel(GramBatch gb, int T, int d_in, int d_out, int has_bias,
-                                                                  int nblk, int npairs, float* __restrict__ out) {
-    __shared__ __attribute__((aligned(16))) uint16_t ring[GP_NS][2 * GB * GP_K];
+// out: partials [B][n_layers * n_units], stored.  Workgroup id g -> XCD g % 8; (layer, example) u = (g / 8 / n_units) * 8 + g % 8,
+// unit = (g / 8) % n_units: the units of one example share an XCD, so that each panel comes from HBM once.
+__global__ __launch_bounds__(512, 1) void gram_units_kernel(GramBatch gb, GramUnits gu, int T, int d_in, int d_out, int has_bias,
+                                                            float* __restrict__ out) {
+    __shared__ __attribute__((aligned(16))) uint16_t ring[GU_LDS];
     const int slot = blockIdx.x >> 3;
-    const int u = (slot / npairs) * 8 + (blockIdx.x & 7);
-    const int pair = slot % npairs;
+    const int u = (slot / gu.n_units) * 8 + (blockIdx.x & 7);
+    const int unit = slot % gu.n_units;
     if (u >= gb.n_layers * gb.B) return;
     const int layer = u / gb.B, i = u - layer * gb.B;
-    int tb = 0, sb = 0;
-    {
-        int p = pair;
-        while (p >= nblk - tb) {  // row tb of the upper triangle holds nblk - tb pairs
-            p -= nblk - tb;
-            ++tb;
-        }
-        sb = tb + p;
-    }
+    const uint32_t rc = gu.rc[unit];
+    const int R = rc & 255, C1 = (rc >> 8) & 255, C2 = (rc >> 16) & 255;
     const uint16_t* A = gb.A[layer] + (size_t)i * T * d_in;
     const uint16_t* G = gb.G[layer] + (size_t)i * T * d_out;
     const float bias_term = has_bias ? 1.f : 0.f;
+    const int npl = 1 + (C1 != R ? 1 : 0) + (C2 != 255 ? 1 : 0);
     float s;
-    if (tb == sb) s = gram_pair_ring<false, GP_NS>(A, G, T, d_in, d_out, tb, sb, bias_term, ring);
-    else s = gram_pair_ring<true, GP_NS>(A, G, T, d_in, d_out, tb, sb, bias_term, ring);
+    if (npl == 3) s = gram_unit_ring<3>(A, G, T, d_in, d_out, R, C1, C2, bias_term, ring);
+    else if (npl == 2) s = gram_unit_ring<2>(A, G, T, d_in, d_out, R, C1, C2, bias_term, ring);
+    else s = gram_unit_ring<1>(A, G, T, d_in, d_out, R, C1, C2, bias_term, ring);
     __syncthreads();  // the ring is free: its first floats serve the reduction
-    const float tot = dp_block_sum<256>(s, reinterpret_cast<float*>(&ring[0][0]));
-    if (threadIdx.x == 0) out[((size_t)i * gb.n_layers + layer) * npairs + pair] = tot;
+    const float tot = dp_block_sum<512>(s, reinterpret_cast<float*>(&ring[0]));
+    if (threadIdx.x == 0) out[((size_t)i * gb.n_layers + layer) * gu.n_units + unit] = tot;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -773,44 +825,70 @@ static dp_status gram_dma_launch(dp_ctx* ctx, const GramBatch& gb, int T, int d_
     return DP_OK;
 }
 
-// The block-pair ring kernel: several 128 x 128 blocks per example, widths multiples of its 64-wide chunk.
-static bool gram_pairs_ok(int T, int d_in, int d_out) {
-    return T > GB && d_in % GP_K == 0 && d_out % GP_K == 0 && d_in > 0 && d_out > 0 &&
+// The upper triangle of an nblk x nblk plane of 128 x 128 cells, paired into units of two cells that share a panel:
+// along each row tb the cells (tb, tb), (tb, tb+1) | (tb, tb+2), (tb, tb+3) | ...; a row with an odd number of cells leaves
+// its last one, (tb, nblk-1), over, and two such leftovers share the panel nblk-1: by symmetry they are the cells
+// (nblk-1, tb1), (nblk-1, tb2) of the row panel nblk-1.  At most one cell stays alone.
+static GramUnits gram_make_units(int nblk) {
+    GramUnits gu;
+    int n = 0, left[GU_MAX_BLK], nleft = 0;
+    for (int tb = 0; tb < nblk; ++tb) {
+        int j = tb;
+        for (; j + 1 < nblk; j += 2) {
+            gu.rc[n++] = (uint32_t)tb | (uint32_t)j << 8 | (uint32_t)(j + 1) << 16;
+        }
+        if (j == nblk - 1) left[nleft++] = tb;
+    }
+    const int last = nblk - 1;
+    int k = nleft;
+    while (k >= 2) {  // the largest leftover may be the diagonal cell (last, last): it leads its unit
+        const int t2 = left[--k], t1 = left[--k];
+        gu.rc[n++] = (uint32_t)last | (uint32_t)(t2 == last ? last : t1) << 8 | (uint32_t)(t2 == last ? t1 : t2) << 16;
+    }
+    if (k == 1) {
+        gu.rc[n++] = (uint32_t)left[0] | (uint32_t)last << 8 | 255u << 16;
+    }
+    gu.n_units = n;
+    return gu;
+}
+
+// The unit kernel: T up to GU_MAX_BLK cells of 128 rows, widths multiples of its 64-wide chunk.
+static bool gram_units_ok(int T, int d_in, int d_out) {
+    return T > GB && T <= GB * GU_MAX_BLK && d_in % GU_K == 0 && d_out % GU_K == 0 && d_in > 0 && d_out > 0 &&
            (size_t)T * (d_in > d_out ? d_in : d_out) * 2 < (1u << 31);
 }
 
-// nl <= GRAM_MAX_BATCH same-shaped layers: partials [B][nl * npairs] through the workspace, added in index order.
-static dp_status gram_pairs_launch(dp_ctx* ctx, const GramBatch& gb, int T, int d_in, int d_out, int has_bias,
+// nl <= GRAM_MAX_BATCH same-shaped layers: partials [B][nl * n_units] through the workspace, added in index order.
+static dp_status gram_units_launch(dp_ctx* ctx, const GramBatch& gb, int T, int d_in, int d_out, int has_bias,
                                    float* sqnorms) {
-    const int nblk = (T + GB - 1) / GB;
-    const long npairs = (long)nblk * (nblk + 1) / 2;
+    const GramUnits gu = gram_make_units((T + GB - 1) / GB);
     const long units = (long)gb.n_layers * gb.B;
-    const long nwg = (units + 7) / 8 * 8 * npairs;
-    if (nwg > 0x7FFFFFFFl || npairs * gb.n_layers > 0x7FFFFFFFl) {
+    const long nwg = (units + 7) / 8 * 8 * gu.n_units;
+    if (nwg > 0x7FFFFFFFl) {
         DP_SET_ERR(ctx, "dp_sqnorms_dense: B * T^2 too large for one launch");
         return DP_ERR_SHAPE;
     }
     dp_ws_alloc ws(ctx);
-    float* part = ws.get<float>((size_t)units * npairs);
+    float* part = ws.get<float>((size_t)units * gu.n_units);
     if (!part) {
-        DP_SET_ERR(ctx, "workspace too small for %ld x %ld Gram partials", units, npairs);
+        DP_SET_ERR(ctx, "workspace too small for %ld x %d Gram partials", units, gu.n_units);
         return DP_ERR_WORKSPACE;
     }
     {
         dp_prof_scope prof(ctx, DP_PROF_GRAM, 2.0 * (double)gb.B * T * ((double)d_in + d_out) * gb.n_layers);
-        hipLaunchKernelGGL((gram_pairs_dma_kernel<2, 2>), dim3((unsigned)nwg), dim3(256), 0, ctx->stream, gb, T, d_in,
-                           d_out, has_bias, nblk, (int)npairs, part);
+        hipLaunchKernelGGL(gram_units_kernel, dim3((unsigned)nwg), dim3(512), 0, ctx->stream, gb, gu, T, d_in, d_out,
+                           has_bias, part);
     }
-    DP_LAUNCH_CHECK(ctx, "gram_pairs_dma");
-    return dpk_finish_partials(ctx, part, gb.B, (int)(npairs * gb.n_layers), sqnorms);
+    DP_LAUNCH_CHECK(ctx, "gram_units");
+    return dpk_finish_partials(ctx, part, gb.B, gu.n_units * gb.n_layers, sqnorms);
 }
 
 dp_status dpk_gram_sqnorms_batched(dp_ctx* ctx, int n_layers, const void* const* A, const void* const* G, dp_dtype dt,
                                    int B, int T, int d_in, int d_out, int has_bias, float* sqnorms) {
-    if (dt == DP_BF16 && gram_pairs_ok(T, d_in, d_out)) {
+    if (dt == DP_BF16 && gram_units_ok(T, d_in, d_out)) {
         // enough layers per launch for a few rounds of workgroups, and partials that fit the workspace
         const int nblk = (T + GB - 1) / GB;
-        const long npairs = (long)nblk * (nblk + 1) / 2;
+        const long npairs = (long)nblk * (nblk + 1) / 2;  // (an upper bound of the units per example)
         int per = GRAM_MAX_BATCH;
         while (per > 1 && ((size_t)per * B * npairs * sizeof(float) > ctx->ws_bytes / 2 ||
                            (long)per * B * npairs > (1l << 22)))
@@ -826,7 +904,7 @@ dp_status dpk_gram_sqnorms_batched(dp_ctx* ctx, int n_layers, const void* const*
             gb.n_layers = nl;
             gb.n_out = 1;
             gb.B = B;
-            dp_status st = gram_pairs_launch(ctx, gb, T, d_in, d_out, has_bias, sqnorms);
+            dp_status st = gram_units_launch(ctx, gb, T, d_in, d_out, has_bias, sqnorms);
             if (st != DP_OK) return st;
         }
         return DP_OK;
@@ -948,7 +1026,7 @@ dp_status dpk_gram_sqnorms(dp_ctx* ctx, const void* A, const void* G, dp_dtype d
         lds_attr_set = true;
     }
     const double bytes = 2.0 * (double)B * T * ((double)d_in + d_out);
-    if (gram_dma_ok(T, d_in, d_out) || (gram_pairs_ok(T, d_in, d_out))) {
+    if (gram_dma_ok(T, d_in, d_out) || gram_units_ok(T, d_in, d_out)) {
         GramBatch gb;
         for (int l = 0; l < GRAM_MAX_BATCH; ++l) {
             gb.A[l] = (const uint16_t*)A;
@@ -958,7 +1036,7 @@ dp_status dpk_gram_sqnorms(dp_ctx* ctx, const void* A, const void* G, dp_dtype d
         gb.n_layers = 1;
         gb.n_out = 1;
         gb.B = B;
-        if (T > GB) return gram_pairs_launch(ctx, gb, T, d_in, d_out, has_bias, sqnorms);
+        if (T > GB) return gram_units_launch(ctx, gb, T, d_in, d_out, has_bias, sqnorms);
         return gram_dma_launch(ctx, gb, T, d_in, d_out, has_bias, sqnorms, bytes);
     }
     if (npairs == 1) {

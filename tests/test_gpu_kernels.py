@@ -219,7 +219,7 @@ DENSE_SHAPES = [
     ("bf16", 9, 300, 264, 128),   # 3 x 3 Gram blocks with a ragged last block, 9 examples over 8 XCD lanes
     ("bf16", 2, 512, 128, 1024),  # 4 x 4 Gram blocks
     ("bf16", 1, 1, 8, 8),         # T = 1
-    ("bf16", 3, 300, 128, 192),   # 3 x 3 blocks, ragged last block, widths the block-pair ring kernel takes
+    ("bf16", 3, 300, 128, 192),   # 3 x 3 blocks, ragged last block, widths the ring-fed unit kernel takes
     ("bf16", 2, 129, 64, 64),     # one row into the second block
     ("bf16", 11, 256, 320, 64),   # 2 x 2 blocks, 11 examples over the 8 XCD lanes
     ("bf16", 4, 20, 1032, 72),    # T <= 32: the one-tile kernel, widths that end inside a 128-column chunk
@@ -227,6 +227,9 @@ DENSE_SHAPES = [
     ("bf16", 2, 33, 128, 64),     # one row more: back to the 128-row kernels
     ("bf16", 5, 20, 1984, 192),   # T <= 32, widths multiples of 64: the ring-fed one-tile kernel, more stages than the ring holds
     ("bf16", 3, 32, 64, 128),     # ... and fewer
+    ("bf16", 2, 640, 64, 128),    # 5 x 5 Gram cells: units of every kind, among them an off-diagonal cell on its own
+    ("bf16", 9, 1100, 64, 64),    # 9 x 9 cells with a ragged last one: units formed from the rows' leftover cells
+    ("bf16", 1, 2100, 64, 64),    # 17 x 17 cells: past the unit kernel's table, the register-staged kernel's block pairs
 ]
 
 
