@@ -58,7 +58,8 @@ typedef enum {
     DP_ERR_SHAPE = -2,     /* a size is negative, or not a multiple the dtype requires */
     DP_ERR_DTYPE = -3,     /* unknown dp_dtype / dp_path value */
     DP_ERR_ALIGN = -4,     /* pointer alignment */
-    DP_ERR_VALUE = -5,     /* C <= 0, sigma < 0, batch_size == 0, step == 0, beta outside [0,1), eps < 0 ... */
+    DP_ERR_VALUE = -5,     /* C <= 0, sigma < 0, batch_size == 0, step == 0, beta outside [0,1), eps < 0 ...; from dp_sync: a
+                              per-example squared norm that pass 2 read was NaN or had overflowed fp32 */
     DP_ERR_INDEX = -6,     /* a token id outside [0, V) was met on the device (reported by dp_sync) */
     DP_ERR_WORKSPACE = -7, /* the context's workspace is too small for this call */
     DP_ERR_HIP = -8        /* a HIP runtime call failed; dp_last_error has the text */
@@ -70,7 +71,8 @@ typedef enum {
 dp_status dp_create(dp_ctx** out, void* hip_stream, size_t workspace_bytes);
 /* Synchronise the stream, then free the workspace and the context. */
 dp_status dp_destroy(dp_ctx* ctx);
-/* hipStreamSynchronize, then fetch-and-clear the device error word: DP_OK or DP_ERR_INDEX / DP_ERR_HIP. */
+/* hipStreamSynchronize, then fetch-and-clear the device error word: DP_OK, DP_ERR_INDEX (a token id outside
+ * [0, V)), DP_ERR_VALUE (a non-finite squared norm met by pass 2; DP_ERR_INDEX wins if both occurred) or DP_ERR_HIP. */
 dp_status dp_sync(dp_ctx* ctx);
 const char* dp_status_str(dp_status s);
 /* Text of the last error of this context; static storage inside the context. */
@@ -131,6 +133,11 @@ dp_status dp_sqnorms_embedding(dp_ctx* ctx, const int32_t* ids, const void* G, d
 /* ---------------------------------------------------------------------------------------------------
  * Pass 2: clip-weighted sums.  With c_i = min(1, C / sqrt(sqnorms[i])) (c_i = 1 where sqnorms[i] == 0),
  * each call ADDS sum_i c_i * (example i's gradient of this layer) to the caller's fp32 sum buffers.
+ * Squared norms live in fp32: an example whose gradient norm exceeds about 1.8e19 overflows it.  Such a value (inf, or
+ * NaN) has no clip factor: on every path alike the factor is NaN, the sums that example enters become NaN, and the next
+ * dp_sync returns DP_ERR_VALUE - nothing is dropped or passed through unclipped silently.  Finite norms up to the
+ * fp32 range are handled exactly like any other (the accumulators of the matrix-core path are rescaled by ratios of
+ * neighbouring factors, at most 1.8e19 / C, and hold at most B times the largest norm: both inside the fp32 range).
  * The caller zeroes the sum buffers once per mega-batch; repeated calls over micro-batches accumulate.
  * sqnorms must hold the finished pass-1 result of the SAME micro-batch.
  * ------------------------------------------------------------------------------------------------- */
@@ -181,9 +188,12 @@ dp_status dp_clip_accumulate_embedding(dp_ctx* ctx, const int32_t* ids, const vo
                                        int d, int V, float C, const float* sqnorms, float* sum_E);
 
 /* The position-embedding case of dp_clip_accumulate_embedding: ids[i,t] = t for every example, so
- * sum_E[t, :] += sum_i c_i G[i,t,:] for t < T (sum_E holds at least T rows of width d; the rows from T on are not
- * touched).  No ids, no sort: one weighted sum over the B examples.  Same result as the general entry point
- * up to fp32 summation order. */
+ * sum_E[t, :] += sum_i c_i G[i,t,:] for t < T.  No ids, no sort: one weighted sum over the B examples.  Same result as
+ * the general entry point up to fp32 summation order.
+ * PRECONDITION: the table behind sum_E has at least T rows of width d (T <= the model's maximum position).  The
+ * call takes no table height and cannot check this: it writes rows 0 .. T-1 and touches no row from T on, so a
+ * table shorter than T rows is overrun.  A caller that cannot guarantee it uses dp_clip_accumulate_embedding with
+ * explicit ids and V, which range-checks every id. */
 dp_status dp_clip_accumulate_positions(dp_ctx* ctx, const void* G, dp_dtype dtype, int B, int T, int d, float C,
                                        const float* sqnorms, float* sum_E);
 

@@ -435,8 +435,11 @@ __global__ __launch_bounds__(512) void wgemm_dma16_kernel(WgemmBatchArgs b) {
     // one unit's tile grid (mode 2), so that its L2 sees each operand row and column about once.
     int tile, unit;
     if (a.xcd_map == 1) {
+        // nunits is a multiple of 8: XCD x works through the CONSECUTIVE units x * nunits/8 ... (x+1) * nunits/8 - 1.  With
+        // 16-tile units two of them run on an XCD at a time, so neighbouring layers that read the same input (the query
+        // and key projections of a block, when the caller hands them one tensor) fetch its panels from HBM once.
         const int g = blockIdx.x, slot = g >> 3;
-        unit = (slot / ntiles) * 8 + (g & 7);
+        unit = (g & 7) * (nunits >> 3) + slot / ntiles;
         if (unit >= nunits) return;
         // An XCD runs about 32 workgroups at a time: walk the unit's tile grid in rect_m x rect_n rectangles so
         // that those 32 share as many operand columns as possible (rect 1 x 1 = plain row-major order).
