@@ -271,11 +271,18 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gram_dma_kernel(GramBatch gb,
         ldsoff[j] = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint16_t*)&ring[0][row0 * GDK];
     }
     int ibuf = 0;  // buffer of the next stage to issue
+    const int rotA = i % nchA, rotG = i % nchG1;
     auto issue = [&](int st) {
         const bool isA = st < nchA;
         const int cgi = st - nchA;                                             // chunk index over all output gradients
         const int which = cgi >= 2 * nchG1 ? 2 : (cgi >= nchG1 ? 1 : 0);       // which of the (up to three) tensors
-        const int soff = __builtin_amdgcn_readfirstlane((isA ? st : cgi - which * nchG1) * GDK * 2);
+        // The chunks of a tensor are taken in an order rotated by the example index: the contraction does not care, and
+        // workgroups that start together (and advance in step) then read different column ranges at any moment.  With one
+        // order for all, every workgroup reads the same 256 bytes of rows that lie 2-8 KiB apart, i.e. the same few memory
+        // channels (+12 % bandwidth on 1024 x 4096 layers, +2 % on 1024 x 1024).
+        const int c0 = isA ? st : cgi - which * nchG1, nc = isA ? nchA : nchG1, r0 = isA ? rotA : rotG;
+        const int cr = c0 + r0 >= nc ? c0 + r0 - nc : c0 + r0;
+        const int soff = __builtin_amdgcn_readfirstlane(cr * GDK * 2);
         // one choice of the source per stage, then a straight run of loads (every descriptor is a variable of its own
         // and stays in scalar registers; with the choice inside the loop each load of an output-gradient stage went
         // through a chain of branches)
@@ -437,6 +444,8 @@ __device__ __forceinline__ float gram_unit_ring(const uint16_t* __restrict__ A, 
         // a slot that nobody multiplies any more
         const int stc = st < nch ? st : nch - 1;
         const bool isA = stc < nchA;
+        // (rotating the chunk order by the example index, which pays in gram_dma_kernel, costs 1-2 % here: the units of an
+        // example need their panels at the same time, and any order serves that)
         const int soff = __builtin_amdgcn_readfirstlane((isA ? stc : stc - nchA) * GU_K * 2);
         auto run = [&](const gram_i32x4& rs, const int (&voff)[NPL][LPP]) {  // (the choice of the source stays outside the run of loads)
 #pragma unroll
