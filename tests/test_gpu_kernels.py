@@ -230,6 +230,7 @@ DENSE_SHAPES = [
     ("bf16", 2, 640, 64, 128),    # 5 x 5 Gram cells: units of every kind, among them an off-diagonal cell on its own
     ("bf16", 9, 1100, 64, 64),    # 9 x 9 cells with a ragged last one: units formed from the rows' leftover cells
     ("bf16", 1, 2100, 64, 64),    # 17 x 17 cells: past the unit kernel's table, the register-staged kernel's block pairs
+    ("bf16", 2, 2048, 64, 128),   # 16 x 16 cells: the unit kernel's largest plane (68 units, its table full)
 ]
 
 
