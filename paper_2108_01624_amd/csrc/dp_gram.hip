@@ -379,7 +379,7 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gram_dma_kernel(GramBatch gb,
 // registers, no LDS store instructions), as in the kernel above.  At this size the contraction, not HBM, is the bound
 // (T flop per byte against ~310 at the machine balance).  A workgroup of 8 waves (two per SIMD, one workgroup per CU) works on a
 // UNIT of two 128 x 128 cells of the example's T x T plane that share their row panel R: cells (R, C1) and (R, C2).  The
-// row panel is filled into LDS once for both cells, so a unit fills three panels where two block pairs fill four, and
+// row panel is filled into LDS once for both cells, so a unit fills three panels where two workgroups with a cell each fill four, and
 // with the leading cell on the diagonal (C1 == R) two; over the upper triangle of a 4 x 4 plane that is 11 panel fills
 // instead of 16.  The fills, not the matrix instructions, bound this kernel: the units of an example run on different
 // CUs at different times, most fills miss L2 and take microseconds, and a CU's LDS holds only a few stages ahead.  Fewer
