@@ -38,6 +38,9 @@ def parse():
     ap.add_argument("--tied-pred", type=int, default=0,
                     help="comparison run: the token table (padded to 30,528 rows) is also the output projection of this many "
                          "prediction slots per example (tied weights); the metric's workload has none")
+    ap.add_argument("--full-embeddings", action="store_true",
+                    help="comparison run: the embedding stage in full (token-type table with 2 rows and the LayerNorm after the "
+                         "sum of the three lookups, which share one output gradient): 334,092,288 parameters")
     ap.add_argument("--batch", type=int, default=0, help="override the micro-batch size (parity/debug only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-examples", type=int, default=0, help="examples in the oracle sample (0 = auto)")
@@ -119,6 +122,10 @@ def main():
         if args.workload == "C2":
             raise SystemExit("--tied-pred needs a workload with a token table (C3, C4, C5)")
         manifest = syn.bert_manifest(24, 1024, 4096, 30528, 512, tied_pred=args.tied_pred)
+    if args.full_embeddings:
+        if args.workload == "C2" or args.tied_pred:
+            raise SystemExit("--full-embeddings needs a workload with embedding tables (C3, C4, C5) and no --tied-pred")
+        manifest = syn.bert_manifest(24, 1024, 4096, 30522, 512, type_vocab=2)
     upd = syn.CONFIGS["C4"]  # update hyper-parameters of the mega-batch workload
     t_gen = time.perf_counter()
     layers = syn.device_layer_inputs(manifest, B, T, dtype=cfg["dtype"], act_std=cfg["act_std"],
@@ -238,7 +245,7 @@ def main():
                                f"micro-batch B={B}, seq T={T}, bf16 inputs / fp32 accumulation, C={cfg['C']}; "
                                f"one step = norms + clip-accumulate over all layers + noise/AdamW over all params"
                                if args.workload != "C2" else f"C2: BERT-Base-shaped stack, B={B}, T={T}",
-                   "params": int(run.P), "micro_batch": B, "micro_batches_per_step": n_micro, "seq_len": T, "norm_path": args.path, "shared_qkv_input": bool(args.share_qkv), "tied_prediction_slots": int(args.tied_pred),
+                   "params": int(run.P), "micro_batch": B, "micro_batches_per_step": n_micro, "seq_len": T, "norm_path": args.path, "shared_qkv_input": bool(args.share_qkv), "tied_prediction_slots": int(args.tied_pred), "full_embedding_stage": bool(args.full_embeddings),
                    "input_bytes": int(in_bytes)},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
