@@ -381,19 +381,19 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gram_dma_kernel(GramBatch gb,
 // UNIT of two 128 x 128 cells of the example's T x T plane that share their row panel R: cells (R, C1) and (R, C2).  The
 // row panel is filled into LDS once for both cells, so a unit fills three panels where two workgroups with a cell each fill four, and
 // with the leading cell on the diagonal (C1 == R) two; over the upper triangle of a 4 x 4 plane that is 11 panel fills
-// instead of 16.  The fills, not the matrix instructions, bound this kernel: the units of an example run on different
-// CUs at different times, most fills miss L2 and take microseconds, and a CU's LDS holds only a few stages ahead.  Fewer
-// bytes per unit and a ring that uses all of the LDS for stages in flight (three stages of 48 KiB, four of 32 KiB when
-// the leading cell is diagonal) are what this form is about.  Waves 0-3 own the 64 x 64 quadrants of the first cell, waves
+// instead of 16.  The LDS, not the matrix pipe, bounds this kernel: per stage it serves 128 KB of fragment reads and takes
+// up to 48 KB of fills against 1024 cycles of MFMAs, and a fill that comes from HBM (every panel does once; the units of an
+// example share it through L2) takes about as long as the two stages a CU's LDS holds ahead.  Fewer fill bytes per unit
+// and a ring that uses all of the LDS for stages in flight (three stages of 48 KiB, four of 32 KiB when the leading cell
+// is diagonal) are what this form is about.  Waves 0-3 own the 64 x 64 quadrants of the first cell, waves
 // 4-7 those of the second; cells below the diagonal never occur (the host pairs the upper triangle's cells into units;
 // by symmetry a cell (R, C) with C < R stands for (C, R)), and a diagonal cell skips its lower-left quadrant and the
 // mirrored tiles of its diagonal quadrants as before.
 // ------------------------------------------------------------------------------------------------
 constexpr int GU_K = 64;         // contraction chunk per stage
 constexpr int GU_LDS = 3 * 3 * GB * GU_K;  // bf16 elements of the ring: 144 KiB
-// Ring stages by the number of panels a stage holds (48, 32 or 16 KiB a stage): what bounds this kernel is how many
-// bytes a CU keeps in flight (a fill that misses L2 takes a few microseconds), so a unit with fewer panels per stage
-// runs further ahead.
+// Ring stages by the number of panels a stage holds (48, 32 or 16 KiB a stage): a fill that misses L2 takes a few
+// microseconds, so a unit with fewer panels per stage runs further ahead.
 __host__ __device__ constexpr int gu_stages(int npl) { return npl == 3 ? 3 : (npl == 2 ? 4 : 8); }
 constexpr int GU_MAX_BLK = 16;   // T <= 2048
 constexpr int GU_MAX_UNITS = GU_MAX_BLK * (GU_MAX_BLK + 1) / 4 + 1;
