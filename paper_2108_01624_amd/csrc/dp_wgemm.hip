@@ -419,7 +419,7 @@ __device__ __forceinline__ int swz16(int row) { return ((row & 3) << 2) | (((row
 
 template <int EPI>
 __global__ __launch_bounds__(512) void wgemm_dma16_kernel(WgemmBatchArgs b) {
-    constexpr int MI = 8, NI = 4, MH = 4, WVN = 4, NT = 512;  // 16 x 16 tiles per wave: MI x NI, worked on in two halves of MH tile rows
+    constexpr int MI = 8, NI = 4, MH = 4, WVN = 4;  // 16 x 16 tiles per wave: MI x NI, worked on in two halves of MH tile rows
     constexpr int WM = 128, WN = 64, BM = 256, BN = 256;
     constexpr int LPS = 4;  // LDS-filling loads per wave per stage (2 for A, 2 for G)
     __shared__ __attribute__((aligned(16))) uint16_t As[DMA_NS][BK * BM];
@@ -559,8 +559,7 @@ __global__ __launch_bounds__(512) void wgemm_dma16_kernel(WgemmBatchArgs b) {
     for (int j = 0; j < NI; ++j) fg[j] = read_frag(&Gs[buf][foffG[j]], BN);
 
     // One loop iteration = one stage = one barrier.
-    int my = 0;      // the stage being multiplied; stages >= nsteps hold zeros
-    int duty_ctr = 0;  // my % duty_mod
+    int duty_ctr = 0;  // (index of the stage being multiplied) % duty_mod
     const int spe = a.T / BK;                                  // stages per example (>= 2)
     int ex_run = (int)((uint32_t)k_lo / (uint32_t)a.T);        // the next example to start (row splits begin on examples)
     const int nex = (int)(a.K / a.T);
@@ -666,7 +665,6 @@ __global__ __launch_bounds__(512) void wgemm_dma16_kernel(WgemmBatchArgs b) {
         ++s_issue;
         ibuf = ibuf + 1 == DMA_NS ? 0 : ibuf + 1;
         buf = buf1;
-        ++my;
     };
     // The unit's rows are whole examples (the host aligns row splits to examples), at least two stages each.
     const int n_ex_unit = nsteps / spe;
