@@ -95,7 +95,7 @@ dp_status dp_sqnorms_dense(dp_ctx* ctx, const void* A, const void* G, dp_dtype d
 /* n_layers dense layers of one shape in one call: the result is that of n_layers calls of dp_sqnorms_dense
  * with the same arguments (each layer's norms added to sqnorms[i], layers in index order).  On the Gram path
  * with widths that are multiples of 64 the layers share launches of up to 16 layers, which keeps the memory
- * pipeline full across examples; their per-layer norms (for T > 128: per layer and unit of two 128 x 128 cells of the T x T plane) pass
+ * pipeline full across examples; their per-layer norms (for T > 128: per layer and unit of two or three 128 x 128 cells of the T x T plane) pass
  * through the library workspace and are added in a fixed order (DP_ERR_WORKSPACE if they do not fit).
  * A, G are HOST arrays of n_layers device pointers, read during the call only. */
 dp_status dp_sqnorms_dense_batched(dp_ctx* ctx, int n_layers, const void* const* A, const void* const* G, dp_dtype dtype,

@@ -376,19 +376,24 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gram_dma_kernel(GramBatch gb,
 
 // ------------------------------------------------------------------------------------------------
 // T > 128, widths multiples of 64: the panels of a 64-wide contraction chunk go straight into an LDS ring (no staging
-// registers, no LDS store instructions), as in the kernel above.  At this size the contraction, not HBM, is the bound
-// (T flop per byte against ~310 at the machine balance).  A workgroup of 8 waves (two per SIMD, one workgroup per CU) works on a
-// UNIT of two 128 x 128 cells of the example's T x T plane that share their row panel R: cells (R, C1) and (R, C2).  The
-// row panel is filled into LDS once for both cells, so a unit fills three panels where two workgroups with a cell each fill four, and
-// with the leading cell on the diagonal (C1 == R) two; over the upper triangle of a 4 x 4 plane that is 11 panel fills
-// instead of 16.  The LDS, not the matrix pipe, bounds this kernel: per stage it serves 128 KB of fragment reads and takes
-// up to 48 KB of fills against 1024 cycles of MFMAs, and a fill that comes from HBM (every panel does once; the units of an
-// example share it through L2) takes about as long as the two stages a CU's LDS holds ahead.  Fewer fill bytes per unit
-// and a ring that uses all of the LDS for stages in flight (three stages of 48 KiB, four of 32 KiB when the leading cell
-// is diagonal) are what this form is about.  Waves 0-3 own the 64 x 64 quadrants of the first cell, waves
-// 4-7 those of the second; cells below the diagonal never occur (the host pairs the upper triangle's cells into units;
-// by symmetry a cell (R, C) with C < R stands for (C, R)), and a diagonal cell skips its lower-left quadrant and the
-// mirrored tiles of its diagonal quadrants as before.
+// registers, no LDS store instructions), as in the kernel above.  At this size the contraction, not HBM, is the bound on
+// paper (T flop per byte against ~310 at the machine balance); in practice it is the path that fills the LDS (a CU takes
+// about 46 bytes per clock from L2 this way, and a panel costs 16 KiB per stage) together with the matrix pipe.  A
+// workgroup of 8 waves (two per SIMD, one workgroup per CU) works on a UNIT of cells of the example's T x T plane, cut into
+// 128 x 128 cells of which only the upper triangle is formed (by symmetry a cell (R, C) with C < R stands for (C, R)):
+//  * a DIAGONAL BLOCK: the three cells (a, a), (a, b), (b, b) of two neighbouring panels a, b = a + 1 - two panel fills
+//    for three cells.  The two diagonal cells need only the tiles on and above their diagonals, so the block has 136
+//    tiles of 16 x 16 where two full cells have 128, and they fit the same registers: cut into 64-wide strips the block
+//    is a 4 x 4 triangle of quadrants; waves 0-5 take the six quadrants off the diagonal (16 tiles each), waves 6 and 7
+//    two diagonal quadrants each (2 x 10 tiles; both operands of such a quadrant are the same fragments).
+//  * a ROW PAIR: two cells (R, C1), (R, C2) that share their row panel R, which is filled once for both: three panel fills
+//    where two workgroups with a cell each fill four (two when the leading cell is the diagonal one, C1 == R).  Waves 0-3
+//    own the 64 x 64 quadrants of the first cell, waves 4-7 those of the second; a leading diagonal cell skips its
+//    lower-left quadrant and the mirrored tiles of its diagonal quadrants.
+// Over the upper triangle of a 4 x 4 plane that is 2 blocks and 2 row pairs: 10 panel fills and 4 workgroups where a
+// workgroup per cell needs 16 and 10.  A ring that uses all of the LDS for stages in flight (three stages of 48 KiB
+// for three panels, four of 32 KiB for two) covers the latency of the fills: every panel comes from HBM once, the units
+// of an example share it through L2.
 // ------------------------------------------------------------------------------------------------
 constexpr int GU_K = 64;         // contraction chunk per stage
 constexpr int GU_LDS = 3 * 3 * GB * GU_K;  // bf16 elements of the ring: 144 KiB
@@ -399,14 +404,16 @@ constexpr int GU_MAX_BLK = 16;   // T <= 2048
 constexpr int GU_MAX_UNITS = GU_MAX_BLK * (GU_MAX_BLK + 1) / 4 + 1;
 struct GramUnits {
     int n_units;
-    uint32_t rc[GU_MAX_UNITS];  // R | C1 << 8 | C2 << 16; C2 == 255: the unit has one cell only
+    // row pair: R | C1 << 8 | C2 << 16 (C2 == 255: the unit has one cell only); diagonal block of panels a, b: a | a << 8 | b << 16 | 1 << 24
+    uint32_t rc[GU_MAX_UNITS];
 };
 
-// NPL: panels filled per stage (1: a diagonal cell alone; 2: diagonal cell + one more, or one off-diagonal cell; 3: two
-// off-diagonal cells).
-template <int NPL>
+// NPL: panels filled per stage (1: a diagonal cell alone; 2: a diagonal block, a diagonal cell + one more of its row, or
+// one off-diagonal cell; 3: two off-diagonal cells).  BLK: the unit is a diagonal block (cells (R, R), (R, C2), (C2, C2)).
+template <int NPL, bool BLK>
 __device__ __forceinline__ float gram_unit_ring(const uint16_t* __restrict__ A, const uint16_t* __restrict__ G, int T, int d_in,
                                                 int d_out, int R, int C1, int C2, float bias_term, uint16_t* ring) {
+    static_assert(!BLK || NPL == 2, "a diagonal block has two panels");
     constexpr int PANEL = GB * GU_K;   // bf16 elements of one panel of a stage
     constexpr int STAGE = NPL * PANEL; // ... of one stage: its NPL panels side by side
     constexpr int GU_NS = gu_stages(NPL);
@@ -417,8 +424,9 @@ __device__ __forceinline__ float gram_unit_ring(const uint16_t* __restrict__ A, 
     const int cell = wave >> 2, wr = (wave >> 1) & 1, wc = wave & 1;
     const bool diag0 = C1 == R, two = C2 != 255;
     // panels of a stage, in this order: rows R; rows C1 when the first cell is off the diagonal; rows C2 when there is a second cell
-    const bool active = cell == 0 ? (!diag0 || wr <= wc) : two;
-    const bool diagw = cell == 0 && diag0 && wr == wc;  // a diagonal quadrant of a diagonal cell: tiles below its diagonal mirror those above
+    const bool active = BLK || (cell == 0 ? (!diag0 || wr <= wc) : two);
+    const bool diagw = !BLK && cell == 0 && diag0 && wr == wc;  // a diagonal quadrant of a diagonal cell: tiles below its diagonal mirror those above
+    const bool twodiag = BLK && wave >= 6;                      // two diagonal quadrants of a diagonal block
     const int nchA = d_in / GU_K, nch = nchA + d_out / GU_K;
     auto swz = [](int r) { return (r >> 1) & 7; };
     // rows >= T lie outside the example's byte range and read as zero
@@ -459,22 +467,23 @@ __device__ __forceinline__ float gram_unit_ring(const uint16_t* __restrict__ A, 
         ibuf = ibuf + 1 == GU_NS ? 0 : ibuf + 1;
     };
     // operand of the 16x16x32 MFMA: lane l holds k = 8*(l/16) .. +7 of row l%16 of its 16-row tile, i.e. 16-byte chunk
-    // 4*kk + l/16 of that row; a wave's 64 x 64 quadrant is 4 x 4 such tiles
-    const int cslot = cell == 0 ? (diag0 ? 0 : 1) : NPL - 1;  // the panel this wave's column fragments come from
+    // 4*kk + l/16 of that row; a wave's 64 x 64 quadrant is 4 x 4 such tiles.  The 64-row strip its row fragments come
+    // from is (panel rslot, half rhalf), that of its column fragments (cslot, chalf).  In a diagonal block the four strips
+    // of the two panels are numbered 0..3; wave w < 6 has the quadrant (strip SR[w], strip SC[w]) above the diagonal,
+    // waves 6 and 7 the diagonal quadrants of the strips (0, 1) and (2, 3): their "row" fragments are strip SR and their
+    // "column" fragments strip SC, each multiplied with itself.
+    int rslot = 0, rhalf = wr, cslot = cell == 0 ? (diag0 ? 0 : 1) : NPL - 1, chalf = wc;
+    if (BLK) {
+        const int sr = (0x20211000u >> (4 * wave)) & 15, sc = (0x31332321u >> (4 * wave)) & 15;
+        rslot = sr >> 1, rhalf = sr & 1, cslot = sc >> 1, chalf = sc & 1;
+    }
     int fr[4], fc[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-        const int r = wr * 64 + u * 16 + (lane & 15), c = wc * 64 + u * 16 + (lane & 15);
-        fr[u] = r * GU_K + (((lane >> 4) ^ swz(r)) << 3);
+        const int r = rhalf * 64 + u * 16 + (lane & 15), c = chalf * 64 + u * 16 + (lane & 15);
+        fr[u] = r * GU_K + (((lane >> 4) ^ swz(r)) << 3) + rslot * PANEL;
         fc[u] = c * GU_K + (((lane >> 4) ^ swz(c)) << 3) + cslot * PANEL;
     }
-    f32x4_t accA[4][4], accG[4][4];
-#pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) accA[a][b][r] = accG[a][b][r] = 0.f;
 
 #pragma unroll
     for (int st = 0; st < GU_NS - 1; ++st) issue(st);
@@ -487,6 +496,9 @@ __device__ __forceinline__ float gram_unit_ring(const uint16_t* __restrict__ A, 
     struct Frags {
         bf16x8_t a[4], b[4];
     };
+    struct Acc {
+        f32x4_t t[4][4], t2[4][4];  // t2: the second diagonal quadrant of MODE 3 (never touched otherwise)
+    };
     auto read_frags = [&](Frags& f, int kk) {
         const uint16_t* st = ring + cbuf * STAGE;
 #pragma unroll
@@ -497,21 +509,36 @@ __device__ __forceinline__ float gram_unit_ring(const uint16_t* __restrict__ A, 
         }
     };
     // MODE 0: a wave with nothing to multiply (it still fills its share of every stage), 1: a full quadrant, 2: a diagonal
-    // quadrant (tiles below its diagonal mirror those above and are skipped).  The mode is fixed per wave, so the loops
-    // exist once per mode: a choice inside the loop body would merge the accumulators of its arms after every stage,
-    // which costs the register allocator more than it has.
-    auto all_stages = [&](auto mode_tag) {
+    // quadrant (tiles below its diagonal mirror those above and are skipped), 3: two diagonal quadrants.  The mode is fixed
+    // per wave, so the loops exist once per mode, each with accumulators of its own and the final sum inside: a choice
+    // inside the loop body would merge the accumulators of its arms after every stage, which costs the register allocator
+    // more than it has.
+    auto all_stages = [&](auto mode_tag) -> float {
         constexpr int MODE = decltype(mode_tag)::value;
-        auto multiply = [&](f32x4_t (&acc)[4][4], const Frags& f) {
+        Acc accA, accG;
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) accA.t[a][b][r] = accG.t[a][b][r] = accA.t2[a][b][r] = accG.t2[a][b][r] = 0.f;
+        auto multiply = [&](Acc& acc, const Frags& f) {
 #pragma unroll
             for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-                for (int nt = 0; nt < 4; ++nt)
-                    if (!(MODE == 2 && mt > nt))
-                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.a[mt], f.b[nt], acc[mt][nt], 0, 0, 0);
+                for (int nt = 0; nt < 4; ++nt) {
+                    if (MODE == 3) {
+                        if (mt <= nt) {
+                            acc.t[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.a[mt], f.a[nt], acc.t[mt][nt], 0, 0, 0);
+                            acc.t2[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.b[mt], f.b[nt], acc.t2[mt][nt], 0, 0, 0);
+                        }
+                    } else if (!(MODE == 2 && mt > nt)) {
+                        acc.t[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.a[mt], f.b[nt], acc.t[mt][nt], 0, 0, 0);
+                    }
+                }
         };
         Frags X, Y;
-        auto stage = [&](f32x4_t (&acc_prev)[4][4], f32x4_t (&acc_cur)[4][4], auto first_tag) {
+        auto stage = [&](Acc& acc_prev, Acc& acc_cur, auto first_tag) {
             // my loads of this chunk have landed (later chunks may be in flight); after the barrier everyone's have,
             // and everyone is done reading the chunk before this one, whose slot the newest chunk overwrites
             asm volatile("s_waitcnt vmcnt(%0)" ::"n"((GU_NS - 2) * LPS) : "memory");
@@ -534,21 +561,33 @@ __device__ __forceinline__ float gram_unit_ring(const uint16_t* __restrict__ A, 
         stage(accA, accG, std::false_type{});  // the first chunk of G: the step held over still belongs to A
         for (int s = nchA + 1; s < nch; ++s) stage(accG, accG, std::false_type{});
         if (MODE != 0) multiply(accG, Y);
+        float sum = 0.f;
+        if (MODE != 0) {
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        // in a diagonal quadrant the tiles above the diagonal stand for their mirror images too; skipped tiles hold zeros
+                        const float w = (MODE >= 2 && a < b) ? 2.f : 1.f;
+                        sum += w * ((accA.t[a][b][r] + bias_term) * accG.t[a][b][r]);
+                        if (MODE == 3) sum += w * ((accA.t2[a][b][r] + bias_term) * accG.t2[a][b][r]);
+                    }
+        }
+        return sum;
     };
-    if (!active) all_stages(std::integral_constant<int, 0>{});
-    else if (diagw) all_stages(std::integral_constant<int, 2>{});
-    else all_stages(std::integral_constant<int, 1>{});
+    float sum;
+    if (!active) sum = all_stages(std::integral_constant<int, 0>{});
+    else if (twodiag) sum = all_stages(std::integral_constant<int, 3>{});
+    else if (diagw) sum = all_stages(std::integral_constant<int, 2>{});
+    else sum = all_stages(std::integral_constant<int, 1>{});
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // nothing may still be writing LDS past this point
-    float sum = 0.f;
-#pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                sum += (a < b && diagw ? 2.f : 1.f) * ((accA[a][b][r] + bias_term) * accG[a][b][r]);  // skipped tiles hold zeros
-    // a cell off the diagonal counts twice (its mirror image is never formed); in a diagonal cell so does the upper-right quadrant
-    const float weight = !active ? 0.f : ((cell == 0 && diag0) ? (wr == wc ? 1.f : 2.f) : 2.f);
+    // a quadrant off the diagonal of the plane counts twice (its mirror image is never formed): every quadrant of a cell off
+    // the diagonal, the upper-right quadrant of a diagonal cell, and the six quadrants above the diagonal of a diagonal block
+    float weight;
+    if (BLK) weight = twodiag ? 1.f : 2.f;
+    else weight = !active ? 0.f : ((cell == 0 && diag0) ? (wr == wc ? 1.f : 2.f) : 2.f);
     return sum * weight;
 }
 
@@ -564,14 +603,16 @@ __global__ __launch_bounds__(512, 1) void gram_units_kernel(GramBatch gb, GramUn
     const int layer = u / gb.B, i = u - layer * gb.B;
     const uint32_t rc = gu.rc[unit];
     const int R = rc & 255, C1 = (rc >> 8) & 255, C2 = (rc >> 16) & 255;
+    const bool blk = (rc >> 24) & 1;
     const uint16_t* A = gb.A[layer] + (size_t)i * T * d_in;
     const uint16_t* G = gb.G[layer] + (size_t)i * T * d_out;
     const float bias_term = has_bias ? 1.f : 0.f;
     const int npl = 1 + (C1 != R ? 1 : 0) + (C2 != 255 ? 1 : 0);
     float s;
-    if (npl == 3) s = gram_unit_ring<3>(A, G, T, d_in, d_out, R, C1, C2, bias_term, ring);
-    else if (npl == 2) s = gram_unit_ring<2>(A, G, T, d_in, d_out, R, C1, C2, bias_term, ring);
-    else s = gram_unit_ring<1>(A, G, T, d_in, d_out, R, C1, C2, bias_term, ring);
+    if (blk) s = gram_unit_ring<2, true>(A, G, T, d_in, d_out, R, C1, C2, bias_term, ring);
+    else if (npl == 3) s = gram_unit_ring<3, false>(A, G, T, d_in, d_out, R, C1, C2, bias_term, ring);
+    else if (npl == 2) s = gram_unit_ring<2, false>(A, G, T, d_in, d_out, R, C1, C2, bias_term, ring);
+    else s = gram_unit_ring<1, false>(A, G, T, d_in, d_out, R, C1, C2, bias_term, ring);
     __syncthreads();  // the ring is free: its first floats serve the reduction
     const float tot = dp_block_sum<512>(s, reinterpret_cast<float*>(&ring[0]));
     if (threadIdx.x == 0) out[((size_t)i * gb.n_layers + layer) * gu.n_units + unit] = tot;
@@ -834,28 +875,24 @@ static dp_status gram_dma_launch(dp_ctx* ctx, const GramBatch& gb, int T, int d_
     return DP_OK;
 }
 
-// The upper triangle of an nblk x nblk plane of 128 x 128 cells, paired into units of two cells that share a panel:
-// along each row tb the cells (tb, tb), (tb, tb+1) | (tb, tb+2), (tb, tb+3) | ...; a row with an odd number of cells leaves
-// its last one, (tb, nblk-1), over, and two such leftovers share the panel nblk-1: by symmetry they are the cells
-// (nblk-1, tb1), (nblk-1, tb2) of the row panel nblk-1.  At most one cell stays alone.
+// The upper triangle of an nblk x nblk plane of 128 x 128 cells, cut into units.  Panels go two by two: the pair (2I, 2I+1)
+// gives the diagonal block (2I, 2I), (2I, 2I+1), (2I+1, 2I+1); two pairs I < J give the four cells of rows 2I, 2I+1 and
+// columns 2J, 2J+1, i.e. two row pairs.  With an odd nblk the last panel has no partner: its diagonal cell leads the row
+// pair (last, last), (last, 0) - by symmetry (last, r) stands for the cell (r, last) - the cells (r, last) of the other
+// rows pair up through the shared panel, (last, r1), (last, r2), and one of them stays alone.
 static GramUnits gram_make_units(int nblk) {
     GramUnits gu;
-    int n = 0, left[GU_MAX_BLK], nleft = 0;
-    for (int tb = 0; tb < nblk; ++tb) {
-        int j = tb;
-        for (; j + 1 < nblk; j += 2) {
-            gu.rc[n++] = (uint32_t)tb | (uint32_t)j << 8 | (uint32_t)(j + 1) << 16;
-        }
-        if (j == nblk - 1) left[nleft++] = tb;
-    }
-    const int last = nblk - 1;
-    int k = nleft;
-    while (k >= 2) {  // the largest leftover may be the diagonal cell (last, last): it leads its unit
-        const int t2 = left[--k], t1 = left[--k];
-        gu.rc[n++] = (uint32_t)last | (uint32_t)(t2 == last ? last : t1) << 8 | (uint32_t)(t2 == last ? t1 : t2) << 16;
-    }
-    if (k == 1) {
-        gu.rc[n++] = (uint32_t)left[0] | (uint32_t)last << 8 | 255u << 16;
+    int n = 0;
+    const int npair = nblk / 2, last = nblk - 1;
+    for (int I = 0; I < npair; ++I) gu.rc[n++] = (uint32_t)(2 * I) | (uint32_t)(2 * I) << 8 | (uint32_t)(2 * I + 1) << 16 | 1u << 24;
+    for (int I = 0; I < npair; ++I)
+        for (int J = I + 1; J < npair; ++J)
+            for (int r = 2 * I; r < 2 * I + 2; ++r) gu.rc[n++] = (uint32_t)r | (uint32_t)(2 * J) << 8 | (uint32_t)(2 * J + 1) << 16;
+    if (nblk & 1) {
+        gu.rc[n++] = (uint32_t)last | (uint32_t)last << 8 | (last > 0 ? 0u : 255u) << 16;
+        int r = 1;
+        for (; r + 1 < last; r += 2) gu.rc[n++] = (uint32_t)last | (uint32_t)r << 8 | (uint32_t)(r + 1) << 16;
+        if (r < last) gu.rc[n++] = (uint32_t)r | (uint32_t)last << 8 | 255u << 16;
     }
     gu.n_units = n;
     return gu;

@@ -217,20 +217,20 @@ DENSE_SHAPES = [
     ("bf16", 3, 100, 72, 136),    # ragged T and widths
     ("bf16", 2, 16, 64, 64),      # T far below one block
     ("bf16", 9, 300, 264, 128),   # 3 x 3 Gram blocks with a ragged last block, 9 examples over 8 XCD lanes
-    ("bf16", 2, 512, 128, 1024),  # 4 x 4 Gram blocks
+    ("bf16", 2, 512, 128, 1024),  # 4 x 4 Gram cells: two diagonal blocks and two row pairs
     ("bf16", 1, 1, 8, 8),         # T = 1
-    ("bf16", 3, 300, 128, 192),   # 3 x 3 blocks, ragged last block, widths the ring-fed unit kernel takes
+    ("bf16", 3, 300, 128, 192),   # 3 x 3 cells, ragged last one: a diagonal block, the last diagonal cell leading a row pair, a lone cell
     ("bf16", 2, 129, 64, 64),     # one row into the second block
-    ("bf16", 11, 256, 320, 64),   # 2 x 2 blocks, 11 examples over the 8 XCD lanes
+    ("bf16", 11, 256, 320, 64),   # 2 x 2 cells = one diagonal block per example, 11 examples over the 8 XCD lanes
     ("bf16", 4, 20, 1032, 72),    # T <= 32: the one-tile kernel, widths that end inside a 128-column chunk
     ("bf16", 3, 32, 520, 256),    # T = 32 exactly
     ("bf16", 2, 33, 128, 64),     # one row more: back to the 128-row kernels
     ("bf16", 5, 20, 1984, 192),   # T <= 32, widths multiples of 64: the ring-fed one-tile kernel, more stages than the ring holds
     ("bf16", 3, 32, 64, 128),     # ... and fewer
     ("bf16", 2, 640, 64, 128),    # 5 x 5 Gram cells: units of every kind, among them an off-diagonal cell on its own
-    ("bf16", 9, 1100, 64, 64),    # 9 x 9 cells with a ragged last one: units formed from the rows' leftover cells
+    ("bf16", 9, 1100, 64, 64),    # 9 x 9 cells with a ragged last one: the cells of the unpaired last panel form row pairs of their own
     ("bf16", 1, 2100, 64, 64),    # 17 x 17 cells: past the unit kernel's table, the register-staged kernel's block pairs
-    ("bf16", 2, 2048, 64, 128),   # 16 x 16 cells: the unit kernel's largest plane (68 units, its table full)
+    ("bf16", 2, 2048, 64, 128),   # 16 x 16 cells: the unit kernel's largest plane (8 diagonal blocks + 56 row pairs)
 ]
 
 
