@@ -378,7 +378,7 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gram_dma_kernel(GramBatch gb,
 // T > 128, widths multiples of 64: the panels of a 64-wide contraction chunk go straight into an LDS ring (no staging
 // registers, no LDS store instructions), as in the kernel above.  At this size the contraction, not HBM, is the bound on
 // paper (T flop per byte against ~310 at the machine balance); in practice it is the path that fills the LDS (a CU takes
-// about 46 bytes per clock from L2 this way, and a panel costs 16 KiB per stage) together with the matrix pipe.  A
+// about 120 GB/s from L2 this way, and a panel costs 16 KiB per stage) together with the matrix pipe.  A
 // workgroup of 8 waves (two per SIMD, one workgroup per CU) works on a UNIT of cells of the example's T x T plane, cut into
 // 128 x 128 cells of which only the upper triangle is formed (by symmetry a cell (R, C) with C < R stands for (C, R)):
 //  * a DIAGONAL BLOCK: the three cells (a, a), (a, b), (b, b) of two neighbouring panels a, b = a + 1 - two panel fills
