@@ -280,6 +280,14 @@ dp_status dp_philox_u32(dp_ctx* ctx, uint32_t* out, uint64_t n, uint64_t elem_of
 dp_status dp_normal_f32(dp_ctx* ctx, float* out, uint64_t n, uint64_t elem_offset, uint64_t seed, uint64_t step);
 /* Host-only, pure: the path DP_PATH_AUTO takes for this shape (HOST pointer out). */
 dp_status dp_choose_path(int T, int d_in, int d_out, dp_dtype dtype, dp_path* out);
+/* Host-only, pure: how the Gram path cuts the T x T plane of an example (128 < T <= 2048) into the units its workgroups
+ * take.  The plane is nblk x nblk cells of 128 x 128, nblk = ceil(T / 128); only cells (r, c) with r <= c are formed.
+ * Writes one word per unit to the HOST array `units` (capacity words) and their number to *n_units:
+ *   bit 24 set:   a diagonal block of the panels a = bits 0-7 and b = bits 16-23: cells (a, a), (a, b), (b, b);
+ *   bit 24 clear: a row pair, R = bits 0-7, C1 = bits 8-15, C2 = bits 16-23: cells (R, C1) and (R, C2), where (x, y) with
+ *                 x > y stands for (y, x); C2 == 255: the cell (R, C1) alone.
+ * DP_ERR_SHAPE if T is outside (128, 2048], DP_ERR_WORKSPACE if capacity is too small (70 words always suffice). */
+dp_status dp_gram_unit_plan(int T, uint32_t* units, int capacity, int* n_units);
 
 
 /* ---------------------------------------------------------------------------------------------------

@@ -59,6 +59,7 @@ SIGNATURES = {
     "dp_philox_u32": [c_void_p, c_void_p, c_uint64, c_uint64, c_uint64, c_uint64],
     "dp_normal_f32": [c_void_p, c_void_p, c_uint64, c_uint64, c_uint64, c_uint64],
     "dp_choose_path": [c_int, c_int, c_int, c_int, ctypes.POINTER(c_int)],
+    "dp_gram_unit_plan": [c_int, ctypes.POINTER(ctypes.c_uint32), c_int, ctypes.POINTER(c_int)],
     "dp_batch_size_schedule": [c_uint64, c_uint64, c_uint64, c_uint64, ctypes.c_uint32, ctypes.POINTER(c_uint64)],
     "dp_lr_schedule": [c_uint64, ctypes.c_double, c_uint64, c_uint64, ctypes.POINTER(ctypes.c_double)],
     "dp_rdp_sampled_gaussian": [ctypes.c_double, ctypes.c_double, c_int, ctypes.POINTER(ctypes.c_double)],
@@ -453,6 +454,16 @@ def dp_choose_path(T, d_in, d_out, dtype=DP_BF16) -> int:
     if st != DP_OK:
         raise DpError(st, "dp_choose_path")
     return out.value
+
+
+def dp_gram_unit_plan(T) -> list:
+    """The unit words of dp_gram_unit_plan for sequence length T (host only)."""
+    buf = (ctypes.c_uint32 * 70)()
+    n = c_int()
+    st = load_library().dp_gram_unit_plan(T, buf, 70, ctypes.byref(n))
+    if st != DP_OK:
+        raise DpError(st, "dp_gram_unit_plan")
+    return [int(buf[k]) for k in range(n.value)]
 
 
 def dp_profile_enable(ctx, enable: bool):

@@ -190,6 +190,12 @@ const char* dp_status_str(dp_status s) {
 
 const char* dp_last_error(const dp_ctx* ctx) { return ctx ? ctx->msg : "no context"; }
 
+dp_status dp_gram_unit_plan(int T, uint32_t* units, int capacity, int* n_units) {
+    if (!units || !n_units) return DP_ERR_NULL;
+    if (capacity < 0) return DP_ERR_SHAPE;
+    return dpk_gram_unit_plan(T, units, capacity, n_units);
+}
+
 dp_status dp_choose_path(int T, int d_in, int d_out, dp_dtype dtype, dp_path* out) {
     if (!out) return DP_ERR_NULL;
     if (dtype != DP_F32 && dtype != DP_BF16) return DP_ERR_DTYPE;

@@ -176,6 +176,7 @@ dp_status dpk_noise_adamw_snr_static(hipStream_t stream, float* params, float* m
                                      uint64_t off, float sigma, float C, uint64_t seed, uint64_t step, uint64_t batch,
                                      float lr, float b1, float b2, float eps, float wd, int zero_sum, float* sq_out);
 
+dp_status dpk_gram_unit_plan(int T, uint32_t* units, int capacity, int* n_units);
 dp_status dpk_gram_sqnorms_batched(dp_ctx*, int n_layers, const void* const* A, const void* const* G, dp_dtype, int B, int T,
                                    int d_in, int d_out, int has_bias, float* sqnorms);
 dp_status dpk_gram_sqnorms_shared(dp_ctx*, int n_groups, const void* const* A, int n_out, const void* const* G, dp_dtype, int B,

@@ -904,6 +904,15 @@ static bool gram_units_ok(int T, int d_in, int d_out) {
            (size_t)T * (d_in > d_out ? d_in : d_out) * 2 < (1u << 31);
 }
 
+dp_status dpk_gram_unit_plan(int T, uint32_t* units, int capacity, int* n_units) {
+    if (T <= GB || T > GB * GU_MAX_BLK) return DP_ERR_SHAPE;
+    const GramUnits gu = gram_make_units((T + GB - 1) / GB);
+    if (gu.n_units > capacity) return DP_ERR_WORKSPACE;
+    for (int k = 0; k < gu.n_units; ++k) units[k] = gu.rc[k];
+    *n_units = gu.n_units;
+    return DP_OK;
+}
+
 // nl <= GRAM_MAX_BATCH same-shaped layers: partials [B][nl * n_units] through the workspace, added in index order.
 static dp_status gram_units_launch(dp_ctx* ctx, const GramBatch& gb, int T, int d_in, int d_out, int has_bias,
                                    float* sqnorms) {

@@ -66,6 +66,56 @@ def test_choose_path_rule(lib):
         pkg.dp_choose_path(1, 4, 4, 5)
 
 
+def _unit_cells(word):
+    """The cells (r, c), r <= c, of one unit word of dp_gram_unit_plan, and the panels it fills."""
+    a, b, c2, blk = word & 255, (word >> 8) & 255, (word >> 16) & 255, (word >> 24) & 1
+    if blk:
+        assert b == a and c2 == a + 1, hex(word)
+        return [(a, a), (a, c2), (c2, c2)], {a, c2}
+    cells = [tuple(sorted((a, b)))]
+    if c2 != 255:
+        cells.append(tuple(sorted((a, c2))))
+    return cells, {a, b} | ({c2} if c2 != 255 else set())
+
+
+@pytest.mark.parametrize("T", [129, 256, 300, 384, 512, 640, 768, 1024, 1100, 1920, 2048])
+def test_gram_unit_plan_covers_the_upper_triangle_once(lib, T):
+    import paper_2108_01624_amd as pkg
+
+    nblk = -(-T // 128)
+    words = pkg.dp_gram_unit_plan(T)
+    seen, fills = [], 0
+    for w in words:
+        cells, panels = _unit_cells(w)
+        assert all(0 <= r <= c < nblk for r, c in cells), (hex(w), nblk)
+        # what a workgroup's registers hold: a diagonal block, or at most two cells of which only the first may be diagonal
+        if not (w >> 24) & 1 and len(cells) == 2:
+            assert cells[1][0] != cells[1][1], hex(w)
+        assert len(panels) <= 3
+        seen += cells
+        fills += len(panels)
+    want = [(r, c) for r in range(nblk) for c in range(r, nblk)]
+    assert sorted(seen) == want                      # every cell of the triangle exactly once
+    assert sum(1 for w in words if (w >> 24) & 1) == nblk // 2   # every pair of neighbouring panels forms a diagonal block
+    assert sum(1 for w in words if not (w >> 24) & 1 and (w >> 16) & 255 == 255) <= 1  # at most one cell on its own
+    if T == 512:
+        assert len(words) == 4 and fills == 10
+    if T == 256:
+        assert len(words) == 1 and fills == 2
+
+
+def test_gram_unit_plan_rejects_other_lengths(lib):
+    import paper_2108_01624_amd as pkg
+
+    for T in (0, 1, 128, 2049, -5):
+        with pytest.raises(pkg.DpError):
+            pkg.dp_gram_unit_plan(T)
+    import ctypes
+    buf, n = (ctypes.c_uint32 * 2)(), ctypes.c_int()
+    assert lib.dp_gram_unit_plan(512, buf, 2, ctypes.byref(n)) == -7   # 4 units do not fit 2 words
+    assert lib.dp_gram_unit_plan(512, None, 2, ctypes.byref(n)) == -1
+
+
 def test_null_context_is_rejected_without_a_gpu(lib):
     assert lib.dp_sync(None) == -1
     assert lib.dp_destroy(None) == -1
