@@ -33,6 +33,10 @@
  *   - Calls are asynchronous on the context's stream and return argument and launch errors at once.
  *     Errors found on the device (a token id outside [0, V)) are returned by the next dp_sync.
  *   - Results are deterministic: the same call sequence on the same inputs gives the same bits.
+ *   - The step's entry points (norms, clip factors, clip-weighted sums, the update, dp_zero_f32) only launch kernels
+ *     on the context's stream: no allocation, no memory-set or copy command, no wait for the device.  A caller may
+ *     therefore record them into a HIP graph on that stream (profiling off) and replay it; replays give the bits of
+ *     the eager calls.  dp_create, dp_destroy, dp_sync and the dp_profile_* calls do wait and must stay outside.
  *   - No entry point prints, throws or exits.  A context must be used by one host thread at a time.
  */
 #ifndef DPCLIP_H
