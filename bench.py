@@ -54,6 +54,33 @@ def parse():
     return ap.parse_args()
 
 
+def vendor_tn_gemm(layers):
+    """Calibration only: the vendor GEMM library, through torch.matmul, on the contraction A^T G of every dense layer of
+    the workload (token rows are the slow index of both operands, as for the clip-weighted GEMM)."""
+    import torch
+
+    dense = [l for l in layers if l["kind"] == "dense" and l["A"].dtype == torch.bfloat16]
+    if not dense:
+        return None
+    ops, flops = [], 0.0
+    for l in dense:
+        K = l["A"].shape[0] * l["A"].shape[1]
+        ops.append((l["A"].view(K, -1).t(), l["G"].view(K, -1)))
+        flops += 2.0 * K * l["A"].shape[-1] * l["G"].shape[-1]
+    outs = {}
+    for a, g in ops:
+        outs.setdefault((a.shape[0], g.shape[1]), torch.empty(a.shape[0], g.shape[1], dtype=torch.bfloat16, device=a.device))
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for rep in range(3):  # the first sweep warms the library up
+        if rep == 1:
+            e0.record()
+        for a, g in ops:
+            torch.matmul(a, g, out=outs[(a.shape[0], g.shape[1])])
+    e1.record()
+    torch.cuda.synchronize()
+    return 2 * flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+
 def cpu_baseline(layers, cfg, n_examples, upd, n_update_elems, P):
     """Time the oracle, as it stands, on a bounded sample of the workload: norms + clip + sum of the first n_examples
     examples over the full manifest, and the noise + Adam update on the first n_update_elems flat parameters."""
@@ -205,6 +232,7 @@ def main():
     # this card, right after the workload (same thermal state).
     a28_ms = a28_n = a28_bytes = 0
     mfma_ceiling = None
+    vendor_tn = None
     if not args.no_calibration:
         for k in range(5):
             run.update(sigma=upd["sigma"], C=cfg["C"], seed=upd["noise_seed"], step=args.warmup + args.steps + 1 + k,
@@ -213,6 +241,7 @@ def main():
         a28_ms, a28_n, a28_bytes = ctx.profile_read(pkg.DP_PROF_ADAMW)
         ctx.profile_enable(False)
         mfma_ceiling = ctx.profile_mfma_ceiling(8192, 8)
+        vendor_tn = vendor_tn_gemm(layers)
     ctx.profile_enable(False)
 
     achieved = g_flops / (g_ms * 1e-3) / 1e12 if g_ms > 0 else 0.0
@@ -256,7 +285,12 @@ def main():
                      "sustained_mfma_only_note": "TFLOP/s of a register-only loop of the same bf16 16x16x32 matrix "
                                                  "instructions (random operands, 8 waves per CU), measured in this run "
                                                  "after the timed region: the card's power limit, not the nominal peak",
-                     "frac_of_sustained": (achieved / mfma_ceiling) if mfma_ceiling else None},
+                     "frac_of_sustained": (achieved / mfma_ceiling) if mfma_ceiling else None,
+                     "vendor_tn_gemm": vendor_tn,
+                     "vendor_tn_gemm_note": "TFLOP/s of the vendor GEMM library (torch.matmul) on the same contractions A^T G "
+                                            "of this run's dense layers - same operands and layout, bf16 result, no clip "
+                                            "factors, no accumulation into an fp32 sum - timed after the timed region: a "
+                                            "reference for the kernel, not part of the path"},
         "kernels": {
             "gram_sqnorms": {"bound": "hbm", "achieved_GBps": n_bytes / (n_ms * 1e-3) / 1e9 if n_ms else 0.0,
                              "frac": n_bytes / (n_ms * 1e-3) / 1e9 / PEAK_HBM_GBS if n_ms else 0.0,
