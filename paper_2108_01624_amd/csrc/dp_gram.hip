@@ -392,14 +392,14 @@ __global__ __launch_bounds__(256, WGS_PER_CU) void gram_dma_kernel(GramBatch gb,
 //    lower-left quadrant and the mirrored tiles of its diagonal quadrants.
 // Over the upper triangle of a 4 x 4 plane that is 2 blocks and 2 row pairs: 10 panel fills and 4 workgroups where a
 // workgroup per cell needs 16 and 10.  A ring that uses all of the LDS for stages in flight (three stages of 48 KiB
-// for three panels, four of 32 KiB for two) covers the latency of the fills: every panel comes from HBM once, the units
+// for three panels, five of 32 KiB for two) covers the latency of the fills: every panel comes from HBM once, the units
 // of an example share it through L2.
 // ------------------------------------------------------------------------------------------------
 constexpr int GU_K = 64;         // contraction chunk per stage
-constexpr int GU_LDS = 3 * 3 * GB * GU_K;  // bf16 elements of the ring: 144 KiB
+constexpr int GU_LDS = 5 * 2 * GB * GU_K;  // bf16 elements of the ring: 160 KiB, all of a CU's LDS
 // Ring stages by the number of panels a stage holds (48, 32 or 16 KiB a stage): a fill that misses L2 takes a few
 // microseconds, so a unit with fewer panels per stage runs further ahead.
-__host__ __device__ constexpr int gu_stages(int npl) { return npl == 3 ? 3 : (npl == 2 ? 4 : 8); }
+__host__ __device__ constexpr int gu_stages(int npl) { return npl == 3 ? 3 : (npl == 2 ? 5 : 10); }
 constexpr int GU_MAX_BLK = 16;   // T <= 2048
 constexpr int GU_MAX_UNITS = GU_MAX_BLK * (GU_MAX_BLK + 1) / 4 + 1;
 struct GramUnits {
